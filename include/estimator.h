@@ -1,0 +1,165 @@
+/*
+ * Batched Estimator for prediction-pipeline configurations -- C ABI.
+ *
+ * The Estimator (arXiv 1812.01776, Section 4.2) is a discrete-event simulation that replays a
+ * sample query trace through a pipeline DAG (Section 2) under one candidate configuration --
+ * per stage a hardware type, a maximum batch size and a replica count (Section 4.1, "an
+ * individual model configuration") -- and yields the latency of every query.  The planner
+ * (Section 4.3, Algorithms 1 and 2) calls it for every candidate it considers and keeps a
+ * candidate only if 99% of the latencies are within the SLO (Section 2), preferring the
+ * cheapest (Section 6, cost model).  This library evaluates many candidates against the same
+ * trace in one call, on one AMD MI355X GPU (gfx950).
+ *
+ * Queueing model (Section 2.1 "maximum batch size", Section 3 "centralized batched queueing
+ * system", Section 4.2): each stage has one FIFO queue ordered by (time the query became ready
+ * at the stage, query index).  Whenever a replica of the stage is idle and the queue is not
+ * empty, the replica takes the first min(max batch, queue length) queries at once; the whole
+ * batch completes together after the profiled latency of a batch of that actual size.  A stage
+ * with several parents becomes ready for a query at the maximum of the parents' completion
+ * times; a query whose visit-mask bit for a stage is clear passes through that stage in zero
+ * time (Section 4.1, scale factor); end-to-end completion is the maximum over sink stages.
+ * All times are integer microseconds and saturate at EST_HORIZON_US.
+ *
+ * Conventions for every function:
+ *   - returns EST_OK (0) or a negative error code; never aborts, never throws;
+ *   - the caller owns every buffer it passes; nothing is retained after return except by
+ *     estimator_create, which deep-copies the DAG and the profiles;
+ *   - outputs are untouched when an error is returned;
+ *   - a handle must not be used by two threads at once.
+ */
+#ifndef ESTIMATOR_H
+#define ESTIMATOR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EST_OK 0
+#define EST_EINVAL (-1)       /* bad argument, malformed DAG / profile / trace / configuration      */
+#define EST_ENOMEM (-2)       /* host or device allocation failed, or workspace too small           */
+#define EST_EDEVICE (-3)      /* HIP runtime error; text in estimator_last_error                    */
+#define EST_EUNSUPPORTED (-4) /* valid input the implementation cannot handle (see est limits)      */
+#define EST_EINTERNAL (-5)    /* the simulation kernel reported an inconsistency                    */
+
+#define EST_MAX_STAGES 32
+#define EST_MAX_BATCH 64
+#define EST_MAX_REPLICAS 64
+#define EST_MAX_MERGE_SOURCES 8 /* most distinct nearest visited ancestors feeding one stage        */
+#define EST_HORIZON_US 0xFFFFFFFFu /* every computed time is min(true time, horizon)                */
+
+typedef struct estimator estimator_t; /* opaque; immutable after estimator_create */
+
+/* Pipeline DAG (Section 2): stages are numbered in a topological order. */
+typedef struct {
+    uint32_t n_stages;          /* S, 1..EST_MAX_STAGES                                              */
+    const uint32_t *parent_off; /* [S+1] CSR offsets into parent_idx, parent_off[0] == 0             */
+    const uint32_t *parent_idx; /* parents of each stage; every parent index < the child's index     */
+} est_dag_t;
+
+/* Model profiles (Section 4.1): latency of one replica as a function of hardware and batch size. */
+typedef struct {
+    uint32_t n_hw;                /* H >= 1 hardware types                                            */
+    uint32_t max_batch;           /* Bmax, 1..EST_MAX_BATCH                                           */
+    const uint32_t *lat_us;       /* [S][H][Bmax]; entry b-1 = latency of a batch of b queries, > 0   */
+    const uint64_t *cost_uusd_hr; /* [S][H] price of one replica, micro-dollars per hour             */
+} est_profiles_t;
+
+/* Sample trace (Section 4.2). */
+typedef struct {
+    uint64_t n;                 /* number of queries, < 2^31                                          */
+    const uint32_t *arrival_us; /* [n] arrival times, non-decreasing                                  */
+    const uint32_t *visit_mask; /* [n] bit s set = the query visits stage s                           */
+} est_trace_t;
+
+/* One stage of one candidate configuration; a candidate is S consecutive entries. */
+typedef struct {
+    uint8_t hw;        /* < H                         */
+    uint8_t batch;     /* maximum batch size, 1..Bmax */
+    uint16_t replicas; /* 1..EST_MAX_REPLICAS         */
+} est_stage_cfg_t;
+
+/* Per-candidate results, each array [n_cfg]. */
+typedef struct {
+    uint32_t *p99_us;       /* nearest-rank P99: the ceil(0.99 n)-th smallest latency; 0 if n == 0   */
+    uint32_t *miss_count;   /* number of queries with latency > slo_us                               */
+    uint64_t *cost_uusd_hr; /* sum over stages of replicas x price                                   */
+} est_result_t;
+
+/* Timing of the most recent run, measured with HIP events on the run's stream. */
+typedef struct {
+    uint32_t n_tiles;         /* kernel launches of the simulation kernel (one per tile of candidates) */
+    uint32_t tile_configs;    /* candidates per full tile                                             */
+    float sim_ms;             /* summed duration of the simulation kernel launches                    */
+    float select_ms;          /* summed duration of the P99 selection kernel launches                 */
+    float prep_ms;            /* trace / configuration preprocessing kernels                          */
+    uint64_t stage_visits;    /* sum over stages of queries visiting the stage (per candidate)        */
+    uint64_t workspace_bytes; /* device scratch used                                                  */
+} est_stats_t;
+
+/*
+ * Build a handle for one pipeline and its profiles (host pointers; deep-copied to host and device).
+ * Errors: EST_EINVAL for NULLs, S out of range, a parent index >= its child, duplicate parents,
+ * H == 0, Bmax out of range, or any latency entry equal to 0; EST_EDEVICE if no usable GPU.
+ */
+int estimator_create(const est_dag_t *dag, const est_profiles_t *profiles, estimator_t **out);
+
+/*
+ * Simulate n_cfg candidates against one trace.  ALL POINTERS ARE HOST POINTERS; inputs are
+ * copied to the GPU, results copied back; the call returns when the results are in place.
+ * configs is [n_cfg][S].  n_cfg == 0 or trace->n == 0 succeeds (p99 = 0, miss_count = 0).
+ * Errors: EST_EINVAL for NULLs, non-monotone arrivals, a configuration entry out of range, or a
+ * trace whose last arrival + sum over stages of the largest profiled latency + slo_us reaches
+ * the horizon; EST_EUNSUPPORTED if a stage would need more than EST_MAX_MERGE_SOURCES input
+ * streams; EST_ENOMEM; EST_EDEVICE.
+ */
+int estimator_run(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *configs,
+                  uint64_t n_cfg, uint32_t slo_us, est_result_t *out);
+
+/*
+ * The same with every array already in GPU memory: trace->arrival_us, trace->visit_mask,
+ * configs and the three arrays of out are DEVICE pointers (the structs themselves live on the
+ * host).  workspace is a device scratch buffer of workspace_bytes bytes owned by the caller, or
+ * NULL to let the library allocate (and cache in the handle) what it needs; with a caller
+ * workspace the candidates are processed in as many tiles as fit.  hip_stream is a hipStream_t
+ * (NULL = the default stream); all work is enqueued on it and the call returns after that work
+ * has completed.  Same errors as estimator_run; EST_ENOMEM if the workspace cannot hold one
+ * candidate.
+ */
+int estimator_run_dev(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *configs,
+                      uint64_t n_cfg, uint32_t slo_us, est_result_t *out, void *workspace,
+                      uint64_t workspace_bytes, void *hip_stream);
+
+/*
+ * Per-query latencies (Section 4.2: the Estimator returns the latency of each query), for
+ * checking: lat_us_out is [n_cfg][n], host memory, indexed by query.  Host pointers throughout.
+ */
+int estimator_run_latencies(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *configs,
+                            uint64_t n_cfg, uint32_t *lat_us_out);
+
+/* Device-pointer variant of estimator_run_latencies; lat_us_out is a device buffer [n_cfg][n]. */
+int estimator_run_latencies_dev(estimator_t *h, const est_trace_t *trace,
+                                const est_stage_cfg_t *configs, uint64_t n_cfg, uint32_t *lat_us_out,
+                                void *workspace, uint64_t workspace_bytes, void *hip_stream);
+
+/*
+ * Device scratch, in bytes, that lets estimator_run_dev process n_cfg candidates of an n-query
+ * trace in a single tile (an upper bound: it assumes every stage forks).  Smaller workspaces work
+ * with more tiles.  Returns 0 on a NULL handle.
+ */
+uint64_t estimator_workspace_bytes(const estimator_t *h, uint64_t n, uint64_t n_cfg);
+
+/* Fill *out with the timing of the last successful run on this handle. */
+int estimator_last_stats(const estimator_t *h, est_stats_t *out);
+
+/* Text of the last error on this handle ("" if none); valid until the next call on the handle. */
+const char *estimator_last_error(const estimator_t *h);
+
+/* Free the handle and everything it owns; estimator_destroy(NULL) is a no-op. */
+void estimator_destroy(estimator_t *h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ESTIMATOR_H */

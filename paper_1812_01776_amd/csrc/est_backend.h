@@ -1,0 +1,33 @@
+// Device-side services the host planner needs: memory, copies, kernel launches, events.
+// Implemented for the GPU in est_kernels.hip.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+#include "est_types.h"
+
+namespace estbe {
+
+int init();                       // 0, or non-zero with last_error() set when no usable GPU is present
+const char *last_error();
+void *dmalloc(size_t bytes);      // nullptr on failure
+void dfree(void *p);
+size_t mem_free();                // free device memory in bytes
+int h2d(void *dst, const void *src, size_t bytes, void *stream);
+int d2h(void *dst, const void *src, size_t bytes, void *stream);
+int d2d(void *dst, const void *src, size_t bytes, void *stream);
+int zero(void *dst, size_t bytes, void *stream);
+int sync(void *stream);
+
+int launch_cfg(const EstCfgArgs &a, void *stream);
+int launch_prep1(const EstPrepArgs &a, void *stream);
+int launch_prep2(const EstPrepArgs &a, void *stream);
+int launch_sim(const EstSimArgs &a, void *stream);
+int launch_select(const EstSelectArgs &a, void *stream);
+
+void *event_create();
+void event_destroy(void *ev);
+int event_record(void *ev, void *stream);
+float event_ms(void *start, void *stop);  // both must have completed
+
+}  // namespace estbe

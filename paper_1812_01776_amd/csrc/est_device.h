@@ -1,0 +1,633 @@
+// Device code of the batched Estimator: one 64-lane wavefront simulates one candidate
+// configuration end to end.  Written against the wv:: primitives only, so that the same text
+// also compiles for a lock-step CPU emulation used by the host-side checks of the kernel logic.
+//
+// The simulated system is the centralized batched queue of arXiv 1812.01776 (Section 3, serving
+// system requirements; Section 2.1, maximum batch size; Section 4.2, event order).  Because
+// queues are unbounded and the DAG is feed-forward, a stage depends only on its own input
+// stream ordered by (ready time, query index); the global event order of Section 4.2 is
+// reproduced by running every stage over its ordered stream:
+//
+//   SCAN   one stage.  Walk the stage's input stream; a batch starts at T = max(earliest replica
+//          free time, ready time of the first waiting query), takes every waiting query with
+//          ready <= T up to the maximum batch size, and completes at T + L(actual size)
+//          (Section 4.2: latency from the profile for a batch of the given size; Section 2.1: the
+//          whole batch returns together).  Completed batches are emitted to the output stream in
+//          (completion time, query index) order.
+//   MERGE  builds a stage's input stream from the output streams of the query's nearest visited
+//          ancestors: a query that skips a stage passes through it in zero time (Section 4.1,
+//          scale factor / conditional control flow) and a stage with several parents is ready at
+//          the maximum of their completions.
+//   LAT    a MERGE into the virtual sink: latency = completion - arrival (Section 4.2), and the
+//          SLO miss count (Section 2: latencies must be below the constraint).
+//
+// Streams are per-candidate rings of 64-bit keys (time << 32 | query index) in global memory,
+// so that comparing keys compares (time, query index).  All operations of a candidate are run
+// round-robin by its wavefront until every stream is drained; an operation stops when it needs
+// input that is not there yet or output space that is not free yet.
+#pragma once
+#include "est_types.h"
+
+namespace estdev {
+
+EST_DEV uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
+EST_DEV uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+EST_DEV uint32_t popc64(uint64_t x) { return (uint32_t)__builtin_popcountll(x); }
+EST_DEV uint32_t ctz64(uint64_t x) { return (uint32_t)__builtin_ctzll(x); }
+EST_DEV uint64_t lanes_below(uint32_t l) { return l >= 64 ? ~0ull : ((1ull << l) - 1ull); }
+
+// Saturating clock: every computed time is min(true time, horizon = 2^32 - 1).
+EST_DEV uint32_t sat_add(uint32_t t, uint32_t d) {
+    uint32_t e = t + d;
+    return e < t ? 0xFFFFFFFFu : e;
+}
+
+// LDS of one wavefront, in 8-byte words, for a plan whose widest merge has k sources:
+// staged keys uint64 [k][64] | merged run uint64 [k*64] | staged positions uint32 [k][64].
+// Size: EST_LDS_WORDS64(k).
+
+struct Ctx {
+    const EstSimArgs *a;
+    const EstPlan *P;
+    uint32_t *st;
+    uint64_t *rings;
+    uint32_t *rep;
+    uint32_t *slots;
+    uint8_t *cnt;
+    uint32_t *lat;
+    const EstStageCfg *cfg;
+    uint64_t *lds;
+};
+
+struct View {
+    const uint64_t *base;
+    uint32_t mask, wr, fin;
+};
+
+EST_DEV View view_of(const Ctx &c, int32_t ring) {
+    View v;
+    if (ring == EST_SRC_TRACE) {
+        v.base = c.a->trace_keys;
+        v.mask = 0xFFFFFFFFu;
+        v.wr = c.a->n;
+        v.fin = 1;
+    } else {
+        const EstRing &R = c.P->rings[ring];
+        v.base = c.rings + R.off;
+        v.mask = R.cap_mask;
+        v.wr = c.st[c.P->wr_off + ring];
+        v.fin = c.st[c.P->fin_off + ring];
+    }
+    return v;
+}
+
+// Free elements of a ring: capacity minus the distance to its slowest consumer.
+EST_DEV uint32_t ring_space(const Ctx &c, int32_t ring, uint32_t wr) {
+    const EstRing &R = c.P->rings[ring];
+    uint32_t used = 0;
+    for (uint32_t i = 0; i < R.n_cons; ++i) used = umax(used, wr - c.st[c.P->rd_off + R.cons_edge[i]]);
+    EST_CHECK(used <= R.cap_mask + 1u);
+    return R.cap_mask + 1u - used;
+}
+
+// Ascending bitonic sort of one value per lane.
+EST_DEV uint32_t sort64(uint32_t v) {
+    const uint32_t ln = wv::lane();
+    for (uint32_t k = 2; k <= 64; k <<= 1)
+        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+            uint32_t o = wv::shfl(v, ln ^ j);
+            bool up = (ln & k) == 0;
+            bool lower = (ln & j) == 0;
+            uint32_t mn = umin(v, o), mx = umax(v, o);
+            v = (lower == up) ? mn : mx;
+        }
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------ SCAN
+
+// Emit, in (completion time, query index) order, the batches whose replica-table lanes are in E.
+// Members of a batch wait, sorted by query index, in the replica's slot.  Batches that complete
+// at the same time are merged by query index.  Stops early (returns false) when the output ring
+// cannot take the next group.
+EST_DEV bool scan_emit(const Ctx &c, const EstOp &op, uint64_t E, uint32_t rend, uint32_t &rcnt,
+                       uint64_t *out, uint32_t omask, uint32_t &wr, uint32_t &space, bool &progress) {
+    const uint32_t ln = wv::lane();
+    const uint32_t *slots = c.slots + op.slot_off;
+    while (E) {
+        bool inE = (E >> ln) & 1ull;
+        uint32_t mv = wv::min_u32(inE ? rend : 0xFFFFFFFFu);
+        uint64_t tie = wv::ballot(inE && rend == mv);
+        uint32_t total = wv::sum_u32(((tie >> ln) & 1ull) ? rcnt : 0u);
+        if (total > space) return false;
+        const uint64_t tkey = (uint64_t)mv << 32;
+        if (popc64(tie) == 1 || mv == 0xFFFFFFFFu) {
+            // one batch, or batches clamped at the horizon (their relative order cannot matter:
+            // everything downstream of a clamped time is clamped too): concatenate
+            uint32_t base = wr;
+            for (uint64_t m = tie; m; m &= m - 1) {
+                uint32_t r = ctz64(m);
+                uint32_t cr = wv::bcast(rcnt, r);
+                EST_CHECK(cr >= 1 && cr <= op.b_max);
+                if (ln < cr) out[(base + ln) & omask] = tkey | slots[(uint64_t)r * op.b_max + ln];
+                base += cr;
+            }
+        } else {
+            // several batches complete together: rank every member among all of them
+            for (uint64_t m = tie; m; m &= m - 1) {
+                uint32_t r = ctz64(m);
+                uint32_t cr = wv::bcast(rcnt, r);
+                uint32_t x = ln < cr ? slots[(uint64_t)r * op.b_max + ln] : 0u;
+                uint32_t rank = ln;
+                for (uint64_t m2 = tie; m2; m2 &= m2 - 1) {
+                    uint32_t r2 = ctz64(m2);
+                    uint32_t c2 = wv::bcast(rcnt, r2);
+                    if (r2 == r || ln >= cr) continue;
+                    const uint32_t *s2 = slots + (uint64_t)r2 * op.b_max;
+                    uint32_t lo = 0, hi = c2;
+                    while (lo < hi) {
+                        uint32_t mid = (lo + hi) >> 1;
+                        if (s2[mid] < x) lo = mid + 1; else hi = mid;
+                    }
+                    rank += lo;
+                }
+                if (ln < cr) out[(wr + rank) & omask] = tkey | x;
+            }
+        }
+        wr += total;
+        space -= total;
+        if ((tie >> ln) & 1ull) rcnt = 0;
+        E &= ~tie;
+        progress = true;
+    }
+    return true;
+}
+
+EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
+    const uint32_t ln = wv::lane();
+    const EstPlan &P = *c.P;
+    const uint32_t s = op.stage;
+    const EstStageCfg sc = c.cfg[s];
+    const uint32_t B = sc.batch, R = sc.replicas;
+    EST_CHECK(B >= 1 && B <= op.b_max && R >= 1 && R <= op.r_max);
+    const uint32_t *Ltab = c.a->lat_us + ((uint64_t)s * c.a->dag->H + sc.hw) * c.a->dag->Bmax;
+    const uint32_t Lmine = ln < B ? Ltab[ln] : 0u;  // lane l holds L(l+1)
+    uint32_t *rep_end = c.rep + op.rep_off;
+    uint32_t *rep_cnt = rep_end + op.r_max;
+    // replica table: lane r < R holds replica r: when it is free again, and how many members of
+    // its last batch still wait to be emitted
+    uint32_t rend = ln < R ? rep_end[ln] : 0xFFFFFFFFu;
+    uint32_t rcnt = ln < R ? rep_cnt[ln] : 0u;
+    uint32_t *slots = c.slots + op.slot_off;
+    const View in = view_of(c, op.src_ring[0]);
+    uint32_t rd = c.st[P.rd_off + op.src_edge[0]];
+    const EstRing &OR = P.rings[op.out_ring];
+    uint64_t *out = c.rings + OR.off;
+    const uint32_t omask = OR.cap_mask;
+    uint32_t wr = c.st[P.wr_off + op.out_ring];
+    uint32_t space = ring_space(c, op.out_ring, wr);
+    bool progress = false, finished = false;
+
+    for (;;) {
+        const uint32_t avail = in.wr - rd;
+        if (avail == 0) {
+            if (in.fin) {  // input exhausted for good: flush what is still in flight
+                uint64_t E = wv::ballot(rcnt > 0);
+                if (!E || scan_emit(c, op, E, rend, rcnt, out, omask, wr, space, progress)) finished = true;
+            }
+            break;
+        }
+        const uint32_t w = umin(avail, 64u);
+        const uint64_t key = ln < w ? in.base[(rd + ln) & in.mask] : ~0ull;
+        const uint32_t rdy = (uint32_t)(key >> 32);
+        uint32_t q = (uint32_t)key;
+        const bool isrep = ln < R;
+        const uint32_t f = wv::min_u32(isrep ? rend : 0xFFFFFFFFu);  // earliest free replica
+        const uint32_t r0 = wv::bcast(rdy, 0);
+        const uint32_t T = umax(f, r0);  // dispatch time of the next batch
+        const uint64_t mm = wv::ballot(ln < umin(w, B) && rdy <= T);
+        const uint32_t b = popc64(mm);
+        EST_CHECK(b >= 1 && mm == lanes_below(b));
+        // The batch is known once it is full, or a later query is seen to be ready only after T,
+        // or no further input can come.
+        const bool decidable = (b == B) || (b < w) || (w == avail && in.fin);
+        if (!decidable) break;
+        // everything that completes by T leaves before this batch is dispatched
+        uint64_t E = wv::ballot(isrep && rcnt > 0 && rend <= T);
+        if (E && !scan_emit(c, op, E, rend, rcnt, out, omask, wr, space, progress)) break;
+        // members wait in the replica's slot sorted by query index
+        uint32_t prev = wv::shfl(q, ln - 1);
+        uint64_t uns = wv::ballot(ln > 0 && ln < b && q < prev);
+        if (uns) q = sort64(ln < b ? q : 0xFFFFFFFFu);
+        const uint32_t slot = ctz64(wv::ballot(isrep && rend == f));
+        EST_CHECK(slot < R);
+        if (ln < b) slots[(uint64_t)slot * op.b_max + ln] = q;
+        const uint32_t end = sat_add(T, wv::bcast(Lmine, b - 1));
+        if (ln == slot) {
+            EST_CHECK(rcnt == 0);
+            rend = end;
+            rcnt = b;
+        }
+        rd += b;
+        progress = true;
+        wv::sync();  // slot contents must be visible to a later emission
+    }
+
+    if (ln < R) {
+        rep_end[ln] = rend;
+        rep_cnt[ln] = rcnt;
+    }
+    if (ln == 0) {
+        c.st[P.rd_off + op.src_edge[0]] = rd;
+        c.st[P.wr_off + op.out_ring] = wr;
+        if (finished) {
+            c.st[P.fin_off + op.out_ring] = 1;
+            c.st[P.done_off + opi] = 1;
+        }
+    }
+    wv::sync();
+    return progress;
+}
+
+// ------------------------------------------------------------------------------------------ MERGE
+
+// Keys clamped at the horizon may appear in any order inside a stream (see scan_emit); for merging
+// they are ordered by (source, staging index) instead of by query index.
+EST_DEV uint64_t eff_key(uint64_t key, uint32_t j, uint32_t l) {
+    return (uint32_t)(key >> 32) == 0xFFFFFFFFu ? (0xFFFFFFFF00000000ull | (uint64_t)(j << 8) | l) : key;
+}
+
+EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
+    const uint32_t ln = wv::lane();
+    const EstPlan &P = *c.P;
+    const uint32_t K = op.n_src;
+    const bool is_lat = op.type == EST_OP_LAT;
+    const uint8_t *acc = c.a->acc + (uint64_t)op.acc_idx * c.a->acc_stride;
+    uint8_t *cnt = c.cnt + op.cnt_off;
+    uint64_t *skey = c.lds;
+    uint64_t *merged = c.lds + P.max_src * 64;
+    uint32_t *spos = (uint32_t *)(c.lds + 2 * P.max_src * 64);
+    const uint64_t below = lanes_below(ln);
+
+    uint32_t raw[EST_KMAX];
+    for (uint32_t j = 0; j < K; ++j) raw[j] = c.st[P.rd_off + op.src_edge[j]];
+    uint64_t *out = nullptr;
+    uint32_t omask = 0, wr, space = 0xFFFFFFFFu;
+    if (is_lat) {
+        wr = c.st[P.miss_off + 1];
+    } else {
+        const EstRing &OR = P.rings[op.out_ring];
+        out = c.rings + OR.off;
+        omask = OR.cap_mask;
+        wr = c.st[P.wr_off + op.out_ring];
+        space = ring_space(c, op.out_ring, wr);
+    }
+    uint32_t miss = 0;
+    bool progress = false, finished = false;
+
+    for (;;) {
+        if (!is_lat && space < 64u * K) break;  // wait for the consumer
+        // ---- stage up to 64 accepted elements of every source
+        uint32_t nst[EST_KMAX], cur[EST_KMAX];
+        uint32_t more = 0;  // bit j: elements beyond the staged ones may exist in source j
+        for (uint32_t j = 0; j < K; ++j) {
+            const View sv = view_of(c, op.src_ring[j]);
+            uint32_t n = 0, rc = raw[j];
+            while (n < 64 && rc != sv.wr) {
+                const uint32_t w = umin(64u, sv.wr - rc);
+                const uint64_t key = ln < w ? sv.base[(rc + ln) & sv.mask] : 0ull;
+                const bool a = ln < w && ((acc[(uint32_t)key] >> j) & 1u);
+                const uint64_t A = wv::ballot(a);
+                const uint32_t room = 64 - n;
+                const uint32_t myrank = popc64(A & below);
+                if (a && myrank < room) {
+                    skey[j * 64 + n + myrank] = key;
+                    spos[j * 64 + n + myrank] = rc + ln;
+                }
+                const uint32_t na = popc64(A);
+                if (na <= room) {
+                    n += na;
+                    rc += w;
+                } else {
+                    // the first accepted element that did not fit is read again next time
+                    uint64_t rest = A;
+                    for (uint32_t i = 0; i < room; ++i) rest &= rest - 1;
+                    rc += ctz64(rest);
+                    n = 64;
+                }
+            }
+            nst[j] = n;
+            cur[j] = rc;
+            if (!(rc == sv.wr && sv.fin)) more |= 1u << j;
+        }
+        wv::sync();
+        // ---- everything up to the smallest "last staged key" of a source that may have more is final
+        uint64_t bound = ~0ull;
+        bool blocked = false;
+        uint32_t staged_total = 0;
+        for (uint32_t j = 0; j < K; ++j) {
+            staged_total += nst[j];
+            if (!((more >> j) & 1u)) continue;
+            if (nst[j] == 0) {
+                blocked = true;
+            } else {
+                uint64_t last = eff_key(skey[j * 64 + nst[j] - 1], j, nst[j] - 1);
+                bound = last < bound ? last : bound;
+            }
+        }
+        if (blocked || staged_total == 0) {
+            if (!blocked) finished = more == 0;
+            break;
+        }
+        // ---- rank every staged element up to the bound among all staged elements
+        uint32_t m_total = 0, m_src[EST_KMAX];
+        for (uint32_t j = 0; j < K; ++j) {
+            const bool have = ln < nst[j];
+            const uint64_t rk = have ? skey[j * 64 + ln] : 0ull;
+            const uint64_t x = eff_key(rk, j, ln);
+            const bool emit = have && x <= bound;
+            m_src[j] = popc64(wv::ballot(emit));
+            if (emit) {
+                uint32_t rank = ln;
+                for (uint32_t j2 = 0; j2 < K; ++j2) {
+                    if (j2 == j) continue;
+                    uint32_t lo = 0, hi = nst[j2];
+                    while (lo < hi) {
+                        uint32_t mid = (lo + hi) >> 1;
+                        uint64_t y = eff_key(skey[j2 * 64 + mid], j2, mid);
+                        bool less = y < x || (y == x && j2 < j);
+                        if (less) lo = mid + 1; else hi = mid;
+                    }
+                    rank += lo;
+                }
+                EST_CHECK(rank < P.max_src * 64);
+                merged[rank] = rk;
+            }
+            m_total += m_src[j];
+        }
+        EST_CHECK(m_total >= 1);
+        wv::sync();
+        // ---- walk the merged run; a query fed by several sources is passed on at its last appearance
+        for (uint32_t base = 0; base < m_total; base += 64) {
+            const bool valid = base + ln < m_total;
+            const uint64_t key = valid ? merged[base + ln] : 0ull;
+            const uint32_t q = (uint32_t)key;
+            bool emitf = valid;
+            if (op.has_cnt) {
+                const uint32_t e = valid ? (uint32_t)__builtin_popcount(acc[q]) : 0u;
+                const bool multi = e > 1;
+                const uint64_t MM = wv::ballot(multi);
+                if (MM) {
+                    const uint32_t c0 = multi ? cnt[q] : 0u;
+                    uint32_t duprank = 0, duptotal = 1;
+                    for (uint64_t todo = MM; todo;) {
+                        const uint32_t l = ctz64(todo);
+                        const uint32_t sq = wv::bcast(q, l);
+                        const uint64_t same = wv::ballot(multi && q == sq);
+                        if (multi && q == sq) {
+                            duprank = popc64(same & below);
+                            duptotal = popc64(same);
+                        }
+                        todo &= ~same;
+                    }
+                    const uint32_t newc = c0 + duprank + 1;
+                    if (multi) {
+                        EST_CHECK(newc <= e);
+                        emitf = newc == e;
+                        if (duprank == duptotal - 1) cnt[q] = (uint8_t)newc;
+                    }
+                    wv::sync();
+                }
+            }
+            const uint64_t Em = wv::ballot(emitf);
+            const uint32_t pos = wr + popc64(Em & below);
+            if (emitf) {
+                if (is_lat) {
+                    const uint32_t l = (uint32_t)(key >> 32) - c.a->arrival[q];
+                    c.lat[c.a->lat_by_qid ? q : pos] = l;
+                    miss += l > c.a->slo_us;
+                } else {
+                    out[pos & omask] = key;
+                }
+            }
+            wr += popc64(Em);
+        }
+        if (!is_lat) space = ring_space(c, op.out_ring, wr);
+        // ---- consumed: everything emitted; what was staged but not emitted is read again
+        for (uint32_t j = 0; j < K; ++j) raw[j] = m_src[j] < nst[j] ? spos[j * 64 + m_src[j]] : cur[j];
+        progress = true;
+        wv::sync();
+    }
+
+    const uint32_t miss_all = is_lat ? wv::sum_u32(miss) : 0u;
+    if (ln == 0) {
+        for (uint32_t j = 0; j < K; ++j) c.st[P.rd_off + op.src_edge[j]] = raw[j];
+        if (is_lat) {
+            c.st[P.miss_off + 1] = wr;
+            c.st[P.miss_off] += miss_all;
+        } else {
+            c.st[P.wr_off + op.out_ring] = wr;
+        }
+        if (finished) {
+            if (!is_lat) c.st[P.fin_off + op.out_ring] = 1;
+            c.st[P.done_off + opi] = 1;
+        }
+    }
+    wv::sync();
+    return progress;
+}
+
+// ------------------------------------------------------------------------------------------ driver
+
+// One wavefront = one candidate.  Every loop ends: an operation that consumes or emits nothing
+// reports no progress, and a full round without progress stops the candidate with an error flag.
+EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint64_t *lds) {
+    const uint32_t ln = wv::lane();
+    const EstPlan &P = *a.plan;
+    Ctx c;
+    c.a = &a;
+    c.P = &P;
+    c.st = a.state + (uint64_t)t * a.state_stride;
+    c.rings = a.rings + (uint64_t)t * a.ring_stride;
+    c.rep = a.rep + (uint64_t)t * a.rep_stride;
+    c.slots = a.slots + (uint64_t)t * a.slot_stride;
+    c.cnt = a.counters + (uint64_t)t * a.cnt_stride;
+    c.lat = a.lat + (uint64_t)t * a.lat_stride;
+    c.cfg = a.cfg + (uint64_t)t * a.dag->S;
+    c.lds = lds;
+
+    for (uint32_t i = ln; i < P.state_words; i += 64) c.st[i] = 0;
+    for (uint64_t i = ln; i < a.rep_stride; i += 64) c.rep[i] = 0;
+    {
+        uint32_t *cw = (uint32_t *)c.cnt;
+        for (uint64_t i = ln; i < a.cnt_stride / 4; i += 64) cw[i] = 0;
+    }
+    wv::sync();
+
+    for (;;) {
+        bool progress = false, alldone = true;
+        for (uint32_t opi = 0; opi < P.n_ops; ++opi) {
+            if (c.st[P.done_off + opi]) continue;
+            const EstOp &op = P.ops[opi];
+            bool p = op.type == EST_OP_SCAN ? scan_run(c, op, opi) : merge_run(c, op, opi);
+            progress = progress || p;
+            alldone = alldone && c.st[P.done_off + opi] != 0;
+        }
+        if (alldone) break;
+        if (!progress) {
+            if (ln == 0) a.status->sim_error = 1;
+            break;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------ P99
+
+// Nearest-rank P99 of one candidate's latencies by a 4-pass radix select (8 bits per pass), one
+// wavefront per candidate, plus the candidate's cost = sum over stages of replicas x price
+// (Section 6, cost model).
+EST_DEV void select_wave(const EstSelectArgs &a, uint32_t t, uint64_t *lds) {
+    const uint32_t ln = wv::lane();
+    const EstStageCfg *cfg = a.cfg + (uint64_t)t * a.dag->S;
+    if (ln == 0) {
+        uint64_t cost = 0;
+        for (uint32_t s = 0; s < a.dag->S; ++s)
+            cost += (uint64_t)cfg[s].replicas * a.cost_uusd_hr[(uint64_t)s * a.dag->H + cfg[s].hw];
+        a.cost[t] = cost;
+    }
+    if (!a.have_lat) return;
+    const uint32_t *lat = a.lat + (uint64_t)t * a.lat_stride;
+    uint32_t *hist = (uint32_t *)lds;  // 256 bins
+    const uint32_t n = a.n;
+    uint32_t k = (uint32_t)(((uint64_t)99 * n + 99) / 100);  // 1-based rank, ceil(0.99 n)
+    uint32_t prefix = 0;
+    for (int pass = 3; pass >= 0; --pass) {
+        const uint32_t shift = (uint32_t)pass * 8;
+        for (uint32_t i = ln; i < 256; i += 64) hist[i] = 0;
+        wv::sync();
+        for (uint32_t i = ln; i < n; i += 64) {
+            const uint32_t v = lat[i];
+            const bool match = pass == 3 || (v >> (shift + 8)) == (prefix >> (shift + 8));
+            if (match) wv::lds_add(&hist[(v >> shift) & 255u], 1u);
+        }
+        wv::sync();
+        // lane l owns bins 4l .. 4l+3
+        const uint32_t h0 = hist[4 * ln], h1 = hist[4 * ln + 1], h2 = hist[4 * ln + 2], h3 = hist[4 * ln + 3];
+        const uint32_t mine = h0 + h1 + h2 + h3;
+        const uint32_t before = wv::prefix_excl_u32(mine);
+        const uint64_t hit = wv::ballot(before < k && k <= before + mine);
+        EST_CHECK(popc64(hit) == 1);
+        const uint32_t hl = ctz64(hit);
+        uint32_t digit = 0, kk = 0;
+        if (ln == hl) {
+            uint32_t r = k - before;  // rank inside my four bins
+            if (r <= h0) { digit = 4 * ln; kk = r; }
+            else if (r <= h0 + h1) { digit = 4 * ln + 1; kk = r - h0; }
+            else if (r <= h0 + h1 + h2) { digit = 4 * ln + 2; kk = r - h0 - h1; }
+            else { digit = 4 * ln + 3; kk = r - h0 - h1 - h2; }
+        }
+        digit = wv::bcast(digit, hl);
+        k = wv::bcast(kk, hl);
+        prefix |= digit << shift;
+        wv::sync();
+    }
+    if (ln == 0) {
+        a.p99[t] = prefix;
+        a.miss[t] = a.state[(uint64_t)t * a.state_stride + a.plan->miss_off];
+    }
+}
+
+// ------------------------------------------------------------------------------------------ preprocessing
+
+// Nearest visited ancestors of every stage (and of the virtual sink, index S) for one query:
+// bit p = the completion of stage p feeds the stage directly, bit EST_TRACE_BIT = the arrival does.
+EST_DEV void nearest_sets(const EstDag &d, uint32_t mask, uint64_t *nv) {
+    for (uint32_t c = 0; c <= d.S; ++c) {
+        uint64_t s = 0;
+        const uint32_t b = d.parent_off[c], e = d.parent_off[c + 1];
+        if (b == e) s = 1ull << EST_TRACE_BIT;
+        for (uint32_t i = b; i < e; ++i) {
+            const uint32_t p = d.parent_idx[i];
+            s |= ((mask >> p) & 1u) ? (1ull << p) : nv[p];
+        }
+        nv[c] = s;
+    }
+}
+
+// Pass 1 over the trace (thread tid of nthreads, strided): monotonicity, per-stage source unions,
+// visit counts.
+EST_DEV void prep1_thread(const EstPrepArgs &a, uint32_t tid, uint32_t nthreads) {
+    const EstDag &d = *a.dag;
+    uint64_t uni[EST_MAX_STAGES + 1];
+    uint32_t cntv[EST_MAX_STAGES + 1];
+    uint64_t multi = 0;  // bit c: some visiting query of stage c has more than one nearest visited ancestor
+    bool bad = false;
+    for (uint32_t c = 0; c <= d.S; ++c) { uni[c] = 0; cntv[c] = 0; }
+    for (uint64_t q = tid; q < a.n; q += nthreads) {
+        const uint32_t m = a.mask[q];
+        if (q > 0 && a.arrival[q] < a.arrival[q - 1]) bad = true;
+        uint64_t nv[EST_MAX_STAGES + 1];
+        nearest_sets(d, m, nv);
+        for (uint32_t c = 0; c <= d.S; ++c) {
+            if (c < d.S && !((m >> c) & 1u)) continue;
+            uni[c] |= nv[c];
+            cntv[c]++;
+            if (__builtin_popcountll(nv[c]) > 1) multi |= 1ull << c;
+        }
+    }
+    for (uint32_t c = 0; c <= d.S; ++c) {
+        if (cntv[c]) {
+            wv::atomic_or_u64(&a.status->src_union[c], uni[c]);
+            wv::atomic_add_u32(&a.status->n_visit[c], cntv[c]);
+            if ((multi >> c) & 1ull) wv::atomic_or_u32(&a.status->multi[c], 1u);
+        }
+    }
+    if (bad) wv::atomic_or_u32(&a.status->bad_trace, 1u);
+    if (tid == 0 && a.n > 0) a.status->last_arrival = a.arrival[a.n - 1];
+}
+
+// Pass 2: the key stream of the trace, and for every merge operation the per-query accept mask:
+// bit j set = source j of the operation is one of the query's nearest visited ancestors.
+EST_DEV void prep2_thread(const EstPrepArgs &a, uint32_t tid, uint32_t nthreads) {
+    const EstDag &d = *a.dag;
+    for (uint64_t q = tid; q < a.n; q += nthreads) {
+        const uint32_t m = a.mask[q];
+        a.trace_keys[q] = ((uint64_t)a.arrival[q] << 32) | q;
+        uint64_t nv[EST_MAX_STAGES + 1];
+        nearest_sets(d, m, nv);
+        for (uint32_t i = 0; i < a.n_acc; ++i) {
+            const uint32_t c = a.acc_stage[i];
+            uint8_t bits = 0;
+            if (c == d.S || ((m >> c) & 1u)) {
+                for (uint64_t s = nv[c]; s; s &= s - 1) {
+                    const uint32_t src = (uint32_t)__builtin_ctzll(s);
+                    bits |= (uint8_t)(1u << a.acc_slot_of_src[c][src]);
+                }
+            }
+            a.acc[(uint64_t)i * a.acc_stride + q] = bits;
+        }
+    }
+}
+
+// Range check of every configuration entry and the per-stage maxima that size the scratch.
+EST_DEV void cfg_thread(const EstCfgArgs &a, uint32_t tid, uint32_t nthreads) {
+    const EstDag &d = *a.dag;
+    uint32_t rmax[EST_MAX_STAGES], bmax[EST_MAX_STAGES];
+    bool bad = false;
+    for (uint32_t s = 0; s < d.S; ++s) { rmax[s] = 0; bmax[s] = 0; }
+    for (uint64_t i = tid; i < a.n_cfg; i += nthreads) {
+        for (uint32_t s = 0; s < d.S; ++s) {
+            const EstStageCfg e = a.cfg[i * d.S + s];
+            if (e.hw >= d.H || e.batch < 1 || e.batch > d.Bmax || e.replicas < 1 || e.replicas > 64) bad = true;
+            rmax[s] = umax(rmax[s], e.replicas);
+            bmax[s] = umax(bmax[s], e.batch);
+        }
+    }
+    for (uint32_t s = 0; s < d.S; ++s) {
+        if (rmax[s]) wv::atomic_max_u32(&a.status->r_max[s], rmax[s]);
+        if (bmax[s]) wv::atomic_max_u32(&a.status->b_max[s], bmax[s]);
+    }
+    if (bad) wv::atomic_or_u32(&a.status->bad_cfg, 1u);
+}
+
+}  // namespace estdev

@@ -1,0 +1,678 @@
+// Host side of the batched Estimator: the C ABI of include/estimator.h, input validation, the
+// per-run plan (which streams feed which stage) and the tiling of candidates over device scratch.
+// Every step of the simulation itself runs in the kernels of est_device.h.
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/estimator.h"
+#include "est_backend.h"
+#include "est_types.h"
+
+static_assert(sizeof(EstStageCfg) == sizeof(est_stage_cfg_t), "configuration entry layout");
+
+struct estimator {
+    EstDag dag;
+    std::vector<uint32_t> lat;
+    std::vector<uint64_t> cost;
+    uint64_t sum_max_lat = 0;  // sum over stages of the largest profiled latency
+    EstDag *d_dag = nullptr;
+    uint32_t *d_lat = nullptr;
+    uint64_t *d_cost = nullptr;
+    EstPlan *d_plan = nullptr;
+    EstStatus *d_status = nullptr;
+    void *ws = nullptr;  // scratch allocated by the library when the caller passes none
+    size_t ws_bytes = 0;
+    std::string err;
+    est_stats_t stats;
+    bool have_stats = false;
+};
+
+namespace {
+
+int fail(estimator *h, int code, const char *fmt, ...) {
+    if (h) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        h->err = buf;
+    }
+    return code;
+}
+
+int dev_fail(estimator *h, const char *what) { return fail(h, EST_EDEVICE, "%s: %s", what, estbe::last_error()); }
+
+uint64_t pow2ceil(uint64_t x) {
+    uint64_t p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+// Sizes of one candidate's scratch, in units of each area.
+struct Sizes {
+    uint64_t state_words = 0, ring_elems = 0, rep_words = 0, slot_words = 0, cnt_bytes = 0;
+    uint64_t per_cfg_bytes(uint64_t n, bool with_lat) const {
+        return state_words * 4 + ring_elems * 8 + rep_words * 4 + slot_words * 4 + cnt_bytes + (with_lat ? n * 4 : 0);
+    }
+};
+
+struct PlanOut {
+    EstPlan plan;
+    Sizes sz;
+    uint32_t n_acc = 0;
+    uint32_t acc_stage[EST_MAX_STAGES + 1];
+    uint8_t acc_slot_of_src[EST_MAX_STAGES + 1][EST_TRACE_BIT + 1];
+};
+
+// Build the operation list for one run from the DAG and what the trace scan found.
+//
+// For stage c (and for the virtual sink, index S) the trace scan gives the union over visiting
+// queries of the query's nearest visited ancestors.  Those are the streams the stage's input has to
+// be merged from.  A stage fed by exactly one stream, every element of which visits the stage, reads
+// that stream directly.
+int build_plan(estimator *h, const EstStatus &st, uint64_t n, PlanOut &po) {
+    const uint32_t S = h->dag.S;
+    EstPlan &P = po.plan;
+    memset(&P, 0, sizeof P);
+    memset(po.acc_slot_of_src, 0xFF, sizeof po.acc_slot_of_src);
+
+    auto count_of = [&](uint32_t src) -> uint64_t { return src == EST_TRACE_BIT ? n : st.n_visit[src]; };
+
+    uint32_t max_rb = 1;
+    for (uint32_t s = 0; s < S; ++s) max_rb = std::max(max_rb, st.r_max[s] * st.b_max[s]);
+    // A bounded ring must take a whole group of batches that complete together (<= R*B members)
+    // while its consumer still holds back a look-ahead window, and a merge wants 64 x sources free.
+    const uint64_t cap_bounded = pow2ceil(std::max<uint64_t>(1024, (uint64_t)max_rb + 64 * EST_KMAX + 65));
+
+    std::vector<int32_t> out_ring(S, -1), in_ring(S, -1);
+    struct Src { uint32_t n; int32_t ring_src[EST_KMAX]; };  // ring_src: stage index or EST_TRACE_BIT
+    std::vector<Src> srcs(S + 1);
+    std::vector<bool> direct(S + 1, false), live(S + 1, false);
+
+    for (uint32_t c = 0; c <= S; ++c) {
+        live[c] = c == S ? true : st.n_visit[c] > 0;
+        srcs[c].n = 0;
+        if (!live[c]) continue;
+        uint64_t u = st.src_union[c];
+        if (u == 0) return fail(h, EST_EINTERNAL, "stage %u is visited but has no input stream", c);
+        for (uint32_t b = 0; b <= EST_TRACE_BIT; ++b) {
+            if (!((u >> b) & 1ull)) continue;
+            if (srcs[c].n == EST_KMAX)
+                return fail(h, EST_EUNSUPPORTED, "stage %u draws from more than %d input streams", c, EST_KMAX);
+            if (b != EST_TRACE_BIT && (b >= S || !live[b]))
+                return fail(h, EST_EINTERNAL, "stage %u fed by dead stage %u", c, b);
+            po.acc_slot_of_src[c][b] = (uint8_t)srcs[c].n;
+            srcs[c].ring_src[srcs[c].n++] = (int32_t)b;
+        }
+        direct[c] = c < S && srcs[c].n == 1 && count_of((uint32_t)srcs[c].ring_src[0]) == st.n_visit[c];
+    }
+
+    // rings
+    uint32_t nr = 0;
+    for (uint32_t s = 0; s < S; ++s) {
+        if (!live[s]) continue;
+        out_ring[s] = (int32_t)nr++;
+        if (!direct[s]) in_ring[s] = (int32_t)nr++;
+    }
+    P.n_rings = nr;
+
+    // operations in topological order, consumers registered on the rings they read
+    uint32_t no = 0, ne = 0;
+    auto add_consumer = [&](int32_t ring, uint32_t edge) -> bool {
+        if (ring < 0) return true;
+        EstRing &R = P.rings[ring];
+        if (R.n_cons == EST_MAX_CONS) return false;
+        R.cons_edge[R.n_cons++] = (uint16_t)edge;
+        return true;
+    };
+    auto ring_of_src = [&](int32_t src) -> int32_t { return src == EST_TRACE_BIT ? EST_SRC_TRACE : out_ring[src]; };
+
+    for (uint32_t c = 0; c <= S; ++c) {
+        if (!live[c]) continue;
+        if (c == S || !direct[c]) {
+            EstOp &op = P.ops[no++];
+            op.type = c == S ? EST_OP_LAT : EST_OP_MERGE;
+            op.stage = c;
+            op.n_src = srcs[c].n;
+            for (uint32_t j = 0; j < srcs[c].n; ++j) {
+                op.src_ring[j] = ring_of_src(srcs[c].ring_src[j]);
+                op.src_edge[j] = ne;
+                if (!add_consumer(op.src_ring[j], ne)) return fail(h, EST_EUNSUPPORTED, "too many consumers of one stream");
+                ++ne;
+            }
+            op.out_ring = c == S ? -1 : in_ring[c];
+            op.acc_idx = po.n_acc;
+            po.acc_stage[po.n_acc++] = c;
+            op.has_cnt = st.multi[c] ? 1 : 0;
+            if (op.has_cnt) {
+                op.cnt_off = po.sz.cnt_bytes;
+                po.sz.cnt_bytes += align_up(n, 16);
+            }
+        }
+        if (c < S) {
+            EstOp &op = P.ops[no++];
+            op.type = EST_OP_SCAN;
+            op.stage = c;
+            op.n_src = 1;
+            op.src_ring[0] = direct[c] ? ring_of_src(srcs[c].ring_src[0]) : in_ring[c];
+            op.src_edge[0] = ne;
+            if (!add_consumer(op.src_ring[0], ne)) return fail(h, EST_EUNSUPPORTED, "too many consumers of one stream");
+            ++ne;
+            op.out_ring = out_ring[c];
+            op.r_max = st.r_max[c];
+            op.b_max = st.b_max[c];
+            op.rep_off = (uint32_t)po.sz.rep_words;
+            po.sz.rep_words += 2ull * op.r_max;
+            op.slot_off = po.sz.slot_words;
+            po.sz.slot_words += (uint64_t)op.r_max * op.b_max;
+        }
+    }
+    P.n_ops = no;
+    P.n_edges = ne;
+    P.max_src = 1;
+    for (uint32_t i = 0; i < no; ++i) P.max_src = std::max(P.max_src, P.ops[i].n_src);
+
+    // ring capacities: a stream read by several operations may have to hold the whole skew between
+    // them (one branch of a fork can lag another by the length of its simulated queue), so it gets
+    // room for every element; a stream with one reader is a bounded ring
+    uint64_t off = 0;
+    for (uint32_t s = 0; s < S; ++s) {
+        if (!live[s]) continue;
+        {
+            EstRing &R = P.rings[out_ring[s]];
+            uint64_t cap = R.n_cons >= 2 ? std::max<uint64_t>(cap_bounded, pow2ceil(st.n_visit[s])) : cap_bounded;
+            R.off = off;
+            R.cap_mask = (uint32_t)(cap - 1);
+            off += cap;
+        }
+        if (in_ring[s] >= 0) {
+            EstRing &R = P.rings[in_ring[s]];
+            R.off = off;
+            R.cap_mask = (uint32_t)(cap_bounded - 1);
+            off += cap_bounded;
+        }
+    }
+    po.sz.ring_elems = off;
+
+    P.wr_off = 0;
+    P.fin_off = P.n_rings;
+    P.rd_off = 2 * P.n_rings;
+    P.done_off = P.rd_off + P.n_edges;
+    P.miss_off = P.done_off + P.n_ops;
+    P.state_words = (uint32_t)align_up(P.miss_off + 2, 4);
+    po.sz.state_words = P.state_words;
+    po.sz.rep_words = align_up(po.sz.rep_words, 4);
+    po.sz.slot_words = align_up(po.sz.slot_words, 4);
+    return EST_OK;
+}
+
+struct EventSet {
+    std::vector<void *> ev;
+    ~EventSet() {
+        for (void *e : ev) estbe::event_destroy(e);
+    }
+    void *make() {
+        void *e = estbe::event_create();
+        if (e) ev.push_back(e);
+        return e;
+    }
+};
+
+enum { MODE_P99 = 0, MODE_LAT = 1 };
+
+int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t *d_mask,
+             const est_stage_cfg_t *d_cfg, uint64_t n_cfg, uint32_t slo_us, int mode, uint32_t *d_p99,
+             uint32_t *d_miss, uint64_t *d_cost, uint32_t *d_lat_out, void *workspace, uint64_t workspace_bytes,
+             void *stream) {
+    if (n >= (1ull << 31)) return fail(h, EST_EINVAL, "trace too long (%llu queries)", (unsigned long long)n);
+    if (n_cfg >= (1ull << 31)) return fail(h, EST_EINVAL, "too many configurations");
+    if (n_cfg == 0) return EST_OK;
+    const uint32_t S = h->dag.S;
+    EventSet evs;
+    void *ev_p0 = evs.make(), *ev_p1 = evs.make(), *ev_p2 = evs.make(), *ev_p3 = evs.make();
+    if (!ev_p0 || !ev_p1 || !ev_p2 || !ev_p3) return dev_fail(h, "event create");
+
+    // ---- scan the configurations and the trace
+    if (estbe::zero(h->d_status, sizeof(EstStatus), stream)) return dev_fail(h, "clear status");
+    estbe::event_record(ev_p0, stream);
+    EstCfgArgs ca;
+    ca.dag = h->d_dag;
+    ca.cfg = (const EstStageCfg *)d_cfg;
+    ca.n_cfg = n_cfg;
+    ca.status = h->d_status;
+    if (estbe::launch_cfg(ca, stream)) return dev_fail(h, "configuration scan");
+    EstPrepArgs pa;
+    memset(&pa, 0, sizeof pa);
+    pa.dag = h->d_dag;
+    pa.arrival = d_arrival;
+    pa.mask = d_mask;
+    pa.n = (uint32_t)n;
+    pa.status = h->d_status;
+    if (n > 0 && estbe::launch_prep1(pa, stream)) return dev_fail(h, "trace scan");
+    estbe::event_record(ev_p1, stream);
+    EstStatus st;
+    if (estbe::d2h(&st, h->d_status, sizeof st, stream) || estbe::sync(stream)) return dev_fail(h, "read status");
+    if (st.bad_cfg) return fail(h, EST_EINVAL, "a configuration entry is out of range (hw < %u, 1 <= batch <= %u, 1 <= replicas <= %d)",
+                                h->dag.H, h->dag.Bmax, EST_MAX_REPLICAS);
+    if (st.bad_trace) return fail(h, EST_EINVAL, "arrival times decrease");
+    if (n > 0 && (uint64_t)st.last_arrival + h->sum_max_lat + slo_us >= EST_HORIZON_US)
+        return fail(h, EST_EINVAL, "trace too close to the horizon: last arrival %u + worst service %llu + slo %u >= 2^32-1",
+                    st.last_arrival, (unsigned long long)h->sum_max_lat, slo_us);
+    st.n_visit[S] = (uint32_t)n;
+
+    PlanOut po;
+    po.sz = Sizes();
+    po.n_acc = 0;
+    if (n > 0) {
+        int rc = build_plan(h, st, n, po);
+        if (rc != EST_OK) return rc;
+    } else {
+        memset(&po.plan, 0, sizeof po.plan);
+        po.plan.state_words = 4;
+        po.sz.state_words = 4;
+    }
+    const bool with_lat = mode == MODE_P99 && n > 0;
+
+    // ---- lay out the scratch
+    const uint64_t n_pad = align_up(std::max<uint64_t>(n, 1), 256);
+    uint64_t fixed = 0;
+    auto take = [&](uint64_t bytes) {
+        uint64_t at = fixed;
+        fixed = align_up(fixed + bytes, 256);
+        return at;
+    };
+    const uint64_t o_keys = take(n_pad * 8);
+    const uint64_t o_acc = take((uint64_t)std::max<uint32_t>(po.n_acc, 1) * n_pad);
+    const uint64_t o_p99 = take(n_cfg * 4);
+    const uint64_t o_miss = take(n_cfg * 4);
+    const uint64_t o_cost = take(n_cfg * 8);
+    const uint64_t per_cfg = po.sz.per_cfg_bytes(n, with_lat) + 64;  // + alignment slack per area
+
+    uint8_t *ws = (uint8_t *)workspace;
+    uint64_t ws_bytes = workspace_bytes;
+    if (!ws) {
+        uint64_t want = fixed + per_cfg * n_cfg + 8 * 256;
+        uint64_t avail = (uint64_t)estbe::mem_free() + h->ws_bytes;
+        uint64_t budget = std::min<uint64_t>(want, avail / 100 * 85);
+        if (h->ws_bytes < budget || h->ws_bytes > 2 * budget + (64u << 20)) {
+            if (h->ws) estbe::dfree(h->ws);
+            h->ws = nullptr;
+            h->ws_bytes = 0;
+            h->ws = estbe::dmalloc(budget);
+            if (!h->ws) return fail(h, EST_ENOMEM, "cannot allocate %llu bytes of device scratch", (unsigned long long)budget);
+            h->ws_bytes = budget;
+        }
+        ws = (uint8_t *)h->ws;
+        ws_bytes = h->ws_bytes;
+    }
+    if (((uintptr_t)ws & 255) != 0) return fail(h, EST_EINVAL, "workspace must be 256-byte aligned");
+    if (ws_bytes < fixed + per_cfg + 8 * 256)
+        return fail(h, EST_ENOMEM, "workspace of %llu bytes cannot hold one candidate (%llu + %llu bytes needed)",
+                    (unsigned long long)ws_bytes, (unsigned long long)fixed, (unsigned long long)per_cfg);
+    uint64_t tile = std::min<uint64_t>((ws_bytes - fixed - 8 * 256) / per_cfg, n_cfg);
+    // areas of one tile
+    uint64_t at = fixed;
+    auto area = [&](uint64_t bytes_per_cfg) {
+        uint64_t a0 = at;
+        at = align_up(at + bytes_per_cfg * tile, 256);
+        return a0;
+    };
+    const uint64_t o_state = area(po.sz.state_words * 4);
+    const uint64_t o_rings = area(po.sz.ring_elems * 8);
+    const uint64_t o_rep = area(po.sz.rep_words * 4);
+    const uint64_t o_slots = area(po.sz.slot_words * 4);
+    const uint64_t o_cnt = area(po.sz.cnt_bytes);
+    const uint64_t o_lat = area(with_lat ? n * 4 : 0);
+    if (at > ws_bytes) return fail(h, EST_EINTERNAL, "scratch layout overflow");
+
+    // ---- per-query tables
+    estbe::event_record(ev_p2, stream);
+    if (n > 0) {
+        if (estbe::h2d(h->d_plan, &po.plan, sizeof(EstPlan), stream)) return dev_fail(h, "upload plan");
+        pa.trace_keys = (uint64_t *)(ws + o_keys);
+        pa.acc = ws + o_acc;
+        pa.acc_stride = n_pad;
+        pa.n_acc = po.n_acc;
+        memcpy(pa.acc_stage, po.acc_stage, sizeof(uint32_t) * po.n_acc);
+        memcpy(pa.acc_slot_of_src, po.acc_slot_of_src, sizeof pa.acc_slot_of_src);
+        if (estbe::launch_prep2(pa, stream)) return dev_fail(h, "trace tables");
+    }
+    estbe::event_record(ev_p3, stream);
+
+    // ---- tiles of candidates
+    uint32_t *s_p99 = (uint32_t *)(ws + o_p99);
+    uint32_t *s_miss = (uint32_t *)(ws + o_miss);
+    uint64_t *s_cost = (uint64_t *)(ws + o_cost);
+    if (n == 0 && mode == MODE_P99) {
+        if (estbe::zero(s_p99, n_cfg * 4, stream) || estbe::zero(s_miss, n_cfg * 4, stream)) return dev_fail(h, "clear results");
+    }
+    std::vector<void *> tev;
+    uint32_t n_tiles = 0;
+    for (uint64_t base = 0; base < n_cfg; base += tile, ++n_tiles) {
+        const uint64_t tn = std::min<uint64_t>(tile, n_cfg - base);
+        void *e0 = evs.make(), *e1 = evs.make(), *e2 = evs.make();
+        if (!e0 || !e1 || !e2) return dev_fail(h, "event create");
+        tev.push_back(e0); tev.push_back(e1); tev.push_back(e2);
+        estbe::event_record(e0, stream);
+        if (n > 0) {
+            EstSimArgs sa;
+            memset(&sa, 0, sizeof sa);
+            sa.plan = h->d_plan;
+            sa.dag = h->d_dag;
+            sa.lat_us = h->d_lat;
+            sa.cost_uusd_hr = h->d_cost;
+            sa.arrival = d_arrival;
+            sa.trace_keys = (const uint64_t *)(ws + o_keys);
+            sa.acc = ws + o_acc;
+            sa.acc_stride = n_pad;
+            sa.cfg = (const EstStageCfg *)d_cfg + base * S;
+            sa.n = (uint32_t)n;
+            sa.tile_n = (uint32_t)tn;
+            sa.slo_us = slo_us;
+            sa.lat_by_qid = mode == MODE_LAT;
+            sa.max_src = po.plan.max_src;
+            sa.state = (uint32_t *)(ws + o_state);  sa.state_stride = po.sz.state_words;
+            sa.rings = (uint64_t *)(ws + o_rings);  sa.ring_stride = po.sz.ring_elems;
+            sa.rep = (uint32_t *)(ws + o_rep);      sa.rep_stride = po.sz.rep_words;
+            sa.slots = (uint32_t *)(ws + o_slots);  sa.slot_stride = po.sz.slot_words;
+            sa.counters = ws + o_cnt;               sa.cnt_stride = po.sz.cnt_bytes;
+            if (mode == MODE_LAT) {
+                sa.lat = d_lat_out + base * n;
+                sa.lat_stride = n;
+            } else {
+                sa.lat = (uint32_t *)(ws + o_lat);
+                sa.lat_stride = n;
+            }
+            sa.status = h->d_status;
+            if (estbe::launch_sim(sa, stream)) return dev_fail(h, "simulation kernel");
+        }
+        estbe::event_record(e1, stream);
+        if (mode == MODE_P99) {
+            EstSelectArgs se;
+            memset(&se, 0, sizeof se);
+            se.plan = h->d_plan;
+            se.dag = h->d_dag;
+            se.cost_uusd_hr = h->d_cost;
+            se.cfg = (const EstStageCfg *)d_cfg + base * S;
+            se.lat = (const uint32_t *)(ws + o_lat);
+            se.lat_stride = n;
+            se.state = (const uint32_t *)(ws + o_state);
+            se.state_stride = po.sz.state_words;
+            se.n = (uint32_t)n;
+            se.tile_n = (uint32_t)tn;
+            se.have_lat = n > 0;
+            se.p99 = s_p99 + base;
+            se.miss = s_miss + base;
+            se.cost = s_cost + base;
+            if (estbe::launch_select(se, stream)) return dev_fail(h, "selection kernel");
+        }
+        estbe::event_record(e2, stream);
+    }
+    EstStatus st2;
+    if (estbe::d2h(&st2, h->d_status, sizeof st2, stream) || estbe::sync(stream)) return dev_fail(h, "run");
+    if (st2.sim_error) return fail(h, EST_EINTERNAL, "the simulation kernel stopped without finishing a candidate");
+    if (mode == MODE_P99) {
+        if (estbe::d2d(d_p99, s_p99, n_cfg * 4, stream) || estbe::d2d(d_miss, s_miss, n_cfg * 4, stream) ||
+            estbe::d2d(d_cost, s_cost, n_cfg * 8, stream) || estbe::sync(stream))
+            return dev_fail(h, "copy results");
+    }
+    est_stats_t &ss = h->stats;
+    memset(&ss, 0, sizeof ss);
+    ss.n_tiles = n_tiles;
+    ss.tile_configs = (uint32_t)tile;
+    for (size_t i = 0; i + 2 < tev.size(); i += 3) {
+        ss.sim_ms += estbe::event_ms(tev[i], tev[i + 1]);
+        ss.select_ms += estbe::event_ms(tev[i + 1], tev[i + 2]);
+    }
+    ss.prep_ms = estbe::event_ms(ev_p0, ev_p1) + estbe::event_ms(ev_p2, ev_p3);
+    for (uint32_t s = 0; s < S; ++s) ss.stage_visits += st.n_visit[s];
+    ss.workspace_bytes = at;
+    h->have_stats = true;
+    return EST_OK;
+}
+
+int check_run_args(estimator *h, const est_trace_t *trace, const est_stage_cfg_t *configs, uint64_t n_cfg) {
+    if (!h) return EST_EINVAL;
+    h->err.clear();
+    if (!trace) return fail(h, EST_EINVAL, "trace is NULL");
+    if (trace->n > 0 && (!trace->arrival_us || !trace->visit_mask)) return fail(h, EST_EINVAL, "trace arrays are NULL");
+    if (n_cfg > 0 && !configs) return fail(h, EST_EINVAL, "configs is NULL");
+    return EST_OK;
+}
+
+struct DevBuf {
+    void *p = nullptr;
+    ~DevBuf() {
+        if (p) estbe::dfree(p);
+    }
+    bool alloc(size_t bytes) {
+        p = estbe::dmalloc(bytes ? bytes : 4);
+        return p != nullptr;
+    }
+};
+
+}  // namespace
+
+extern "C" {
+
+int estimator_create(const est_dag_t *dag, const est_profiles_t *prof, estimator_t **out) {
+    if (!out) return EST_EINVAL;
+    *out = nullptr;
+    if (!dag || !prof || !dag->parent_off || !prof->lat_us || !prof->cost_uusd_hr) return EST_EINVAL;
+    const uint32_t S = dag->n_stages;
+    if (S < 1 || S > EST_MAX_STAGES) return EST_EINVAL;
+    if (prof->n_hw < 1 || prof->n_hw > 255 || prof->max_batch < 1 || prof->max_batch > EST_MAX_BATCH) return EST_EINVAL;
+    if (dag->parent_off[0] != 0) return EST_EINVAL;
+    for (uint32_t c = 0; c < S; ++c) {
+        if (dag->parent_off[c + 1] < dag->parent_off[c] || dag->parent_off[c + 1] - dag->parent_off[c] > c) return EST_EINVAL;
+        if (dag->parent_off[c + 1] > dag->parent_off[c] && !dag->parent_idx) return EST_EINVAL;
+        for (uint32_t e = dag->parent_off[c]; e < dag->parent_off[c + 1]; ++e) {
+            if (dag->parent_idx[e] >= c) return EST_EINVAL;
+            for (uint32_t f = dag->parent_off[c]; f < e; ++f)
+                if (dag->parent_idx[f] == dag->parent_idx[e]) return EST_EINVAL;
+        }
+    }
+    const size_t nl = (size_t)S * prof->n_hw * prof->max_batch;
+    for (size_t i = 0; i < nl; ++i)
+        if (prof->lat_us[i] == 0) return EST_EINVAL;
+
+    estimator *h = new (std::nothrow) estimator;
+    if (!h) return EST_ENOMEM;
+    try {
+        h->lat.assign(prof->lat_us, prof->lat_us + nl);
+        h->cost.assign(prof->cost_uusd_hr, prof->cost_uusd_hr + (size_t)S * prof->n_hw);
+    } catch (...) {
+        delete h;
+        return EST_ENOMEM;
+    }
+    memset(&h->dag, 0, sizeof h->dag);
+    memset(&h->stats, 0, sizeof h->stats);
+    h->dag.S = S;
+    h->dag.H = prof->n_hw;
+    h->dag.Bmax = prof->max_batch;
+    bool has_child[EST_MAX_STAGES] = {false};
+    const uint32_t E = dag->parent_off[S];
+    for (uint32_t c = 0; c <= S; ++c) h->dag.parent_off[c] = dag->parent_off[c];
+    for (uint32_t e = 0; e < E; ++e) {
+        h->dag.parent_idx[e] = dag->parent_idx[e];
+        has_child[dag->parent_idx[e]] = true;
+    }
+    uint32_t e2 = E;  // the virtual sink's parents: every stage without children
+    for (uint32_t s = 0; s < S; ++s)
+        if (!has_child[s]) h->dag.parent_idx[e2++] = s;
+    h->dag.parent_off[S + 1] = e2;
+    for (uint32_t s = 0; s < S; ++s) {
+        uint32_t m = 0;
+        for (size_t i = 0; i < (size_t)prof->n_hw * prof->max_batch; ++i)
+            m = std::max(m, h->lat[(size_t)s * prof->n_hw * prof->max_batch + i]);
+        h->sum_max_lat += m;
+    }
+    if (estbe::init()) {
+        delete h;
+        return EST_EDEVICE;
+    }
+    h->d_dag = (EstDag *)estbe::dmalloc(sizeof(EstDag));
+    h->d_lat = (uint32_t *)estbe::dmalloc(nl * 4);
+    h->d_cost = (uint64_t *)estbe::dmalloc(h->cost.size() * 8);
+    h->d_plan = (EstPlan *)estbe::dmalloc(sizeof(EstPlan));
+    h->d_status = (EstStatus *)estbe::dmalloc(sizeof(EstStatus));
+    if (!h->d_dag || !h->d_lat || !h->d_cost || !h->d_plan || !h->d_status) {
+        estimator_destroy(h);
+        return EST_ENOMEM;
+    }
+    if (estbe::h2d(h->d_dag, &h->dag, sizeof(EstDag), nullptr) || estbe::h2d(h->d_lat, h->lat.data(), nl * 4, nullptr) ||
+        estbe::h2d(h->d_cost, h->cost.data(), h->cost.size() * 8, nullptr) || estbe::sync(nullptr)) {
+        estimator_destroy(h);
+        return EST_EDEVICE;
+    }
+    *out = h;
+    return EST_OK;
+}
+
+int estimator_run_dev(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *configs, uint64_t n_cfg,
+                      uint32_t slo_us, est_result_t *out, void *workspace, uint64_t workspace_bytes, void *hip_stream) {
+    int rc = check_run_args(h, trace, configs, n_cfg);
+    if (rc != EST_OK) return rc;
+    if (n_cfg > 0 && (!out || !out->p99_us || !out->miss_count || !out->cost_uusd_hr)) return fail(h, EST_EINVAL, "result arrays are NULL");
+    try {
+        return run_core(h, trace->n, trace->arrival_us, trace->visit_mask, configs, n_cfg, slo_us, MODE_P99, out ? out->p99_us : nullptr,
+                        out ? out->miss_count : nullptr, out ? out->cost_uusd_hr : nullptr, nullptr, workspace, workspace_bytes, hip_stream);
+    } catch (const std::bad_alloc &) {
+        return fail(h, EST_ENOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(h, EST_EINTERNAL, "unexpected exception");
+    }
+}
+
+int estimator_run_latencies_dev(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *configs, uint64_t n_cfg,
+                                uint32_t *lat_us_out, void *workspace, uint64_t workspace_bytes, void *hip_stream) {
+    int rc = check_run_args(h, trace, configs, n_cfg);
+    if (rc != EST_OK) return rc;
+    if (n_cfg > 0 && trace->n > 0 && !lat_us_out) return fail(h, EST_EINVAL, "lat_us_out is NULL");
+    try {
+        return run_core(h, trace->n, trace->arrival_us, trace->visit_mask, configs, n_cfg, 0, MODE_LAT, nullptr, nullptr, nullptr,
+                        lat_us_out, workspace, workspace_bytes, hip_stream);
+    } catch (const std::bad_alloc &) {
+        return fail(h, EST_ENOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(h, EST_EINTERNAL, "unexpected exception");
+    }
+}
+
+static int run_host(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *configs, uint64_t n_cfg, uint32_t slo_us,
+                    est_result_t *out, uint32_t *lat_out) {
+    const uint64_t n = trace->n;
+    const uint32_t S = h->dag.S;
+    if (n >= (1ull << 31) || n_cfg >= (1ull << 31)) return fail(h, EST_EINVAL, "trace or configuration set too large");
+    if (n_cfg == 0) return EST_OK;
+    // validate on the host first, so that a bad input never reaches the GPU
+    for (uint64_t q = 1; q < n; ++q)
+        if (trace->arrival_us[q] < trace->arrival_us[q - 1]) return fail(h, EST_EINVAL, "arrival times decrease at query %llu", (unsigned long long)q);
+    for (uint64_t i = 0; i < n_cfg * S; ++i) {
+        const est_stage_cfg_t &e = configs[i];
+        if (e.hw >= h->dag.H || e.batch < 1 || e.batch > h->dag.Bmax || e.replicas < 1 || e.replicas > EST_MAX_REPLICAS)
+            return fail(h, EST_EINVAL, "configuration %llu stage %llu out of range", (unsigned long long)(i / S), (unsigned long long)(i % S));
+    }
+    DevBuf d_arr, d_mask, d_cfg, d_p99, d_miss, d_cost, d_lat;
+    if (!d_arr.alloc(n * 4) || !d_mask.alloc(n * 4) || !d_cfg.alloc(n_cfg * S * sizeof(est_stage_cfg_t)))
+        return fail(h, EST_ENOMEM, "device allocation of the inputs failed");
+    if (estbe::h2d(d_arr.p, trace->arrival_us, n * 4, nullptr) || estbe::h2d(d_mask.p, trace->visit_mask, n * 4, nullptr) ||
+        estbe::h2d(d_cfg.p, configs, n_cfg * S * sizeof(est_stage_cfg_t), nullptr))
+        return dev_fail(h, "upload inputs");
+    int rc;
+    if (lat_out) {
+        if (!d_lat.alloc(n_cfg * n * 4)) return fail(h, EST_ENOMEM, "device allocation of the latency matrix failed");
+        rc = run_core(h, n, (const uint32_t *)d_arr.p, (const uint32_t *)d_mask.p, (const est_stage_cfg_t *)d_cfg.p, n_cfg, 0, MODE_LAT,
+                      nullptr, nullptr, nullptr, (uint32_t *)d_lat.p, nullptr, 0, nullptr);
+        if (rc != EST_OK) return rc;
+        if (n > 0 && (estbe::d2h(lat_out, d_lat.p, n_cfg * n * 4, nullptr) || estbe::sync(nullptr))) return dev_fail(h, "download latencies");
+        return EST_OK;
+    }
+    if (!d_p99.alloc(n_cfg * 4) || !d_miss.alloc(n_cfg * 4) || !d_cost.alloc(n_cfg * 8)) return fail(h, EST_ENOMEM, "device allocation of the results failed");
+    rc = run_core(h, n, (const uint32_t *)d_arr.p, (const uint32_t *)d_mask.p, (const est_stage_cfg_t *)d_cfg.p, n_cfg, slo_us, MODE_P99,
+                  (uint32_t *)d_p99.p, (uint32_t *)d_miss.p, (uint64_t *)d_cost.p, nullptr, nullptr, 0, nullptr);
+    if (rc != EST_OK) return rc;
+    std::vector<uint32_t> p99(n_cfg), miss(n_cfg);
+    std::vector<uint64_t> cost(n_cfg);
+    if (estbe::d2h(p99.data(), d_p99.p, n_cfg * 4, nullptr) || estbe::d2h(miss.data(), d_miss.p, n_cfg * 4, nullptr) ||
+        estbe::d2h(cost.data(), d_cost.p, n_cfg * 8, nullptr) || estbe::sync(nullptr))
+        return dev_fail(h, "download results");
+    memcpy(out->p99_us, p99.data(), n_cfg * 4);
+    memcpy(out->miss_count, miss.data(), n_cfg * 4);
+    memcpy(out->cost_uusd_hr, cost.data(), n_cfg * 8);
+    return EST_OK;
+}
+
+int estimator_run(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *configs, uint64_t n_cfg, uint32_t slo_us,
+                  est_result_t *out) {
+    int rc = check_run_args(h, trace, configs, n_cfg);
+    if (rc != EST_OK) return rc;
+    if (n_cfg > 0 && (!out || !out->p99_us || !out->miss_count || !out->cost_uusd_hr)) return fail(h, EST_EINVAL, "result arrays are NULL");
+    try {
+        return run_host(h, trace, configs, n_cfg, slo_us, out, nullptr);
+    } catch (const std::bad_alloc &) {
+        return fail(h, EST_ENOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(h, EST_EINTERNAL, "unexpected exception");
+    }
+}
+
+int estimator_run_latencies(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *configs, uint64_t n_cfg,
+                            uint32_t *lat_us_out) {
+    int rc = check_run_args(h, trace, configs, n_cfg);
+    if (rc != EST_OK) return rc;
+    if (n_cfg > 0 && trace->n > 0 && !lat_us_out) return fail(h, EST_EINVAL, "lat_us_out is NULL");
+    static uint32_t dummy;
+    try {
+        return run_host(h, trace, configs, n_cfg, 0, nullptr, lat_us_out ? lat_us_out : &dummy);
+    } catch (const std::bad_alloc &) {
+        return fail(h, EST_ENOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(h, EST_EINTERNAL, "unexpected exception");
+    }
+}
+
+uint64_t estimator_workspace_bytes(const estimator_t *h, uint64_t n, uint64_t n_cfg) {
+    if (!h) return 0;
+    const uint32_t S = h->dag.S;
+    const uint64_t n_pad = align_up(std::max<uint64_t>(n, 1), 256);
+    // every stage forking: an unbounded out ring, a bounded in ring, counters, full slots
+    const uint64_t cap_b = pow2ceil(EST_MAX_REPLICAS * EST_MAX_BATCH + 64 * EST_KMAX + 65);
+    uint64_t per_cfg = (4ull * EST_MAX_RINGS + EST_MAX_EDGES + EST_MAX_OPS) * 4;
+    per_cfg += (uint64_t)S * (std::max(cap_b, pow2ceil(std::max<uint64_t>(n, 1))) + cap_b) * 8;
+    per_cfg += (uint64_t)S * (2 * EST_MAX_REPLICAS + EST_MAX_REPLICAS * EST_MAX_BATCH) * 4;
+    per_cfg += (uint64_t)(S + 1) * align_up(n, 16);
+    per_cfg += n * 4 + 64;
+    uint64_t fixed = n_pad * 8 + (uint64_t)(S + 1) * n_pad + n_cfg * 16 + 16 * 256;
+    return fixed + per_cfg * std::max<uint64_t>(n_cfg, 1);
+}
+
+int estimator_last_stats(const estimator_t *h, est_stats_t *out) {
+    if (!h || !out) return EST_EINVAL;
+    if (!h->have_stats) return EST_EINVAL;
+    *out = h->stats;
+    return EST_OK;
+}
+
+const char *estimator_last_error(const estimator_t *h) { return h ? h->err.c_str() : "invalid handle"; }
+
+void estimator_destroy(estimator_t *h) {
+    if (!h) return;
+    if (h->d_dag) estbe::dfree(h->d_dag);
+    if (h->d_lat) estbe::dfree(h->d_lat);
+    if (h->d_cost) estbe::dfree(h->d_cost);
+    if (h->d_plan) estbe::dfree(h->d_plan);
+    if (h->d_status) estbe::dfree(h->d_status);
+    if (h->ws) estbe::dfree(h->ws);
+    delete h;
+}
+
+}  // extern "C"

@@ -1,0 +1,132 @@
+// GPU back end: kernel entry points (one 64-lane wavefront per workgroup) and the HIP runtime
+// calls the host planner needs.  gfx950 only.
+#include <hip/hip_runtime.h>
+
+#include <string>
+
+#include "est_backend.h"
+#include "wave_gfx950.h"
+#include "est_device.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+int check(hipError_t e, const char *what) {
+    if (e == hipSuccess) return 0;
+    g_err = std::string(what) + ": " + hipGetErrorString(e);
+    return 1;
+}
+
+// One wavefront per candidate of the tile.
+__global__ __launch_bounds__(64) void est_sim_kernel(EstSimArgs a) {
+    extern __shared__ uint64_t lds[];  // EST_LDS_WORDS64(widest merge of the plan)
+    if (blockIdx.x < a.tile_n) estdev::sim_wave(a, blockIdx.x, lds);
+}
+
+__global__ __launch_bounds__(64) void est_select_kernel(EstSelectArgs a) {
+    __shared__ uint64_t lds[128];
+    if (blockIdx.x < a.tile_n) estdev::select_wave(a, blockIdx.x, lds);
+}
+
+__global__ __launch_bounds__(256) void est_prep1_kernel(EstPrepArgs a) {
+    estdev::prep1_thread(a, blockIdx.x * blockDim.x + threadIdx.x, gridDim.x * blockDim.x);
+}
+
+__global__ __launch_bounds__(256) void est_prep2_kernel(EstPrepArgs a) {
+    estdev::prep2_thread(a, blockIdx.x * blockDim.x + threadIdx.x, gridDim.x * blockDim.x);
+}
+
+__global__ __launch_bounds__(256) void est_cfg_kernel(EstCfgArgs a) {
+    estdev::cfg_thread(a, blockIdx.x * blockDim.x + threadIdx.x, gridDim.x * blockDim.x);
+}
+
+uint32_t blocks_for(uint64_t items, uint32_t per_block, uint32_t max_blocks) {
+    uint64_t b = (items + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    return (uint32_t)(b > max_blocks ? max_blocks : b);
+}
+
+}  // namespace
+
+namespace estbe {
+
+const char *last_error() { return g_err.c_str(); }
+
+int init() {
+    int n = 0;
+    if (check(hipGetDeviceCount(&n), "hipGetDeviceCount")) return 1;
+    if (n < 1) {
+        g_err = "no HIP device";
+        return 1;
+    }
+    return 0;
+}
+
+void *dmalloc(size_t bytes) {
+    void *p = nullptr;
+    if (check(hipMalloc(&p, bytes), "hipMalloc")) return nullptr;
+    return p;
+}
+
+void dfree(void *p) { (void)hipFree(p); }
+
+size_t mem_free() {
+    size_t f = 0, t = 0;
+    if (hipMemGetInfo(&f, &t) != hipSuccess) return 0;
+    return f;
+}
+
+int h2d(void *dst, const void *src, size_t bytes, void *stream) {
+    if (bytes == 0) return 0;
+    return check(hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, (hipStream_t)stream), "hipMemcpyAsync H2D");
+}
+int d2h(void *dst, const void *src, size_t bytes, void *stream) {
+    if (bytes == 0) return 0;
+    return check(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, (hipStream_t)stream), "hipMemcpyAsync D2H");
+}
+int d2d(void *dst, const void *src, size_t bytes, void *stream) {
+    if (bytes == 0) return 0;
+    return check(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, (hipStream_t)stream), "hipMemcpyAsync D2D");
+}
+int zero(void *dst, size_t bytes, void *stream) {
+    if (bytes == 0) return 0;
+    return check(hipMemsetAsync(dst, 0, bytes, (hipStream_t)stream), "hipMemsetAsync");
+}
+int sync(void *stream) { return check(hipStreamSynchronize((hipStream_t)stream), "hipStreamSynchronize"); }
+
+int launch_cfg(const EstCfgArgs &a, void *stream) {
+    est_cfg_kernel<<<blocks_for(a.n_cfg, 256, 1024), 256, 0, (hipStream_t)stream>>>(a);
+    return check(hipGetLastError(), "est_cfg_kernel");
+}
+int launch_prep1(const EstPrepArgs &a, void *stream) {
+    est_prep1_kernel<<<blocks_for(a.n, 256 * 8, 1024), 256, 0, (hipStream_t)stream>>>(a);
+    return check(hipGetLastError(), "est_prep1_kernel");
+}
+int launch_prep2(const EstPrepArgs &a, void *stream) {
+    est_prep2_kernel<<<blocks_for(a.n, 256, 4096), 256, 0, (hipStream_t)stream>>>(a);
+    return check(hipGetLastError(), "est_prep2_kernel");
+}
+int launch_sim(const EstSimArgs &a, void *stream) {
+    est_sim_kernel<<<a.tile_n, 64, EST_LDS_WORDS64(a.max_src) * 8, (hipStream_t)stream>>>(a);
+    return check(hipGetLastError(), "est_sim_kernel");
+}
+int launch_select(const EstSelectArgs &a, void *stream) {
+    est_select_kernel<<<a.tile_n, 64, 0, (hipStream_t)stream>>>(a);
+    return check(hipGetLastError(), "est_select_kernel");
+}
+
+void *event_create() {
+    hipEvent_t e = nullptr;
+    if (check(hipEventCreate(&e), "hipEventCreate")) return nullptr;
+    return (void *)e;
+}
+void event_destroy(void *ev) { (void)hipEventDestroy((hipEvent_t)ev); }
+int event_record(void *ev, void *stream) { return check(hipEventRecord((hipEvent_t)ev, (hipStream_t)stream), "hipEventRecord"); }
+float event_ms(void *start, void *stop) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, (hipEvent_t)start, (hipEvent_t)stop) != hipSuccess) return 0.f;
+    return ms;
+}
+
+}  // namespace estbe

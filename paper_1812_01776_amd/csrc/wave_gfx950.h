@@ -1,0 +1,68 @@
+// Wavefront-level primitives for gfx950 (64 lanes).  One workgroup is one wavefront.
+// Every function here must be called by all 64 lanes in wave-uniform control flow.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define EST_DEV __device__ __forceinline__
+#define EST_CHECK(cond) ((void)0)
+
+namespace wv {
+
+EST_DEV uint32_t lane() { return threadIdx.x; }
+
+EST_DEV uint64_t ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+
+// value of v in lane src (src may differ per lane)
+EST_DEV uint32_t shfl(uint32_t v, uint32_t src) {
+    return (uint32_t)__builtin_amdgcn_ds_bpermute((int)(src << 2), (int)v);
+}
+
+// value of v in lane l; l must be the same in every lane
+EST_DEV uint32_t bcast(uint32_t v, uint32_t l) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)__builtin_amdgcn_readfirstlane((int)l));
+}
+
+EST_DEV uint32_t uniform(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+
+EST_DEV uint32_t min_u32(uint32_t v) {
+#pragma unroll
+    for (uint32_t d = 32; d >= 1; d >>= 1) {
+        uint32_t o = shfl(v, lane() ^ d);
+        v = o < v ? o : v;
+    }
+    return uniform(v);
+}
+
+EST_DEV uint32_t sum_u32(uint32_t v) {
+#pragma unroll
+    for (uint32_t d = 32; d >= 1; d >>= 1) v += shfl(v, lane() ^ d);
+    return uniform(v);
+}
+
+// exclusive prefix sum over lanes
+EST_DEV uint32_t prefix_excl_u32(uint32_t v) {
+    uint32_t x = v;
+#pragma unroll
+    for (uint32_t d = 1; d < 64; d <<= 1) {
+        uint32_t o = shfl(x, lane() - d);
+        if (lane() >= d) x += o;
+    }
+    return x - v;
+}
+
+// Make earlier memory writes (global and LDS) of any lane visible to later reads of any lane
+// of this wavefront.
+EST_DEV void sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+EST_DEV void lds_add(uint32_t *p, uint32_t v) { atomicAdd(p, v); }
+EST_DEV void atomic_or_u64(uint64_t *p, uint64_t v) { atomicOr((unsigned long long *)p, (unsigned long long)v); }
+EST_DEV void atomic_or_u32(uint32_t *p, uint32_t v) { atomicOr(p, v); }
+EST_DEV void atomic_add_u32(uint32_t *p, uint32_t v) { atomicAdd(p, v); }
+EST_DEV void atomic_max_u32(uint32_t *p, uint32_t v) { atomicMax(p, v); }
+
+}  // namespace wv

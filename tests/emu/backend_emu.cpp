@@ -1,0 +1,132 @@
+// Host back end for the lock-step wavefront emulation (test infrastructure): "device" memory is
+// host memory, a kernel launch runs every wavefront as 64 fibers, one wavefront after the other.
+#include <string.h>
+#include <ucontext.h>
+
+#include <functional>
+#include <string>
+#include <vector>
+
+#include "wave_emu.h"
+#include "../../paper_1812_01776_amd/csrc/est_backend.h"
+#include "../../paper_1812_01776_amd/csrc/est_device.h"
+
+namespace emu {
+
+namespace {
+const size_t STACK = 256 * 1024;
+ucontext_t g_sched, g_ctx[64];
+std::vector<char> g_stacks;
+bool g_done[64];
+uint32_t g_cur;
+uint64_t g_x[2][64];
+uint32_t g_tag[64];
+uint32_t g_nb[64];
+const std::function<void()> *g_body;
+
+void trampoline() {
+    (*g_body)();
+    g_done[g_cur] = true;
+    swapcontext(&g_ctx[g_cur], &g_sched);
+}
+}  // namespace
+
+uint32_t lane() { return g_cur; }
+
+const uint64_t *exchange(uint64_t v, uint32_t tag) {
+    const uint32_t me = g_cur;
+    const uint32_t ph = g_nb[me] & 1u;
+    g_x[ph][me] = v;
+    g_tag[me] = tag;
+    g_nb[me]++;
+    swapcontext(&g_ctx[me], &g_sched);  // wait for the other lanes
+    g_cur = me;
+    return g_x[ph];
+}
+
+void run_wave(const std::function<void()> &body) {
+    if (g_stacks.empty()) g_stacks.resize(64 * STACK);
+    g_body = &body;
+    for (int l = 0; l < 64; ++l) {
+        g_done[l] = false;
+        g_nb[l] = 0;
+        getcontext(&g_ctx[l]);
+        g_ctx[l].uc_stack.ss_sp = g_stacks.data() + (size_t)l * STACK;
+        g_ctx[l].uc_stack.ss_size = STACK;
+        g_ctx[l].uc_link = &g_sched;
+        makecontext(&g_ctx[l], trampoline, 0);
+    }
+    for (;;) {
+        int ndone = 0;
+        for (int l = 0; l < 64; ++l) {
+            if (g_done[l]) { ++ndone; continue; }
+            g_cur = (uint32_t)l;
+            swapcontext(&g_sched, &g_ctx[l]);
+            if (g_done[l]) ++ndone;
+        }
+        if (ndone == 64) break;
+        if (ndone != 0) {
+            fprintf(stderr, "emu: %d lanes left the kernel while others wait in a primitive\n", ndone);
+            abort();
+        }
+        for (int l = 1; l < 64; ++l)
+            if (g_tag[l] != g_tag[0] || g_nb[l] != g_nb[0]) {
+                fprintf(stderr, "emu: lanes diverged at a primitive (lane %d tag %u vs lane 0 tag %u)\n", l, g_tag[l], g_tag[0]);
+                abort();
+            }
+    }
+}
+
+}  // namespace emu
+
+namespace estbe {
+
+static std::string g_err;
+const char *last_error() { return g_err.c_str(); }
+int init() { return 0; }
+void *dmalloc(size_t bytes) {
+    void *p = nullptr;
+    if (posix_memalign(&p, 256, bytes ? bytes : 256)) return nullptr;
+    memset(p, 0xA5, bytes);  // uninitialised device memory is not zero
+    return p;
+}
+void dfree(void *p) { free(p); }
+size_t mem_free() { return (size_t)2 << 30; }
+int h2d(void *d, const void *s, size_t n, void *) { if (n) memcpy(d, s, n); return 0; }
+int d2h(void *d, const void *s, size_t n, void *) { if (n) memcpy(d, s, n); return 0; }
+int d2d(void *d, const void *s, size_t n, void *) { if (n) memcpy(d, s, n); return 0; }
+int zero(void *d, size_t n, void *) { if (n) memset(d, 0, n); return 0; }
+int sync(void *) { return 0; }
+
+int launch_cfg(const EstCfgArgs &a, void *) {
+    for (uint32_t t = 0; t < 7; ++t) estdev::cfg_thread(a, t, 7);
+    return 0;
+}
+int launch_prep1(const EstPrepArgs &a, void *) {
+    for (uint32_t t = 0; t < 7; ++t) estdev::prep1_thread(a, t, 7);
+    return 0;
+}
+int launch_prep2(const EstPrepArgs &a, void *) {
+    for (uint32_t t = 0; t < 7; ++t) estdev::prep2_thread(a, t, 7);
+    return 0;
+}
+int launch_sim(const EstSimArgs &a, void *) {
+    static uint64_t lds[EST_KMAX * 160];
+    for (uint32_t t = 0; t < a.tile_n; ++t) {
+        memset(lds, 0x5A, sizeof lds);
+        emu::run_wave([&] { estdev::sim_wave(a, t, lds); });
+    }
+    return 0;
+}
+int launch_select(const EstSelectArgs &a, void *) {
+    static uint64_t lds[128];
+    for (uint32_t t = 0; t < a.tile_n; ++t) emu::run_wave([&] { estdev::select_wave(a, t, lds); });
+    return 0;
+}
+
+void *event_create() { return malloc(1); }
+void event_destroy(void *e) { free(e); }
+int event_record(void *, void *) { return 0; }
+float event_ms(void *, void *) { return 0.f; }
+
+}  // namespace estbe

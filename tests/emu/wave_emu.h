@@ -1,0 +1,86 @@
+// Lock-step CPU emulation of the 64-lane wavefront primitives (test infrastructure).
+//
+// The device code of the Estimator is written against the wv:: primitives only.  Here every lane is
+// a fiber; a primitive is a rendezvous of all 64 fibers, so lanes advance in lock step between
+// primitives exactly as far as the device code may rely on.  It exists to run the kernel logic on
+// the host with consistency checks (EST_CHECK) enabled; it is never part of the GPU library and
+// the Python binding cannot load it.
+#pragma once
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+
+#define EST_DEV static inline
+#define EST_CHECK(cond)                                                                       \
+    do {                                                                                      \
+        if (!(cond)) {                                                                        \
+            fprintf(stderr, "EST_CHECK failed: %s at %s:%d (lane %u)\n", #cond, __FILE__, __LINE__, wv::lane()); \
+            abort();                                                                          \
+        }                                                                                     \
+    } while (0)
+
+namespace emu {
+uint32_t lane();
+// all 64 lanes deposit v, then every lane may read any lane's value through the returned array
+const uint64_t *exchange(uint64_t v, uint32_t tag);
+}  // namespace emu
+
+namespace wv {
+
+EST_DEV uint32_t lane() { return emu::lane(); }
+
+EST_DEV uint64_t ballot(bool p) {
+    const uint64_t *x = emu::exchange(p ? 1 : 0, 1);
+    uint64_t m = 0;
+    for (int l = 0; l < 64; ++l) m |= (x[l] & 1ull) << l;
+    return m;
+}
+
+EST_DEV uint32_t shfl(uint32_t v, uint32_t src) { return (uint32_t)emu::exchange(v, 2)[src & 63u]; }
+
+EST_DEV uint32_t bcast(uint32_t v, uint32_t l) {
+    const uint64_t *x = emu::exchange(((uint64_t)l << 32) | v, 3);
+    for (int i = 0; i < 64; ++i)
+        if ((uint32_t)(x[i] >> 32) != l) {
+            fprintf(stderr, "bcast: lane index not uniform (%u vs %u)\n", (uint32_t)(x[i] >> 32), l);
+            abort();
+        }
+    if (l >= 64) {
+        fprintf(stderr, "bcast: lane %u out of range\n", l);
+        abort();
+    }
+    return (uint32_t)x[l];
+}
+
+EST_DEV uint32_t uniform(uint32_t v) { return (uint32_t)emu::exchange(v, 4)[0]; }
+
+EST_DEV uint32_t min_u32(uint32_t v) {
+    const uint64_t *x = emu::exchange(v, 5);
+    uint32_t m = 0xFFFFFFFFu;
+    for (int l = 0; l < 64; ++l) m = (uint32_t)x[l] < m ? (uint32_t)x[l] : m;
+    return m;
+}
+
+EST_DEV uint32_t sum_u32(uint32_t v) {
+    const uint64_t *x = emu::exchange(v, 6);
+    uint32_t s = 0;
+    for (int l = 0; l < 64; ++l) s += (uint32_t)x[l];
+    return s;
+}
+
+EST_DEV uint32_t prefix_excl_u32(uint32_t v) {
+    const uint64_t *x = emu::exchange(v, 7);
+    uint32_t s = 0;
+    for (uint32_t l = 0; l < emu::lane(); ++l) s += (uint32_t)x[l];
+    return s;
+}
+
+EST_DEV void sync() { (void)emu::exchange(0, 8); }
+
+EST_DEV void lds_add(uint32_t *p, uint32_t v) { *p += v; }
+EST_DEV void atomic_or_u64(uint64_t *p, uint64_t v) { *p |= v; }
+EST_DEV void atomic_or_u32(uint32_t *p, uint32_t v) { *p |= v; }
+EST_DEV void atomic_add_u32(uint32_t *p, uint32_t v) { *p += v; }
+EST_DEV void atomic_max_u32(uint32_t *p, uint32_t v) { if (v > *p) *p = v; }
+
+}  // namespace wv

@@ -1,0 +1,212 @@
+"""GPU parity: the HIP library against the CPU oracle, bit-exact (all values are integers: per-query
+latency, P99, miss count, cost).  Everything goes through the C ABI of include/estimator.h."""
+import hashlib
+import json
+import os
+
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_1812_01776_amd import estimator as binding
+from paper_1812_01776_amd import workloads
+
+pytestmark = pytest.mark.gpu
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _compare(w, latencies=True, est=None):
+    own = est is None
+    est = est or binding.Estimator(w.parents, w.lat_us, w.cost_uusd_hr)
+    cfg = binding.pack_configs(w.cfg_hw, w.cfg_batch, w.cfg_replicas)
+    got = est.run(w.arrival_us, w.visit_mask, cfg, w.slo_us)
+    ref = oracle.run(w.parents, w.lat_us, w.cost_uusd_hr, w.arrival_us, w.visit_mask, w.cfg_hw, w.cfg_batch,
+                     w.cfg_replicas, w.slo_us, want_latencies=latencies)
+    assert np.array_equal(got["p99_us"].astype(np.uint64), ref["p99_us"])
+    assert np.array_equal(got["miss_count"].astype(np.uint64), ref["miss_count"])
+    assert np.array_equal(got["cost_uusd_hr"], ref["cost_uusd_hr"])
+    if latencies:
+        lat = est.run_latencies(w.arrival_us, w.visit_mask, cfg)
+        assert np.array_equal(lat.astype(np.uint64), ref["latency"])
+    if own:
+        est.close()
+
+
+def _hand_examples():
+    with open(os.path.join(GOLD, "hand_traces.json")) as f:
+        return json.load(f)["examples"]
+
+
+@pytest.mark.parametrize("ex", _hand_examples(), ids=lambda e: e["name"])
+def test_hand_traces(ex):
+    S = len(ex["parents"])
+    Bm = max(len(x) for x in ex["L"])
+    lat = np.array([[list(x) + [x[-1]] * (Bm - len(x))] for x in ex["L"]], dtype=np.uint32)
+    est = binding.Estimator(ex["parents"], lat, np.full((S, 1), 10**6, np.uint64))
+    cfg = binding.pack_configs([[0] * S], [ex["batch"]], [ex["replicas"]])
+    assert est.run_latencies(ex["arrival"], ex["mask"], cfg)[0].tolist() == ex["latency"]
+    r = est.run(ex["arrival"], ex["mask"], cfg, ex["slo"])
+    assert (int(r["p99_us"][0]), int(r["miss_count"][0]), int(r["cost_uusd_hr"][0])) == \
+        (ex["p99"], ex["miss_count"], 10**6 * sum(ex["replicas"]))
+    est.close()
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_random_dags(seed):
+    _compare(workloads.random_case(seed, tie_heavy=(seed % 2 == 0)))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_wide_batches_many_replicas_ties(seed):
+    """R up to 16, B up to 64, several thousand queries (bounded rings wrap, ragged tails), times on a
+    10-us grid so that batches complete together."""
+    _compare(workloads.random_case(100 + seed, S=4, n=6000 + 37 * seed, C=24, max_b=64, max_r=16, tie_heavy=True,
+                                   dag="linear" if seed % 2 else "random"))
+
+
+def test_replica_and_batch_limits():
+    """R = 64 and B = 64, the largest the interface allows."""
+    w = workloads.random_case(7, S=2, n=5000, C=4, max_b=64, max_r=4, dag="linear")
+    w.cfg_replicas[:] = np.array([[64, 1], [64, 64], [1, 64], [33, 17]], np.uint16)
+    w.cfg_batch[:] = np.array([[64, 64], [1, 64], [64, 1], [63, 2]], np.uint8)
+    _compare(w)
+
+
+def test_degenerate_inputs():
+    w = workloads.random_case(3, S=3, n=40, C=3, dag="linear")
+    est = binding.Estimator(w.parents, w.lat_us, w.cost_uusd_hr)
+    cfg = binding.pack_configs(w.cfg_hw, w.cfg_batch, w.cfg_replicas)
+    r = est.run(np.zeros(0, np.uint32), np.zeros(0, np.uint32), cfg, 100)
+    assert r["p99_us"].tolist() == [0, 0, 0] and r["miss_count"].tolist() == [0, 0, 0]
+    assert est.run(w.arrival_us, w.visit_mask, cfg[:0], 100)["p99_us"].shape == (0,)
+    # one query; all queries at the same instant; nobody visits any stage; a stage nobody visits
+    for arr, mask in ((np.array([5], np.uint32), np.array([7], np.uint32)),
+                      (np.full(300, 9, np.uint32), np.full(300, 7, np.uint32)),
+                      (np.arange(50, dtype=np.uint32), np.zeros(50, np.uint32)),
+                      (np.arange(200, dtype=np.uint32) * 3, np.full(200, 5, np.uint32))):
+        w2 = workloads.Workload("deg", w.parents, w.lat_us, w.cost_uusd_hr, arr, mask, w.cfg_hw, w.cfg_batch, w.cfg_replicas, 100)
+        _compare(w2, est=est)
+    with pytest.raises(binding.EstimatorError) as ei:
+        bad = w.arrival_us.copy(); bad[3] = bad[2] - 1
+        est.run(bad, w.visit_mask, cfg, 100)
+    assert ei.value.code == binding.EST_EINVAL
+    est.close()
+
+
+def test_clock_saturates_at_the_horizon():
+    rng = np.random.default_rng(1)
+    n = 4000
+    arr = (np.uint64(3_000_000_000) + np.cumsum(rng.integers(0, 2000, size=n)).astype(np.uint64)).astype(np.uint32)
+    lat = np.zeros((3, 1, 4), np.uint32)
+    lat[:] = np.array([900_000, 1_000_000, 1_100_000, 1_200_000], np.uint32)
+    lat[1] = lat[1] // 3
+    mask = (rng.integers(0, 8, size=n) | 1).astype(np.uint32)
+    w = workloads.Workload("sat", [[], [0], [0, 1]], lat, np.full((3, 1), 5, np.uint64), arr, mask,
+                           np.zeros((3, 3), np.uint8), np.array([[1, 1, 1], [2, 4, 1], [4, 2, 3]], np.uint8),
+                           np.array([[1, 1, 1], [2, 1, 2], [1, 3, 2]], np.uint16), 1000)
+    _compare(w)
+
+
+def test_w1_full():
+    _compare(workloads.w1())
+
+
+def test_w2_full():
+    _compare(workloads.w2())
+
+
+def test_device_pointer_entry_points_and_tiling():
+    """estimator_run_dev / estimator_run_latencies_dev with torch-owned memory, the torch stream, and a
+    caller workspace small enough to force several tiles."""
+    import torch
+    w = workloads.w2().subset(cfg_index=np.arange(0, 1024, 4))
+    est = binding.Estimator(w.parents, w.lat_us, w.cost_uusd_hr)
+    cfg = binding.pack_configs(w.cfg_hw, w.cfg_batch, w.cfg_replicas)
+    dev = torch.device("cuda:0")
+    arr_t = torch.from_numpy(w.arrival_us.view(np.int32)).to(dev)
+    msk_t = torch.from_numpy(w.visit_mask.view(np.int32)).to(dev)
+    cfg_t = torch.from_numpy(cfg.view(np.uint8).reshape(-1)).to(dev)
+    ref = oracle.run(w.parents, w.lat_us, w.cost_uusd_hr, w.arrival_us, w.visit_mask, w.cfg_hw, w.cfg_batch,
+                     w.cfg_replicas, w.slo_us, want_latencies=True)
+    ws = torch.empty(6_000_000, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.Stream(device=dev)
+    with torch.cuda.stream(stream):
+        got = est.run_dev(arr_t, msk_t, cfg_t, w.n_configs, w.slo_us, workspace_t=ws)
+        lat = est.run_latencies_dev(arr_t, msk_t, cfg_t, w.n_configs, workspace_t=ws)
+    assert est.stats()["n_tiles"] > 1
+    assert np.array_equal(got["p99_us"].cpu().numpy().view(np.uint32).astype(np.uint64), ref["p99_us"])
+    assert np.array_equal(got["miss_count"].cpu().numpy().view(np.uint32).astype(np.uint64), ref["miss_count"])
+    assert np.array_equal(got["cost_uusd_hr"].cpu().numpy().view(np.uint64), ref["cost_uusd_hr"])
+    assert np.array_equal(lat.cpu().numpy().view(np.uint32).astype(np.uint64), ref["latency"])
+    est.close()
+
+
+# ----------------------------------------------------------------------------- the large workloads
+
+def _expected(name):
+    with open(os.path.join(GOLD, "expected_%s.json" % name.lower())) as f:
+        return json.load(f)
+
+
+def _check_rows(w, exp, p99, miss, cost, est, lat_rows):
+    """p99/miss/cost: full arrays over all configurations of the sweep; per-query latencies are
+    recomputed for lat_rows of the sampled configurations and compared by SHA-256."""
+    for row in exp["rows"]:
+        c = row["config"]
+        assert int(p99[c]) == row["p99_us"], (c, int(p99[c]), row["p99_us"])
+        assert int(miss[c]) == row["miss_count"], c
+        assert int(cost[c]) == row["cost_uusd_hr"], c
+    rows = exp["rows"][:lat_rows]
+    idx = [r["config"] for r in rows]
+    cfg = binding.pack_configs(w.cfg_hw[idx], w.cfg_batch[idx], w.cfg_replicas[idx])
+    lat = est.run_latencies(w.arrival_us, w.visit_mask, cfg)
+    for i, row in enumerate(rows):
+        assert hashlib.sha256(lat[i].astype("<u4").tobytes()).hexdigest() == row["latency_sha256"], row["config"]
+
+
+def test_w3_full_sweep_sampled_against_oracle():
+    """All 8,192 configurations x 100,000 queries in one call (the launch shape the benchmark uses);
+    48 sampled configurations are compared with stored oracle results (P99, misses, cost, and every
+    per-query latency through its SHA-256), and all configurations with the live oracle on the first
+    2,000 queries."""
+    w = workloads.w3()
+    exp = _expected("W3")
+    assert exp["n_queries"] == w.n_queries and exp["n_configs"] == w.n_configs
+    est = binding.Estimator(w.parents, w.lat_us, w.cost_uusd_hr)
+    cfg = binding.pack_configs(w.cfg_hw, w.cfg_batch, w.cfg_replicas)
+    got = est.run(w.arrival_us, w.visit_mask, cfg, w.slo_us)
+    _check_rows(w, exp, got["p99_us"], got["miss_count"], got["cost_uusd_hr"], est, lat_rows=48)
+    # cost of every configuration has a closed form
+    want_cost = (w.cfg_replicas.astype(np.uint64) * w.cost_uusd_hr[np.arange(5)[None, :], w.cfg_hw]).sum(axis=1)
+    assert np.array_equal(got["cost_uusd_hr"], want_cost)
+    est.close()
+    _compare(w.subset(cfg_index=np.arange(0, 8192, 8), n_queries=2000), latencies=False)
+
+
+@pytest.mark.parametrize("name", ["W4", "W5"])
+def test_w4_w5_sampled_configs_full_trace(name):
+    """The sampled configurations of the 10-stage workloads at the full trace length (1e6 / 2e6
+    queries): P99, misses, cost and every per-query latency (SHA-256) against stored oracle results."""
+    w = workloads.WORKLOADS[name]()
+    exp = _expected(name)
+    assert exp["n_queries"] == w.n_queries and exp["n_configs"] == w.n_configs
+    idx = [r["config"] for r in exp["rows"]]
+    est = binding.Estimator(w.parents, w.lat_us, w.cost_uusd_hr)
+    cfg = binding.pack_configs(w.cfg_hw[idx], w.cfg_batch[idx], w.cfg_replicas[idx])
+    got = est.run(w.arrival_us, w.visit_mask, cfg, w.slo_us)
+    lat = est.run_latencies(w.arrival_us, w.visit_mask, cfg)
+    for i, row in enumerate(exp["rows"]):
+        assert int(got["p99_us"][i]) == row["p99_us"], row["config"]
+        assert int(got["miss_count"][i]) == row["miss_count"], row["config"]
+        assert int(got["cost_uusd_hr"][i]) == row["cost_uusd_hr"], row["config"]
+        assert hashlib.sha256(lat[i].astype("<u4").tobytes()).hexdigest() == row["latency_sha256"], row["config"]
+    est.close()
+
+
+@pytest.mark.parametrize("name", ["W4", "W5"])
+def test_w4_w5_many_configs_short_trace(name):
+    """A spread of 2,048 configurations of each 10-stage sweep on the first 2,000 queries, against the
+    live oracle (P99, misses, cost)."""
+    w = workloads.WORKLOADS[name](n=2000) if name == "W4" else workloads.w5().subset(n_queries=2000)
+    step = w.n_configs // 2048
+    _compare(w.subset(cfg_index=np.arange(0, w.n_configs, step)), latencies=False)
