@@ -1,0 +1,111 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched Estimator on one MI355X.
+
+One step = one pass of the whole hot path (trace scan, per-stage batch-queue scans, merges/joins,
+latencies + miss counts, P99 selection, cost) over every candidate configuration of the workload,
+with all inputs already resident in GPU memory.  Prints one JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload W5]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1)
+    ap.add_argument("--warmup", type=int, default=0)
+    ap.add_argument("--workload", default="W5", choices=["W1", "W2", "W3", "W4", "W5"])
+    ap.add_argument("--cpu-sample", type=int, default=-1, help="configs timed on the CPU oracle (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: candidate configurations are independent, so more GPUs would each take "
+              "a slice of the configurations, but this build runs and reports a single MI355X (--gpus 1).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1812_01776_amd import estimator, workloads
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    w = workloads.WORKLOADS[args.workload]()
+    est = estimator.Estimator(w.parents, w.lat_us, w.cost_uusd_hr)
+    cfg = estimator.pack_configs(w.cfg_hw, w.cfg_batch, w.cfg_replicas)
+    arr_t = torch.from_numpy(w.arrival_us.view(np.int32)).to(dev)
+    msk_t = torch.from_numpy(w.visit_mask.view(np.int32)).to(dev)
+    cfg_t = torch.from_numpy(cfg.view(np.uint8).reshape(-1)).to(dev)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        est.run_dev(arr_t, msk_t, cfg_t, w.n_configs, w.slo_us)
+    torch.cuda.synchronize()
+    sim_ms = sel_ms = 0.0
+    launches = 0
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        res = est.run_dev(arr_t, msk_t, cfg_t, w.n_configs, w.slo_us)
+        st = est.stats()  # HIP-event durations of this step's kernels, on the stream they ran on
+        sim_ms += st["sim_ms"]; sel_ms += st["select_ms"]; launches += st["n_tiles"]
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    sims = w.n_configs * w.n_queries
+    value = sims / (ms_per_step * 1e-3)
+
+    # roofline of the dominant kernel (the simulation kernel): algorithmic bytes = 8 B per stage visit
+    # (one ready time in, one completion time out), per candidate, per launch
+    visits = st["stage_visits"]
+    cfgs_per_launch = w.n_configs * args.steps / launches
+    alg_bytes_per_launch = 8.0 * visits * cfgs_per_launch
+    avg_launch_s = sim_ms * 1e-3 / launches
+    achieved = alg_bytes_per_launch / avg_launch_s / 1e9
+
+    p99 = res["p99_us"].cpu().numpy().view(np.uint32)
+    feasible = int((p99 <= w.slo_us).sum())
+
+    # CPU baseline: the oracle as it stands, single thread, on a bounded sample of the same workload
+    n_sample = args.cpu_sample if args.cpu_sample >= 0 else {"W1": 16, "W2": 256, "W3": 64, "W4": 6, "W5": 4}[args.workload]
+    cpu = None
+    if n_sample > 0:
+        from oracle import oracle
+        rng = np.random.default_rng(7)
+        idx = np.sort(rng.choice(w.n_configs, size=min(n_sample, w.n_configs), replace=False))
+        c0 = time.perf_counter()
+        ref = oracle.run(w.parents, w.lat_us, w.cost_uusd_hr, w.arrival_us, w.visit_mask, w.cfg_hw[idx], w.cfg_batch[idx],
+                         w.cfg_replicas[idx], w.slo_us)
+        c1 = time.perf_counter()
+        ok = (np.array_equal(ref["p99_us"], p99[idx].astype(np.uint64)) and
+              np.array_equal(ref["miss_count"], res["miss_count"].cpu().numpy().view(np.uint32)[idx].astype(np.uint64)))
+        cpu = {"value": len(idx) * w.n_queries / (c1 - c0), "unit": "config*query simulations/s", "cores": 1, "kind": "oracle",
+               "sample": "%d seeded configurations of %s at the full %d queries, one thread" % (len(idx), args.workload, w.n_queries),
+               "matches_gpu": bool(ok)}
+
+    out = {
+        "metric": "config x query simulations/sec on 1 MI355X",
+        "value": value, "unit": "config*query simulations/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32", "data": "synthetic",
+        "config": {"workload": args.workload, "n_configs": w.n_configs, "n_queries": w.n_queries, "n_stages": w.n_stages,
+                   "stage_visits_per_config": visits, "tiles_per_step": launches // args.steps, "feasible_configs": feasible},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "kernel": "est_sim_kernel", "avg_launch_ms": avg_launch_s * 1e3,
+                     "select_kernel_ms_per_step": sel_ms / args.steps},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -90,72 +90,115 @@ EST_DEV uint32_t ring_space(const Ctx &c, int32_t ring, uint32_t wr) {
     return R.cap_mask + 1u - used;
 }
 
-// Ascending bitonic sort of one value per lane.
-EST_DEV uint32_t sort64(uint32_t v) {
+// Ascending bitonic sort of the values of lanes 0 .. width-1 (width a power of two, the same in
+// every lane; lanes beyond it take part but their result is not used).
+EST_DEV uint32_t cmpx(uint32_t v, uint32_t o, uint32_t ln, uint32_t k, uint32_t j) {
+    const bool up = (ln & k) == 0, lower = (ln & j) == 0;
+    const uint32_t mn = umin(v, o), mx = umax(v, o);
+    return (lower == up) ? mn : mx;
+}
+EST_DEV uint32_t sort_lanes(uint32_t v, uint32_t width) {
     const uint32_t ln = wv::lane();
-    for (uint32_t k = 2; k <= 64; k <<= 1)
-        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-            uint32_t o = wv::shfl(v, ln ^ j);
-            bool up = (ln & k) == 0;
-            bool lower = (ln & j) == 0;
-            uint32_t mn = umin(v, o), mx = umax(v, o);
-            v = (lower == up) ? mn : mx;
-        }
+    v = cmpx(v, wv::xor1(v), ln, 2, 1);
+    if (width <= 2) return v;
+    v = cmpx(v, wv::xor2(v), ln, 4, 2);
+    v = cmpx(v, wv::xor1(v), ln, 4, 1);
+    if (width <= 4) return v;
+    v = cmpx(v, wv::xor4(v), ln, 8, 4);
+    v = cmpx(v, wv::xor2(v), ln, 8, 2);
+    v = cmpx(v, wv::xor1(v), ln, 8, 1);
+    if (width <= 8) return v;
+    v = cmpx(v, wv::xor8(v), ln, 16, 8);
+    v = cmpx(v, wv::xor4(v), ln, 16, 4);
+    v = cmpx(v, wv::xor2(v), ln, 16, 2);
+    v = cmpx(v, wv::xor1(v), ln, 16, 1);
+    if (width <= 16) return v;
+    v = cmpx(v, wv::shfl(v, ln ^ 16), ln, 32, 16);
+    v = cmpx(v, wv::xor8(v), ln, 32, 8);
+    v = cmpx(v, wv::xor4(v), ln, 32, 4);
+    v = cmpx(v, wv::xor2(v), ln, 32, 2);
+    v = cmpx(v, wv::xor1(v), ln, 32, 1);
+    if (width <= 32) return v;
+    v = cmpx(v, wv::shfl(v, ln ^ 32), ln, 64, 32);
+    v = cmpx(v, wv::shfl(v, ln ^ 16), ln, 64, 16);
+    v = cmpx(v, wv::xor8(v), ln, 64, 8);
+    v = cmpx(v, wv::xor4(v), ln, 64, 4);
+    v = cmpx(v, wv::xor2(v), ln, 64, 2);
+    v = cmpx(v, wv::xor1(v), ln, 64, 1);
     return v;
 }
 
 // ------------------------------------------------------------------------------------------ SCAN
+//
+// Per-wavefront working set of a scan, in LDS:
+//   in-ring   256 (key, source position) pairs: the next elements of the stage's input stream,
+//             refilled from the source ring in chunks (and filtered on the way, when only some
+//             elements of the source visit the stage);
+//   slots     one per replica: the members of the replica's last batch, sorted by query index,
+//             waiting to be emitted when the batch completes.
+// The replica table lives in registers, lane r holding the r-th replica in order of the time it is
+// free again, so the earliest free replica is lane 0 and batches complete in lane order.
+enum { SCAN_INRING = 256 };
 
-// Emit, in (completion time, query index) order, the batches whose replica-table lanes are in E.
-// Members of a batch wait, sorted by query index, in the replica's slot.  Batches that complete
-// at the same time are merged by query index.  Stops early (returns false) when the output ring
-// cannot take the next group.
-EST_DEV bool scan_emit(const Ctx &c, const EstOp &op, uint64_t E, uint32_t rend, uint32_t &rcnt,
-                       uint64_t *out, uint32_t omask, uint32_t &wr, uint32_t &space, bool &progress) {
+// Emit, in (completion time, query index) order, the batches whose replica-table lanes are in E
+// (ascending lanes = ascending completion time).  Batches that complete at the same time are
+// merged by query index.  Stops early (returns false) when the output ring cannot take the next
+// group.
+EST_DEV bool scan_emit(const EstOp &op, const uint32_t *lslots, uint64_t E, uint32_t rend, uint32_t &rcnt,
+                       uint32_t rslot, uint64_t *out, uint32_t omask, uint32_t &wr, uint32_t &space, bool &progress) {
     const uint32_t ln = wv::lane();
-    const uint32_t *slots = c.slots + op.slot_off;
+    const uint32_t bm = op.b_max;
     while (E) {
-        bool inE = (E >> ln) & 1ull;
-        uint32_t mv = wv::min_u32(inE ? rend : 0xFFFFFFFFu);
-        uint64_t tie = wv::ballot(inE && rend == mv);
-        uint32_t total = wv::sum_u32(((tie >> ln) & 1ull) ? rcnt : 0u);
-        if (total > space) return false;
+        const uint32_t l0 = ctz64(E);
+        const uint32_t mv = wv::bcast(rend, l0);
+        const uint64_t tie = E & wv::ballot(rend == mv);
         const uint64_t tkey = (uint64_t)mv << 32;
-        if (popc64(tie) == 1 || mv == 0xFFFFFFFFu) {
-            // one batch, or batches clamped at the horizon (their relative order cannot matter:
-            // everything downstream of a clamped time is clamped too): concatenate
-            uint32_t base = wr;
-            for (uint64_t m = tie; m; m &= m - 1) {
-                uint32_t r = ctz64(m);
-                uint32_t cr = wv::bcast(rcnt, r);
-                EST_CHECK(cr >= 1 && cr <= op.b_max);
-                if (ln < cr) out[(base + ln) & omask] = tkey | slots[(uint64_t)r * op.b_max + ln];
-                base += cr;
-            }
+        if ((tie & (tie - 1)) == 0) {  // the common case: one batch
+            const uint32_t cr = wv::bcast(rcnt, l0), sl = wv::bcast(rslot, l0);
+            EST_CHECK(cr >= 1 && cr <= bm);
+            if (cr > space) return false;
+            if (ln < cr) out[(wr + ln) & omask] = tkey | lslots[sl * bm + ln];
+            wr += cr;
+            space -= cr;
         } else {
-            // several batches complete together: rank every member among all of them
-            for (uint64_t m = tie; m; m &= m - 1) {
-                uint32_t r = ctz64(m);
-                uint32_t cr = wv::bcast(rcnt, r);
-                uint32_t x = ln < cr ? slots[(uint64_t)r * op.b_max + ln] : 0u;
-                uint32_t rank = ln;
-                for (uint64_t m2 = tie; m2; m2 &= m2 - 1) {
-                    uint32_t r2 = ctz64(m2);
-                    uint32_t c2 = wv::bcast(rcnt, r2);
-                    if (r2 == r || ln >= cr) continue;
-                    const uint32_t *s2 = slots + (uint64_t)r2 * op.b_max;
-                    uint32_t lo = 0, hi = c2;
-                    while (lo < hi) {
-                        uint32_t mid = (lo + hi) >> 1;
-                        if (s2[mid] < x) lo = mid + 1; else hi = mid;
-                    }
-                    rank += lo;
+            uint32_t total = 0;
+            for (uint64_t m = tie; m; m &= m - 1) total += wv::bcast(rcnt, ctz64(m));
+            if (total > space) return false;
+            if (mv == 0xFFFFFFFFu) {
+                // clamped at the horizon: relative order cannot matter (everything downstream of a
+                // clamped time is clamped too): concatenate
+                uint32_t base = wr;
+                for (uint64_t m = tie; m; m &= m - 1) {
+                    const uint32_t r = ctz64(m);
+                    const uint32_t cr = wv::bcast(rcnt, r), sl = wv::bcast(rslot, r);
+                    if (ln < cr) out[(base + ln) & omask] = tkey | lslots[sl * bm + ln];
+                    base += cr;
                 }
-                if (ln < cr) out[(wr + rank) & omask] = tkey | x;
+            } else {
+                // several batches complete together: rank every member among all of them
+                for (uint64_t m = tie; m; m &= m - 1) {
+                    const uint32_t r = ctz64(m);
+                    const uint32_t cr = wv::bcast(rcnt, r), sl = wv::bcast(rslot, r);
+                    const uint32_t x = ln < cr ? lslots[sl * bm + ln] : 0u;
+                    uint32_t rank = ln;
+                    for (uint64_t m2 = tie; m2; m2 &= m2 - 1) {
+                        const uint32_t r2 = ctz64(m2);
+                        const uint32_t c2 = wv::bcast(rcnt, r2), sl2 = wv::bcast(rslot, r2);
+                        if (r2 == r || ln >= cr) continue;
+                        const uint32_t *s2 = lslots + sl2 * bm;
+                        uint32_t lo = 0, hi = c2;
+                        while (lo < hi) {
+                            const uint32_t mid = (lo + hi) >> 1;
+                            if (s2[mid] < x) lo = mid + 1; else hi = mid;
+                        }
+                        rank += lo;
+                    }
+                    if (ln < cr) out[(wr + rank) & omask] = tkey | x;
+                }
             }
+            wr += total;
+            space -= total;
         }
-        wr += total;
-        space -= total;
         if ((tie >> ln) & 1ull) rcnt = 0;
         E &= ~tie;
         progress = true;
@@ -168,19 +211,33 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     const EstPlan &P = *c.P;
     const uint32_t s = op.stage;
     const EstStageCfg sc = c.cfg[s];
-    const uint32_t B = sc.batch, R = sc.replicas;
+    const uint32_t B = sc.batch, R = sc.replicas, bm = op.b_max;
     EST_CHECK(B >= 1 && B <= op.b_max && R >= 1 && R <= op.r_max);
     const uint32_t *Ltab = c.a->lat_us + ((uint64_t)s * c.a->dag->H + sc.hw) * c.a->dag->Bmax;
     const uint32_t Lmine = ln < B ? Ltab[ln] : 0u;  // lane l holds L(l+1)
-    uint32_t *rep_end = c.rep + op.rep_off;
-    uint32_t *rep_cnt = rep_end + op.r_max;
-    // replica table: lane r < R holds replica r: when it is free again, and how many members of
-    // its last batch still wait to be emitted
-    uint32_t rend = ln < R ? rep_end[ln] : 0xFFFFFFFFu;
-    uint32_t rcnt = ln < R ? rep_cnt[ln] : 0u;
-    uint32_t *slots = c.slots + op.slot_off;
+    uint32_t *g_end = c.rep + op.rep_off, *g_cnt = g_end + op.r_max, *g_slot = g_cnt + op.r_max;
+    uint32_t *g_slots = c.slots + op.slot_off;
+    uint64_t *lkey = c.lds;
+    uint32_t *lpos = (uint32_t *)(c.lds + SCAN_INRING);
+    uint32_t *lslots = lpos + SCAN_INRING;
+    const uint8_t *acc = c.a->acc + (uint64_t)op.acc_idx * c.a->acc_stride;
+    const uint64_t below = lanes_below(ln);
+
+    // replica table, sorted by the time the replica is free again
+    const bool isrep = ln < R;
+    uint32_t rend = isrep ? g_end[ln] : 0xFFFFFFFFu;
+    uint32_t rcnt = isrep ? g_cnt[ln] : 0u;
+    uint32_t rslot = isrep ? g_slot[ln] : 0u;
+    for (uint64_t m = wv::ballot(rcnt > 0); m; m &= m - 1) {  // members still waiting: back into LDS
+        const uint32_t l = ctz64(m);
+        const uint32_t cn = wv::bcast(rcnt, l), sl = wv::bcast(rslot, l);
+        if (ln < cn) lslots[sl * bm + ln] = g_slots[sl * bm + ln];
+    }
+    wv::sync();
+
     const View in = view_of(c, op.src_ring[0]);
-    uint32_t rd = c.st[P.rd_off + op.src_edge[0]];
+    uint32_t rraw = c.st[P.rd_off + op.src_edge[0]];  // next source position to read
+    uint32_t lhead = 0, ltail = 0;                     // in-ring: consumed / filled
     const EstRing &OR = P.rings[op.out_ring];
     uint64_t *out = c.rings + OR.off;
     const uint32_t omask = OR.cap_mask;
@@ -189,56 +246,96 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     bool progress = false, finished = false;
 
     for (;;) {
-        const uint32_t avail = in.wr - rd;
-        if (avail == 0) {
+        uint32_t staged = ltail - lhead;
+        if (staged < 64 && rraw != in.wr) {
+            // refill: up to three 64-element windows of the source, loads issued together
+            const uint32_t left = in.wr - rraw;
+            const uint32_t w0 = umin(left, 64u), w1 = left > 64 ? umin(left - 64, 64u) : 0u,
+                           w2 = left > 128 ? umin(left - 128, 64u) : 0u;
+            const uint64_t k0 = ln < w0 ? in.base[(rraw + ln) & in.mask] : 0ull;
+            const uint64_t k1 = ln < w1 ? in.base[(rraw + 64 + ln) & in.mask] : 0ull;
+            const uint64_t k2 = ln < w2 ? in.base[(rraw + 128 + ln) & in.mask] : 0ull;
+            bool a0 = ln < w0, a1 = ln < w1, a2 = ln < w2;
+            if (op.filtered) {
+                a0 = a0 && (acc[(uint32_t)k0] & 1u);
+                a1 = a1 && (acc[(uint32_t)k1] & 1u);
+                a2 = a2 && (acc[(uint32_t)k2] & 1u);
+            }
+            const uint64_t A0 = wv::ballot(a0), A1 = wv::ballot(a1), A2 = wv::ballot(a2);
+            if (a0) { const uint32_t i = (ltail + popc64(A0 & below)) & (SCAN_INRING - 1); lkey[i] = k0; lpos[i] = rraw + ln; }
+            ltail += popc64(A0);
+            if (a1) { const uint32_t i = (ltail + popc64(A1 & below)) & (SCAN_INRING - 1); lkey[i] = k1; lpos[i] = rraw + 64 + ln; }
+            ltail += popc64(A1);
+            if (a2) { const uint32_t i = (ltail + popc64(A2 & below)) & (SCAN_INRING - 1); lkey[i] = k2; lpos[i] = rraw + 128 + ln; }
+            ltail += popc64(A2);
+            rraw += w0 + w1 + w2;
+            EST_CHECK(ltail - lhead <= SCAN_INRING);
+            wv::sync();
+            continue;
+        }
+        if (staged == 0) {
             if (in.fin) {  // input exhausted for good: flush what is still in flight
-                uint64_t E = wv::ballot(rcnt > 0);
-                if (!E || scan_emit(c, op, E, rend, rcnt, out, omask, wr, space, progress)) finished = true;
+                const uint64_t E = wv::ballot(rcnt > 0);
+                if (!E || scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress)) finished = true;
             }
             break;
         }
-        const uint32_t w = umin(avail, 64u);
-        const uint64_t key = ln < w ? in.base[(rd + ln) & in.mask] : ~0ull;
+        const uint32_t w = umin(staged, 64u);
+        const uint64_t key = ln < w ? lkey[(lhead + ln) & (SCAN_INRING - 1)] : ~0ull;
         const uint32_t rdy = (uint32_t)(key >> 32);
         uint32_t q = (uint32_t)key;
-        const bool isrep = ln < R;
-        const uint32_t f = wv::min_u32(isrep ? rend : 0xFFFFFFFFu);  // earliest free replica
-        const uint32_t r0 = wv::bcast(rdy, 0);
+        const uint32_t f = wv::uniform(rend);  // earliest free replica = lane 0
+        const uint32_t r0 = wv::uniform(rdy);
         const uint32_t T = umax(f, r0);  // dispatch time of the next batch
         const uint64_t mm = wv::ballot(ln < umin(w, B) && rdy <= T);
         const uint32_t b = popc64(mm);
         EST_CHECK(b >= 1 && mm == lanes_below(b));
         // The batch is known once it is full, or a later query is seen to be ready only after T,
-        // or no further input can come.
-        const bool decidable = (b == B) || (b < w) || (w == avail && in.fin);
+        // or no further input can come.  (Fewer than 64 staged means the source is drained.)
+        const bool decidable = (b == B) || (b < w) || in.fin;
         if (!decidable) break;
         // everything that completes by T leaves before this batch is dispatched
-        uint64_t E = wv::ballot(isrep && rcnt > 0 && rend <= T);
-        if (E && !scan_emit(c, op, E, rend, rcnt, out, omask, wr, space, progress)) break;
+        const uint64_t E = wv::ballot(isrep && rcnt > 0 && rend <= T);
+        if (E && !scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress)) break;
         // members wait in the replica's slot sorted by query index
-        uint32_t prev = wv::shfl(q, ln - 1);
-        uint64_t uns = wv::ballot(ln > 0 && ln < b && q < prev);
-        if (uns) q = sort64(ln < b ? q : 0xFFFFFFFFu);
-        const uint32_t slot = ctz64(wv::ballot(isrep && rend == f));
-        EST_CHECK(slot < R);
-        if (ln < b) slots[(uint64_t)slot * op.b_max + ln] = q;
-        const uint32_t end = sat_add(T, wv::bcast(Lmine, b - 1));
-        if (ln == slot) {
-            EST_CHECK(rcnt == 0);
-            rend = end;
-            rcnt = b;
+        if (b > 1) {
+            const uint32_t prev = wv::shr1(q);
+            if (wv::ballot(ln > 0 && ln < b && q < prev)) {
+                uint32_t width = 2;
+                while (width < b) width <<= 1;
+                q = sort_lanes(ln < b ? q : 0xFFFFFFFFu, width);
+            }
         }
-        rd += b;
+        const uint32_t slot = wv::uniform(rslot);  // the earliest free replica takes the batch
+        EST_CHECK(wv::uniform(rcnt) == 0 && slot < op.r_max);
+        if (ln < b) lslots[slot * bm + ln] = q;
+        const uint32_t end = sat_add(T, wv::bcast(Lmine, b - 1));
+        // drop lane 0 from the table and insert the new entry so that the table stays sorted
+        const uint32_t p = popc64(wv::ballot(ln >= 1 && isrep && rend <= end));
+        const uint32_t nend = wv::shl1(rend), ncnt = wv::shl1(rcnt), nslot = wv::shl1(rslot);
+        if (ln < p) {
+            rend = nend; rcnt = ncnt; rslot = nslot;
+        } else if (ln == p) {
+            rend = end; rcnt = b; rslot = slot;
+        }
+        lhead += b;
         progress = true;
-        wv::sync();  // slot contents must be visible to a later emission
     }
 
-    if (ln < R) {
-        rep_end[ln] = rend;
-        rep_cnt[ln] = rcnt;
+    // back to memory: the table, the members still waiting, the cursors
+    if (isrep) {
+        g_end[ln] = rend;
+        g_cnt[ln] = rcnt;
+        g_slot[ln] = rslot;
+    }
+    for (uint64_t m = wv::ballot(rcnt > 0); m; m &= m - 1) {
+        const uint32_t l = ctz64(m);
+        const uint32_t cn = wv::bcast(rcnt, l), sl = wv::bcast(rslot, l);
+        if (ln < cn) g_slots[sl * bm + ln] = lslots[sl * bm + ln];
     }
     if (ln == 0) {
-        c.st[P.rd_off + op.src_edge[0]] = rd;
+        // staged but unconsumed elements are read again next time
+        c.st[P.rd_off + op.src_edge[0]] = (ltail != lhead) ? lpos[lhead & (SCAN_INRING - 1)] : rraw;
         c.st[P.wr_off + op.out_ring] = wr;
         if (finished) {
             c.st[P.fin_off + op.out_ring] = 1;
@@ -458,6 +555,11 @@ EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint64_t *lds) {
 
     for (uint32_t i = ln; i < P.state_words; i += 64) c.st[i] = 0;
     for (uint64_t i = ln; i < a.rep_stride; i += 64) c.rep[i] = 0;
+    wv::sync();
+    for (uint32_t opi = 0; opi < P.n_ops; ++opi) {  // every replica starts idle at t = 0 and owns one slot
+        const EstOp &op = P.ops[opi];
+        if (op.type == EST_OP_SCAN && ln < op.r_max) c.rep[op.rep_off + 2 * op.r_max + ln] = ln;
+    }
     {
         uint32_t *cw = (uint32_t *)c.cnt;
         for (uint64_t i = ln; i < a.cnt_stride / 4; i += 64) cw[i] = 0;

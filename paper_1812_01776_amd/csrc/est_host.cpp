@@ -68,6 +68,7 @@ struct PlanOut {
     EstPlan plan;
     Sizes sz;
     uint32_t n_acc = 0;
+    uint32_t lds_bytes = 0;
     uint32_t acc_stage[EST_MAX_STAGES + 1];
     uint8_t acc_slot_of_src[EST_MAX_STAGES + 1][EST_TRACE_BIT + 1];
 };
@@ -95,7 +96,7 @@ int build_plan(estimator *h, const EstStatus &st, uint64_t n, PlanOut &po) {
     std::vector<int32_t> out_ring(S, -1), in_ring(S, -1);
     struct Src { uint32_t n; int32_t ring_src[EST_KMAX]; };  // ring_src: stage index or EST_TRACE_BIT
     std::vector<Src> srcs(S + 1);
-    std::vector<bool> direct(S + 1, false), live(S + 1, false);
+    std::vector<bool> direct(S + 1, false), filtered(S + 1, false), live(S + 1, false);
 
     for (uint32_t c = 0; c <= S; ++c) {
         live[c] = c == S ? true : st.n_visit[c] > 0;
@@ -113,6 +114,8 @@ int build_plan(estimator *h, const EstStatus &st, uint64_t n, PlanOut &po) {
             srcs[c].ring_src[srcs[c].n++] = (int32_t)b;
         }
         direct[c] = c < S && srcs[c].n == 1 && count_of((uint32_t)srcs[c].ring_src[0]) == st.n_visit[c];
+        // one source, but only some of its elements visit the stage: the scan filters while it reads
+        filtered[c] = c < S && srcs[c].n == 1 && !direct[c];
     }
 
     // rings
@@ -120,7 +123,7 @@ int build_plan(estimator *h, const EstStatus &st, uint64_t n, PlanOut &po) {
     for (uint32_t s = 0; s < S; ++s) {
         if (!live[s]) continue;
         out_ring[s] = (int32_t)nr++;
-        if (!direct[s]) in_ring[s] = (int32_t)nr++;
+        if (!direct[s] && !filtered[s]) in_ring[s] = (int32_t)nr++;
     }
     P.n_rings = nr;
 
@@ -137,7 +140,7 @@ int build_plan(estimator *h, const EstStatus &st, uint64_t n, PlanOut &po) {
 
     for (uint32_t c = 0; c <= S; ++c) {
         if (!live[c]) continue;
-        if (c == S || !direct[c]) {
+        if (c == S || (!direct[c] && !filtered[c])) {
             EstOp &op = P.ops[no++];
             op.type = c == S ? EST_OP_LAT : EST_OP_MERGE;
             op.stage = c;
@@ -162,7 +165,12 @@ int build_plan(estimator *h, const EstStatus &st, uint64_t n, PlanOut &po) {
             op.type = EST_OP_SCAN;
             op.stage = c;
             op.n_src = 1;
-            op.src_ring[0] = direct[c] ? ring_of_src(srcs[c].ring_src[0]) : in_ring[c];
+            op.src_ring[0] = (direct[c] || filtered[c]) ? ring_of_src(srcs[c].ring_src[0]) : in_ring[c];
+            op.filtered = filtered[c] ? 1 : 0;
+            if (filtered[c]) {
+                op.acc_idx = po.n_acc;
+                po.acc_stage[po.n_acc++] = c;
+            }
             op.src_edge[0] = ne;
             if (!add_consumer(op.src_ring[0], ne)) return fail(h, EST_EUNSUPPORTED, "too many consumers of one stream");
             ++ne;
@@ -170,7 +178,7 @@ int build_plan(estimator *h, const EstStatus &st, uint64_t n, PlanOut &po) {
             op.r_max = st.r_max[c];
             op.b_max = st.b_max[c];
             op.rep_off = (uint32_t)po.sz.rep_words;
-            po.sz.rep_words += 2ull * op.r_max;
+            po.sz.rep_words += 3ull * op.r_max;
             op.slot_off = po.sz.slot_words;
             po.sz.slot_words += (uint64_t)op.r_max * op.b_max;
         }
@@ -179,6 +187,7 @@ int build_plan(estimator *h, const EstStatus &st, uint64_t n, PlanOut &po) {
     P.n_edges = ne;
     P.max_src = 1;
     for (uint32_t i = 0; i < no; ++i) P.max_src = std::max(P.max_src, P.ops[i].n_src);
+    po.lds_bytes = (uint32_t)align_up(std::max<uint64_t>(EST_LDS_MERGE_BYTES(P.max_src), EST_LDS_SCAN_BYTES(max_rb)), 256);
 
     // ring capacities: a stream read by several operations may have to hold the whole skew between
     // them (one branch of a fork can lag another by the length of its simulated queue), so it gets
@@ -379,6 +388,7 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
             sa.slo_us = slo_us;
             sa.lat_by_qid = mode == MODE_LAT;
             sa.max_src = po.plan.max_src;
+            sa.lds_bytes = po.lds_bytes;
             sa.state = (uint32_t *)(ws + o_state);  sa.state_stride = po.sz.state_words;
             sa.rings = (uint64_t *)(ws + o_rings);  sa.ring_stride = po.sz.ring_elems;
             sa.rep = (uint32_t *)(ws + o_rep);      sa.rep_stride = po.sz.rep_words;

@@ -12,7 +12,8 @@
 #define EST_MAX_CONS 36         // consumers of one ring
 #define EST_TRACE_BIT 32        // bit of the "arrival trace" pseudo-source in a source set
 #define EST_SRC_TRACE (-1)
-#define EST_LDS_WORDS64(k) ((k) * 160u)   // LDS of one wavefront in 8-byte words for a k-source merge
+#define EST_LDS_MERGE_BYTES(k) ((k) * 1280u)          // LDS of one wavefront for a k-source merge
+#define EST_LDS_SCAN_BYTES(rb) (3072u + 4u * (rb))      // ... for a scan whose replica slots hold rb members
 
 enum { EST_OP_SCAN = 0, EST_OP_MERGE = 1, EST_OP_LAT = 2 };
 
@@ -38,7 +39,7 @@ struct EstOp {
     uint32_t r_max;               // SCAN: replica table width (largest replica count of the stage in this run)
     uint64_t slot_off;            // SCAN: word offset of the member slots inside one candidate's slot area
     uint32_t b_max;               // SCAN: slot width (largest max-batch of the stage in this run)
-    uint32_t pad;
+    uint32_t filtered;            // SCAN: only the source elements whose accept mask has bit 0 set visit the stage
 };
 
 struct EstPlan {
@@ -89,7 +90,7 @@ struct EstSimArgs {
     uint32_t slo_us;
     uint32_t lat_by_qid;           // 1: latencies indexed by query (checking mode)
     uint32_t max_src;              // widest merge of the plan (sizes the LDS)
-    uint32_t pad;
+    uint32_t lds_bytes;            // LDS per wavefront
     // per-candidate scratch, candidate t at base + t * stride
     uint32_t *state;    uint64_t state_stride;   // words
     uint64_t *rings;    uint64_t ring_stride;    // elements

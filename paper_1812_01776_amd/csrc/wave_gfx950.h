@@ -23,6 +23,19 @@ EST_DEV uint32_t bcast(uint32_t v, uint32_t l) {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)__builtin_amdgcn_readfirstlane((int)l));
 }
 
+// value of lane-1 (lane 0 keeps its own) / of lane+1 (lane 63 keeps its own)
+EST_DEV uint32_t shr1(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x138, 0xF, 0xF, false); }
+EST_DEV uint32_t shl1(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x130, 0xF, 0xF, false); }
+// value of lane ^ 1, ^ 2, ^ 4, ^ 8 (data-parallel-primitive moves inside a row of 16 lanes)
+EST_DEV uint32_t xor1(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xF, 0xF, false); }
+EST_DEV uint32_t xor2(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xF, 0xF, false); }
+EST_DEV uint32_t xor8(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x128, 0xF, 0xF, false); }
+EST_DEV uint32_t xor4(uint32_t v) {
+    const uint32_t down = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x124, 0xF, 0xF, false);  // from lane-4 (mod 16)
+    const uint32_t up = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x12C, 0xF, 0xF, false);    // from lane+4 (mod 16)
+    return (threadIdx.x & 4u) ? down : up;
+}
+
 EST_DEV uint32_t uniform(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
 
 EST_DEV uint32_t min_u32(uint32_t v) {

@@ -111,7 +111,8 @@ int launch_prep2(const EstPrepArgs &a, void *) {
     return 0;
 }
 int launch_sim(const EstSimArgs &a, void *) {
-    static uint64_t lds[EST_KMAX * 160];
+    static uint64_t lds[(64 * 1024) / 8];
+    if (a.lds_bytes > sizeof lds) abort();
     for (uint32_t t = 0; t < a.tile_n; ++t) {
         memset(lds, 0x5A, sizeof lds);
         emu::run_wave([&] { estdev::sim_wave(a, t, lds); });

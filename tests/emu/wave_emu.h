@@ -52,6 +52,13 @@ EST_DEV uint32_t bcast(uint32_t v, uint32_t l) {
     return (uint32_t)x[l];
 }
 
+EST_DEV uint32_t shr1(uint32_t v) { const uint64_t *x = emu::exchange(v, 9); uint32_t l = emu::lane(); return l == 0 ? v : (uint32_t)x[l - 1]; }
+EST_DEV uint32_t shl1(uint32_t v) { const uint64_t *x = emu::exchange(v, 10); uint32_t l = emu::lane(); return l == 63 ? v : (uint32_t)x[l + 1]; }
+EST_DEV uint32_t xor1(uint32_t v) { return (uint32_t)emu::exchange(v, 11)[emu::lane() ^ 1u]; }
+EST_DEV uint32_t xor2(uint32_t v) { return (uint32_t)emu::exchange(v, 12)[emu::lane() ^ 2u]; }
+EST_DEV uint32_t xor4(uint32_t v) { return (uint32_t)emu::exchange(v, 13)[emu::lane() ^ 4u]; }
+EST_DEV uint32_t xor8(uint32_t v) { return (uint32_t)emu::exchange(v, 14)[emu::lane() ^ 8u]; }
+
 EST_DEV uint32_t uniform(uint32_t v) { return (uint32_t)emu::exchange(v, 4)[0]; }
 
 EST_DEV uint32_t min_u32(uint32_t v) {

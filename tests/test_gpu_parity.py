@@ -32,6 +32,24 @@ def _compare(w, latencies=True, est=None):
         est.close()
 
 
+def test_wave_primitive_lane_layout():
+    """The data-parallel-primitive moves the kernels rely on (lane +-1, lane ^ 1/2/4/8) and the bitonic
+    network built from them, checked lane by lane on the device (in-bounds, one wavefront)."""
+    import ctypes
+    lib = binding.load_library()
+    out = np.zeros((12, 64), np.uint32)
+    assert lib.est_selftest_wave(ctypes.c_void_p(out.ctypes.data)) == 0
+    ln = np.arange(64)
+    v = 7 * ln + 3
+    assert out[0].tolist() == [3] + v[:-1].tolist()
+    assert out[1].tolist() == v[1:].tolist() + [int(v[63])]
+    for row, j in ((2, 1), (3, 2), (4, 4), (5, 8)):
+        assert out[row].tolist() == v[ln ^ j].tolist(), j
+    scr = (ln * 37 + 11) & 63
+    for i, width in enumerate((2, 4, 8, 16, 32, 64)):
+        assert out[6 + i][:width].tolist() == sorted(scr[:width].tolist()), width
+
+
 def _hand_examples():
     with open(os.path.join(GOLD, "hand_traces.json")) as f:
         return json.load(f)["examples"]
