@@ -51,13 +51,13 @@ def main():
     for _ in range(args.warmup):
         est.run_dev(arr_t, msk_t, cfg_t, w.n_configs, w.slo_us)
     torch.cuda.synchronize()
-    sim_ms = sel_ms = 0.0
+    sim_ms = 0.0
     launches = 0
     t0 = time.perf_counter()
     for _ in range(args.steps):
         res = est.run_dev(arr_t, msk_t, cfg_t, w.n_configs, w.slo_us)
         st = est.stats()  # HIP-event durations of this step's kernels, on the stream they ran on
-        sim_ms += st["sim_ms"]; sel_ms += st["select_ms"]; launches += st["n_tiles"]
+        sim_ms += st["sim_ms"]; launches += st["n_launches"]
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -98,10 +98,9 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32", "data": "synthetic",
         "config": {"workload": args.workload, "n_configs": w.n_configs, "n_queries": w.n_queries, "n_stages": w.n_stages,
-                   "stage_visits_per_config": visits, "tiles_per_step": launches // args.steps, "feasible_configs": feasible},
+                   "stage_visits_per_config": visits, "scratch_slots": st["n_slots"], "feasible_configs": feasible},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "kernel": "est_sim_kernel", "avg_launch_ms": avg_launch_s * 1e3,
-                     "select_kernel_ms_per_step": sel_ms / args.steps},
+                     "traffic": None, "kernel": "est_sim_kernel", "avg_launch_ms": avg_launch_s * 1e3},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -89,10 +89,9 @@ typedef struct {
 
 /* Timing of the most recent run, measured with HIP events on the run's stream. */
 typedef struct {
-    uint32_t n_tiles;         /* kernel launches of the simulation kernel (one per tile of candidates) */
-    uint32_t tile_configs;    /* candidates per full tile                                             */
-    float sim_ms;             /* summed duration of the simulation kernel launches                    */
-    float select_ms;          /* summed duration of the P99 selection kernel launches                 */
+    uint32_t n_launches;      /* launches of the simulation kernel                                    */
+    uint32_t n_slots;         /* wavefronts (each with its own scratch) that shared the candidates    */
+    float sim_ms;             /* duration of the simulation kernel (simulation + P99 selection)       */
     float prep_ms;            /* trace / configuration preprocessing kernels                          */
     uint64_t stage_visits;    /* sum over stages of queries visiting the stage (per candidate)        */
     uint64_t workspace_bytes; /* device scratch used                                                  */
@@ -121,8 +120,8 @@ int estimator_run(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_
  * The same with every array already in GPU memory: trace->arrival_us, trace->visit_mask,
  * configs and the three arrays of out are DEVICE pointers (the structs themselves live on the
  * host).  workspace is a device scratch buffer of workspace_bytes bytes owned by the caller, or
- * NULL to let the library allocate (and cache in the handle) what it needs; with a caller
- * workspace the candidates are processed in as many tiles as fit.  hip_stream is a hipStream_t
+ * NULL to let the library allocate (and cache in the handle) what it needs; a smaller workspace
+ * means fewer wavefronts share the candidates (scratch is per wavefront, not per candidate).  hip_stream is a hipStream_t
  * (NULL = the default stream); all work is enqueued on it and the call returns after that work
  * has completed.  Same errors as estimator_run; EST_ENOMEM if the workspace cannot hold one
  * candidate.
@@ -144,9 +143,9 @@ int estimator_run_latencies_dev(estimator_t *h, const est_trace_t *trace,
                                 void *workspace, uint64_t workspace_bytes, void *hip_stream);
 
 /*
- * Device scratch, in bytes, that lets estimator_run_dev process n_cfg candidates of an n-query
- * trace in a single tile (an upper bound: it assumes every stage forks).  Smaller workspaces work
- * with more tiles.  Returns 0 on a NULL handle.
+ * Device scratch, in bytes, that gives every one of n_cfg candidates of an n-query trace its own
+ * wavefront (an upper bound: it assumes every stage forks).  Smaller workspaces work, with fewer
+ * wavefronts.  Returns 0 on a NULL handle.
  */
 uint64_t estimator_workspace_bytes(const estimator_t *h, uint64_t n, uint64_t n_cfg);
 

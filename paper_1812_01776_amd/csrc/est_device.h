@@ -215,11 +215,15 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     EST_CHECK(B >= 1 && B <= op.b_max && R >= 1 && R <= op.r_max);
     const uint32_t *Ltab = c.a->lat_us + ((uint64_t)s * c.a->dag->H + sc.hw) * c.a->dag->Bmax;
     const uint32_t Lmine = ln < B ? Ltab[ln] : 0u;  // lane l holds L(l+1)
+    const uint32_t L1 = wv::bcast(Lmine, 0);
+    // the light-load shortcut below needs: no batch is faster than a single query
+    const bool mono = wv::ballot(ln < B && Lmine < L1) == 0;
     uint32_t *g_end = c.rep + op.rep_off, *g_cnt = g_end + op.r_max, *g_slot = g_cnt + op.r_max;
     uint32_t *g_slots = c.slots + op.slot_off;
     uint64_t *lkey = c.lds;
     uint32_t *lpos = (uint32_t *)(c.lds + SCAN_INRING);
-    uint32_t *lslots = lpos + SCAN_INRING;
+    uint32_t *ltab = lpos + SCAN_INRING;   // 4 x 64 words: staging for re-sorting the replica table, group ends
+    uint32_t *lslots = ltab + 256;
     const uint8_t *acc = c.a->acc + (uint64_t)op.acc_idx * c.a->acc_stride;
     const uint64_t below = lanes_below(ln);
 
@@ -244,6 +248,8 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     uint32_t wr = c.st[P.wr_off + op.out_ring];
     uint32_t space = ring_space(c, op.out_ring, wr);
     bool progress = false, finished = false;
+    uint32_t fp_skip = 0;  // general batches still to do before the light-load shortcut is tried again
+    uint32_t d_gen = 0, d_gene = 0, d_fp = 0, d_fpe = 0, d_b1 = 0, d_b1e = 0;  // diagnostics
 
     for (;;) {
         uint32_t staged = ltail - lhead;
@@ -284,6 +290,160 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         const uint64_t key = ln < w ? lkey[(lhead + ln) & (SCAN_INRING - 1)] : ~0ull;
         const uint32_t rdy = (uint32_t)(key >> 32);
         uint32_t q = (uint32_t)key;
+        if (B == 1) {
+            // Maximum batch size 1: every query is its own batch and the service time is the constant
+            // L(1), so completions keep the input order and query i runs on the replica that served
+            // query i-R:  end_i = max(ready_i, end_{i-R}) + L(1).  The sorted replica table is exactly
+            // (end_{i-R}, ..., end_{i-1}), so a whole window is evaluated at once with a max-plus
+            // scan of stride R.  Nothing waits in slots: results are written out immediately.
+            uint32_t x = sat_add(umax(rdy, isrep ? rend : 0u), L1);
+            for (uint32_t d = R, mul = 1; d < 64; d <<= 1, mul <<= 1) {
+                const uint32_t y = wv::shfl(x, ln - d);
+                const uint32_t inc = (uint64_t)mul * L1 > 0xFFFFFFFFull ? 0xFFFFFFFFu : mul * L1;
+                if (ln >= d) x = umax(x, sat_add(y, inc));
+            }
+            // Batches left waiting by a general step complete no later than anything that follows
+            // (constant service time), so they can be written out now -- except those that tie with
+            // the first new completion time, which have to be merged with it by query index.
+            const uint32_t x0 = wv::uniform(x);
+            const uint64_t pend = wv::ballot(rcnt > 0);
+            const uint64_t early = wv::ballot(rcnt > 0 && rend < x0);
+            if (early && !scan_emit(op, lslots, early, rend, rcnt, rslot, out, omask, wr, space, progress)) break;
+            // keep back the trailing run of equal completion times (it may continue in the next
+            // window and has to come out ordered by query index), unless this is the very end
+            const uint32_t xp = wv::shr1(x);
+            const uint32_t qp = wv::shr1(q);
+            const uint64_t bnd = wv::ballot(ln > 0 && ln < w && x != xp) | 1ull;  // starts of runs
+            const bool last = staged <= 64 && rraw == in.wr && in.fin;
+            uint32_t m = umin(w, space);
+            if (!(last && m == w)) m = 63u - (uint32_t)__builtin_clzll(bnd & lanes_below(m + 1));
+            const uint64_t inv = wv::ballot(ln > 0 && ln < m && x == xp && q < qp);
+            if (m > 0 && inv == 0 && pend == early) {
+                if (ln < m) out[(wr + ln) & omask] = ((uint64_t)x << 32) | q;
+                wr += m;
+                space -= m;
+                // the table becomes the last R completion times
+                ++d_b1; d_b1e += m;
+                const uint32_t keep = R > m ? R - m : 0u;  // old entries that stay
+                const uint32_t told = wv::shfl(rend, ln + m);
+                const uint32_t tnew = wv::shfl(x, ln + m - R);
+                if (isrep) rend = ln < keep ? told : tnew;
+                lhead += m;
+                progress = true;
+                continue;
+            }
+            if (space == 0) break;
+            // a whole window of equal times, or equal times out of query order: one general step
+        } else if (mono && fp_skip == 0) {
+            // Light load: as long as every group of queries that become ready at the same instant
+            // finds an idle replica at that instant and fits one batch, each group is one batch started
+            // at its ready time r and finished at r + L(group size).  If each batch also finishes
+            // before any later one possibly can, the output keeps the input order, and a whole run of
+            // groups is evaluated at once and written out immediately (nothing waits in slots).  The p replicas idle at the first
+            // ready time serve the groups in turn; replicas still busy are left alone, and the run
+            // stops before it would overtake a busy replica's unwritten batch.
+            const uint32_t r0 = wv::uniform(rdy);
+            const uint64_t E0 = wv::ballot(isrep && rcnt > 0 && rend <= r0);
+            if (E0 && !scan_emit(op, lslots, E0, rend, rcnt, rslot, out, omask, wr, space, progress)) break;
+            const uint32_t p = popc64(wv::ballot(isrep && rend <= r0));  // a prefix of the sorted table
+            uint32_t m = 0;
+            if (p > 0) {
+                const uint32_t rprev = wv::shr1(rdy);
+                const uint64_t heads = wv::ballot(ln < w && (ln == 0 || rdy != rprev));  // first query of each group
+                const uint64_t upto = below | (1ull << ln);
+                const uint32_t bid = popc64(heads & upto) - 1u;                // group index of this lane
+                const uint32_t start = 63u - (uint32_t)__builtin_clzll(heads & upto);
+                const uint64_t later = ln == 63 ? 0ull : (heads >> (ln + 1));
+                const uint32_t nh = later ? ln + 1 + ctz64(later) : w;         // where the next group starts
+                const uint32_t g = nh - start;
+                const bool final = staged <= 64 && rraw == in.wr && in.fin;
+                const uint32_t e = sat_add(rdy, wv::shfl(Lmine, g - 1));       // (L is 0 beyond B: rejected below)
+                uint32_t *lend = ltab + 192;                                   // completion time of each group
+                if (ln < w && ln == start) lend[bid] = e;
+                wv::sync();
+                // Batches of busy replicas that still wait to be written (all end after r0) are woven
+                // into the output where their completion time falls.  Equal completion times would have
+                // to be ordered by query index: the run stops short of any such tie.
+                const uint64_t busyp = wv::ballot(isrep && rcnt > 0);
+                const uint32_t rend_next = wv::shl1(rend);
+                const uint32_t rcnt_next = wv::shl1(rcnt);
+                const uint64_t tiep = wv::ballot(isrep && ln + 1 < R && rend > r0 && rend == rend_next && (rcnt > 0 || rcnt_next > 0));
+                const uint32_t ecap = tiep ? wv::bcast(rend, ctz64(tiep)) : 0xFFFFFFFFu;
+                bool ok = ln < w && e < ecap && g <= B;  // (ecap <= 2^32-1: a clamped time never passes)
+                for (uint64_t pm = busyp; pm; pm &= pm - 1) {
+                    const uint32_t ep = wv::bcast(rend, ctz64(pm));
+                    ok = ok && e != ep;
+                }
+                ok = ok && (nh < w || final);                            // the whole group is in view
+                ok = ok && (bid < p || lend[bid - p] <= rdy);            // an idle replica, first come first served
+                // written out at once, so it must finish before anything later possibly can: any later
+                // batch starts no earlier than the next group's ready time and takes at least L(1)
+                const uint32_t rnh = wv::shfl(rdy, nh);
+                ok = ok && (nh >= w || e < sat_add(rnh, L1));
+                const uint64_t okm = wv::ballot(ok);
+                m = okm == ~0ull ? 64u : ctz64(~okm);                    // (a group is accepted or rejected as a whole)
+                // waiting batches that complete before the last accepted completion go out with the run
+                uint32_t shift = 0, extra = 0;
+                uint64_t woven = 0;
+                if (m > 0 && busyp) {
+                    const uint32_t elast = wv::bcast(e, m - 1);
+                    for (uint64_t pm = busyp; pm; pm &= pm - 1) {
+                        const uint32_t j = ctz64(pm);
+                        const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j);
+                        if (ej >= elast) break;  // sorted: the rest complete later and keep waiting
+                        woven |= 1ull << j;
+                        extra += cj;
+                        if (ej < e) shift += cj;
+                    }
+                }
+                if (m + extra > space) m = 0;  // leave it to the general path (or to the consumer)
+                if (m > 0) {
+                    if (ln < m) out[(wr + ln + shift) & omask] = ((uint64_t)e << 32) | q;
+                    uint32_t before = 0;
+                    for (uint64_t pm = woven; pm; pm &= pm - 1) {
+                        const uint32_t j = ctz64(pm);
+                        const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j), sj = wv::bcast(rslot, j);
+                        const uint32_t pos = wr + before + popc64(wv::ballot(ln < m && e < ej));
+                        if (ln < cj) out[(pos + ln) & omask] = ((uint64_t)ej << 32) | lslots[sj * bm + ln];
+                        before += cj;
+                    }
+                    if ((woven >> ln) & 1ull) rcnt = 0;
+                    wr += m + extra;
+                    space -= m + extra;
+                    // new table: the idle replicas not used (still <= r0), then the last min(nb,p) new
+                    // completion times merged with the busy replicas by time
+                    const uint32_t nb = popc64(heads & lanes_below(m));      // groups accepted
+                    const uint32_t nn = umin(nb, p), na = p - nn, first_new = nb - nn;
+                    const bool is_a = ln >= nn && ln < p;                 // unused idle entry
+                    const bool is_b = isrep && ln >= p;                   // busy entry
+                    const bool is_n = ln < nn;                            // k-th of the last nn new completions
+                    const uint32_t en = is_n ? lend[first_new + ln] : 0u;
+                    uint32_t rank_n = na + ln, rank_b = na + (ln - p);
+                    for (uint64_t bm2 = wv::ballot(is_b); bm2; bm2 &= bm2 - 1) {
+                        const uint32_t j = ctz64(bm2);
+                        const uint32_t ej = wv::bcast(rend, j);
+                        const uint32_t less_new = popc64(wv::ballot(is_n && en < ej));
+                        if (ln == j) rank_b += less_new;
+                        if (is_n && ej <= en) rank_n += 1;
+                    }
+                    // (lane k < nn holds idle entry k, whose slot the k-th new entry inherits)
+                    if (is_a) { ltab[ln - nn] = rend; ltab[64 + ln - nn] = 0; ltab[128 + ln - nn] = rslot; }
+                    if (is_b) { ltab[rank_b] = rend; ltab[64 + rank_b] = rcnt; ltab[128 + rank_b] = rslot; }
+                    if (is_n) { ltab[rank_n] = en; ltab[64 + rank_n] = 0; ltab[128 + rank_n] = rslot; }
+                    wv::sync();
+                    if (isrep) { rend = ltab[ln]; rcnt = ltab[64 + ln]; rslot = ltab[128 + ln]; }
+                    wv::sync();
+                    lhead += m;
+                    progress = true;
+                }
+            }
+            ++d_fp; d_fpe += m;
+            if (m < 3) fp_skip = 6;  // not the regime for this shortcut: leave it alone for a few batches
+            if (m > 0) continue;
+            if (space == 0) break;
+        }
+        if (fp_skip) --fp_skip;
+        ++d_gen;
         const uint32_t f = wv::uniform(rend);  // earliest free replica = lane 0
         const uint32_t r0 = wv::uniform(rdy);
         const uint32_t T = umax(f, r0);  // dispatch time of the next batch
@@ -319,9 +479,17 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             rend = end; rcnt = b; rslot = slot;
         }
         lhead += b;
+        d_gene += b;
         progress = true;
     }
 
+    if (c.a->dbg_ticks && ln == 0) {
+        uint64_t *dc = c.a->status->dbg_cnt;
+        wv::atomic_add_u64(dc + 0, d_gen); wv::atomic_add_u64(dc + 1, d_fp); wv::atomic_add_u64(dc + 2, d_fpe);
+        wv::atomic_add_u64(dc + 3, d_b1); wv::atomic_add_u64(dc + 4, d_b1e); wv::atomic_add_u64(dc + 7, 1);
+        wv::atomic_add_u64(dc + 8 + s, d_gen); wv::atomic_add_u64(dc + 8 + EST_MAX_STAGES + s, d_gene);
+        wv::atomic_add_u64(dc + 8 + 2 * EST_MAX_STAGES + s, d_fpe + d_b1e);
+    }
     // back to memory: the table, the members still waiting, the cursors
     if (isrep) {
         g_end[ln] = rend;
@@ -366,7 +534,8 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     uint32_t *spos = (uint32_t *)(c.lds + 2 * P.max_src * 64);
     const uint64_t below = lanes_below(ln);
 
-    uint32_t raw[EST_KMAX];
+    // small per-source tables (the same values in every lane) kept in LDS rather than in private memory
+    uint32_t *raw = spos + P.max_src * 64, *nst = raw + EST_KMAX, *cur = nst + EST_KMAX, *m_src = cur + EST_KMAX;
     for (uint32_t j = 0; j < K; ++j) raw[j] = c.st[P.rd_off + op.src_edge[j]];
     uint64_t *out = nullptr;
     uint32_t omask = 0, wr, space = 0xFFFFFFFFu;
@@ -385,7 +554,6 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     for (;;) {
         if (!is_lat && space < 64u * K) break;  // wait for the consumer
         // ---- stage up to 64 accepted elements of every source
-        uint32_t nst[EST_KMAX], cur[EST_KMAX];
         uint32_t more = 0;  // bit j: elements beyond the staged ones may exist in source j
         for (uint32_t j = 0; j < K; ++j) {
             const View sv = view_of(c, op.src_ring[j]);
@@ -437,7 +605,7 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             break;
         }
         // ---- rank every staged element up to the bound among all staged elements
-        uint32_t m_total = 0, m_src[EST_KMAX];
+        uint32_t m_total = 0;
         for (uint32_t j = 0; j < K; ++j) {
             const bool have = ln < nst[j];
             const uint64_t rk = have ? skey[j * 64 + ln] : 0ull;
@@ -463,6 +631,7 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             m_total += m_src[j];
         }
         EST_CHECK(m_total >= 1);
+        if (c.a->dbg_ticks && ln == 0) { wv::atomic_add_u64(c.a->status->dbg_cnt + 5, 1); wv::atomic_add_u64(c.a->status->dbg_cnt + 6, m_total); }
         wv::sync();
         // ---- walk the merged run; a query fed by several sources is passed on at its last appearance
         for (uint32_t base = 0; base < m_total; base += 64) {
@@ -538,18 +707,18 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
 
 // One wavefront = one candidate.  Every loop ends: an operation that consumes or emits nothing
 // reports no progress, and a full round without progress stops the candidate with an error flag.
-EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint64_t *lds) {
+EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *lds) {
     const uint32_t ln = wv::lane();
     const EstPlan &P = *a.plan;
     Ctx c;
     c.a = &a;
     c.P = &P;
-    c.st = a.state + (uint64_t)t * a.state_stride;
-    c.rings = a.rings + (uint64_t)t * a.ring_stride;
-    c.rep = a.rep + (uint64_t)t * a.rep_stride;
-    c.slots = a.slots + (uint64_t)t * a.slot_stride;
-    c.cnt = a.counters + (uint64_t)t * a.cnt_stride;
-    c.lat = a.lat + (uint64_t)t * a.lat_stride;
+    c.st = a.state + (uint64_t)slot * a.state_stride;
+    c.rings = a.rings + (uint64_t)slot * a.ring_stride;
+    c.rep = a.rep + (uint64_t)slot * a.rep_stride;
+    c.slots = a.slots + (uint64_t)slot * a.slot_stride;
+    c.cnt = a.counters + (uint64_t)slot * a.cnt_stride;
+    c.lat = a.lat + (uint64_t)(a.lat_by_qid ? t : slot) * a.lat_stride;
     c.cfg = a.cfg + (uint64_t)t * a.dag->S;
     c.lds = lds;
 
@@ -588,7 +757,7 @@ EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint64_t *lds) {
 // Nearest-rank P99 of one candidate's latencies by a 4-pass radix select (8 bits per pass), one
 // wavefront per candidate, plus the candidate's cost = sum over stages of replicas x price
 // (Section 6, cost model).
-EST_DEV void select_wave(const EstSelectArgs &a, uint32_t t, uint64_t *lds) {
+EST_DEV void select_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *lds) {
     const uint32_t ln = wv::lane();
     const EstStageCfg *cfg = a.cfg + (uint64_t)t * a.dag->S;
     if (ln == 0) {
@@ -598,7 +767,7 @@ EST_DEV void select_wave(const EstSelectArgs &a, uint32_t t, uint64_t *lds) {
         a.cost[t] = cost;
     }
     if (!a.have_lat) return;
-    const uint32_t *lat = a.lat + (uint64_t)t * a.lat_stride;
+    const uint32_t *lat = a.lat + (uint64_t)slot * a.lat_stride;
     uint32_t *hist = (uint32_t *)lds;  // 256 bins
     const uint32_t n = a.n;
     uint32_t k = (uint32_t)(((uint64_t)99 * n + 99) / 100);  // 1-based rank, ceil(0.99 n)
@@ -635,7 +804,25 @@ EST_DEV void select_wave(const EstSelectArgs &a, uint32_t t, uint64_t *lds) {
     }
     if (ln == 0) {
         a.p99[t] = prefix;
-        a.miss[t] = a.state[(uint64_t)t * a.state_stride + a.plan->miss_off];
+        a.miss[t] = a.state[(uint64_t)slot * a.state_stride + a.plan->miss_off];
+    }
+}
+
+// A wavefront takes candidates from the launch's work counter until none is left, simulating each
+// in its own scratch slot and, unless per-query latencies were asked for, selecting the P99 right
+// away from the slot's latency array.
+EST_DEV void slot_loop(const EstSimArgs &a, uint32_t slot, uint64_t *lds) {
+    for (;;) {
+        uint32_t t = 0;
+        if (wv::lane() == 0) t = wv::fetch_add_u32(&a.status->next_cfg, 1u);
+        t = wv::bcast(t, 0);
+        if (t >= a.n_cfg) break;
+        const uint64_t t0 = a.dbg_ticks ? wv::ticks() : 0;
+        if (a.n > 0) sim_wave(a, t, slot, lds);
+        wv::sync();
+        if (!a.lat_by_qid) select_wave(a, t, slot, lds);
+        wv::sync();
+        if (a.dbg_ticks && wv::lane() == 0) a.dbg_ticks[t] = wv::ticks() - t0;
     }
 }
 

@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -216,7 +217,8 @@ int build_plan(estimator *h, const EstStatus &st, uint64_t n, PlanOut &po) {
     P.rd_off = 2 * P.n_rings;
     P.done_off = P.rd_off + P.n_edges;
     P.miss_off = P.done_off + P.n_ops;
-    P.state_words = (uint32_t)align_up(P.miss_off + 2, 4);
+    P.pub_off = P.miss_off + 2;
+    P.state_words = (uint32_t)align_up(P.pub_off + P.n_rings, 4);
     po.sz.state_words = P.state_words;
     po.sz.rep_words = align_up(po.sz.rep_words, 4);
     po.sz.slot_words = align_up(po.sz.slot_words, 4);
@@ -236,6 +238,19 @@ struct EventSet {
 };
 
 enum { MODE_P99 = 0, MODE_LAT = 1 };
+
+struct DevBuf {
+    void *p = nullptr;
+    ~DevBuf() {
+        if (p) estbe::dfree(p);
+    }
+    bool alloc(size_t bytes) {
+        p = estbe::dmalloc(bytes ? bytes : 4);
+        return p != nullptr;
+    }
+};
+
+
 
 int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t *d_mask,
              const est_stage_cfg_t *d_cfg, uint64_t n_cfg, uint32_t slo_us, int mode, uint32_t *d_p99,
@@ -308,7 +323,8 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     uint8_t *ws = (uint8_t *)workspace;
     uint64_t ws_bytes = workspace_bytes;
     if (!ws) {
-        uint64_t want = fixed + per_cfg * n_cfg + 8 * 256;
+        const uint64_t max_slots = std::min<uint64_t>(n_cfg, std::max<uint32_t>(estbe::max_resident_waves(), 1));
+        uint64_t want = fixed + per_cfg * max_slots + 8 * 256;
         uint64_t avail = (uint64_t)estbe::mem_free() + h->ws_bytes;
         uint64_t budget = std::min<uint64_t>(want, avail / 100 * 85);
         if (h->ws_bytes < budget || h->ws_bytes > 2 * budget + (64u << 20)) {
@@ -326,12 +342,14 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     if (ws_bytes < fixed + per_cfg + 8 * 256)
         return fail(h, EST_ENOMEM, "workspace of %llu bytes cannot hold one candidate (%llu + %llu bytes needed)",
                     (unsigned long long)ws_bytes, (unsigned long long)fixed, (unsigned long long)per_cfg);
-    uint64_t tile = std::min<uint64_t>((ws_bytes - fixed - 8 * 256) / per_cfg, n_cfg);
-    // areas of one tile
+    // scratch slots: one per wavefront that works on this launch; more than the device can hold at once
+    // would only wait
+    uint64_t n_slots = std::min<uint64_t>((ws_bytes - fixed - 8 * 256) / per_cfg, n_cfg);
+    n_slots = std::min<uint64_t>(n_slots, std::max<uint32_t>(estbe::max_resident_waves(), 1));
     uint64_t at = fixed;
     auto area = [&](uint64_t bytes_per_cfg) {
         uint64_t a0 = at;
-        at = align_up(at + bytes_per_cfg * tile, 256);
+        at = align_up(at + bytes_per_cfg * n_slots, 256);
         return a0;
     };
     const uint64_t o_state = area(po.sz.state_words * 4);
@@ -356,79 +374,73 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     }
     estbe::event_record(ev_p3, stream);
 
-    // ---- tiles of candidates
+    // ---- the simulation launch
     uint32_t *s_p99 = (uint32_t *)(ws + o_p99);
     uint32_t *s_miss = (uint32_t *)(ws + o_miss);
     uint64_t *s_cost = (uint64_t *)(ws + o_cost);
     if (n == 0 && mode == MODE_P99) {
         if (estbe::zero(s_p99, n_cfg * 4, stream) || estbe::zero(s_miss, n_cfg * 4, stream)) return dev_fail(h, "clear results");
     }
-    std::vector<void *> tev;
-    uint32_t n_tiles = 0;
-    for (uint64_t base = 0; base < n_cfg; base += tile, ++n_tiles) {
-        const uint64_t tn = std::min<uint64_t>(tile, n_cfg - base);
-        void *e0 = evs.make(), *e1 = evs.make(), *e2 = evs.make();
-        if (!e0 || !e1 || !e2) return dev_fail(h, "event create");
-        tev.push_back(e0); tev.push_back(e1); tev.push_back(e2);
-        estbe::event_record(e0, stream);
-        if (n > 0) {
-            EstSimArgs sa;
-            memset(&sa, 0, sizeof sa);
-            sa.plan = h->d_plan;
-            sa.dag = h->d_dag;
-            sa.lat_us = h->d_lat;
-            sa.cost_uusd_hr = h->d_cost;
-            sa.arrival = d_arrival;
-            sa.trace_keys = (const uint64_t *)(ws + o_keys);
-            sa.acc = ws + o_acc;
-            sa.acc_stride = n_pad;
-            sa.cfg = (const EstStageCfg *)d_cfg + base * S;
-            sa.n = (uint32_t)n;
-            sa.tile_n = (uint32_t)tn;
-            sa.slo_us = slo_us;
-            sa.lat_by_qid = mode == MODE_LAT;
-            sa.max_src = po.plan.max_src;
-            sa.lds_bytes = po.lds_bytes;
-            sa.state = (uint32_t *)(ws + o_state);  sa.state_stride = po.sz.state_words;
-            sa.rings = (uint64_t *)(ws + o_rings);  sa.ring_stride = po.sz.ring_elems;
-            sa.rep = (uint32_t *)(ws + o_rep);      sa.rep_stride = po.sz.rep_words;
-            sa.slots = (uint32_t *)(ws + o_slots);  sa.slot_stride = po.sz.slot_words;
-            sa.counters = ws + o_cnt;               sa.cnt_stride = po.sz.cnt_bytes;
-            if (mode == MODE_LAT) {
-                sa.lat = d_lat_out + base * n;
-                sa.lat_stride = n;
-            } else {
-                sa.lat = (uint32_t *)(ws + o_lat);
-                sa.lat_stride = n;
-            }
-            sa.status = h->d_status;
+    // diagnostics: EST_DEBUG_TICKS=<file> dumps how long each candidate's wavefront ran (100 MHz ticks)
+    const char *dbg_path = getenv("EST_DEBUG_TICKS");
+    DevBuf dbg_buf;
+    uint64_t *dbg_ticks = nullptr;
+    if (dbg_path && n > 0 && dbg_buf.alloc(n_cfg * 8)) dbg_ticks = (uint64_t *)dbg_buf.p;
+    void *e0 = evs.make(), *e1 = evs.make();
+    if (!e0 || !e1) return dev_fail(h, "event create");
+    estbe::event_record(e0, stream);
+    {
+        EstSimArgs sa;
+        memset(&sa, 0, sizeof sa);
+        sa.plan = h->d_plan;
+        sa.dag = h->d_dag;
+        sa.lat_us = h->d_lat;
+        sa.cost_uusd_hr = h->d_cost;
+        sa.arrival = d_arrival;
+        sa.trace_keys = (const uint64_t *)(ws + o_keys);
+        sa.acc = ws + o_acc;
+        sa.acc_stride = n_pad;
+        sa.cfg = (const EstStageCfg *)d_cfg;
+        sa.n = (uint32_t)n;
+        sa.n_cfg = (uint32_t)n_cfg;
+        sa.slo_us = slo_us;
+        sa.lat_by_qid = mode == MODE_LAT;
+        sa.max_src = po.plan.max_src;
+        sa.lds_bytes = n > 0 ? po.lds_bytes : 1024;
+        sa.n_slots = (uint32_t)n_slots;
+        sa.have_lat = with_lat ? 1 : 0;
+        sa.state = (uint32_t *)(ws + o_state);  sa.state_stride = po.sz.state_words;
+        sa.rings = (uint64_t *)(ws + o_rings);  sa.ring_stride = po.sz.ring_elems;
+        sa.rep = (uint32_t *)(ws + o_rep);      sa.rep_stride = po.sz.rep_words;
+        sa.slots = (uint32_t *)(ws + o_slots);  sa.slot_stride = po.sz.slot_words;
+        sa.counters = ws + o_cnt;               sa.cnt_stride = po.sz.cnt_bytes;
+        if (mode == MODE_LAT) {
+            sa.lat = d_lat_out;
+            sa.lat_stride = n;
+        } else {
+            sa.lat = (uint32_t *)(ws + o_lat);
+            sa.lat_stride = n;
+        }
+        sa.status = h->d_status;
+        sa.dbg_ticks = dbg_ticks;
+        sa.p99 = s_p99; sa.miss = s_miss; sa.cost = s_cost;
+        if (mode == MODE_P99 || n > 0)
             if (estbe::launch_sim(sa, stream)) return dev_fail(h, "simulation kernel");
-        }
-        estbe::event_record(e1, stream);
-        if (mode == MODE_P99) {
-            EstSelectArgs se;
-            memset(&se, 0, sizeof se);
-            se.plan = h->d_plan;
-            se.dag = h->d_dag;
-            se.cost_uusd_hr = h->d_cost;
-            se.cfg = (const EstStageCfg *)d_cfg + base * S;
-            se.lat = (const uint32_t *)(ws + o_lat);
-            se.lat_stride = n;
-            se.state = (const uint32_t *)(ws + o_state);
-            se.state_stride = po.sz.state_words;
-            se.n = (uint32_t)n;
-            se.tile_n = (uint32_t)tn;
-            se.have_lat = n > 0;
-            se.p99 = s_p99 + base;
-            se.miss = s_miss + base;
-            se.cost = s_cost + base;
-            if (estbe::launch_select(se, stream)) return dev_fail(h, "selection kernel");
-        }
-        estbe::event_record(e2, stream);
     }
+    estbe::event_record(e1, stream);
     EstStatus st2;
     if (estbe::d2h(&st2, h->d_status, sizeof st2, stream) || estbe::sync(stream)) return dev_fail(h, "run");
     if (st2.sim_error) return fail(h, EST_EINTERNAL, "the simulation kernel stopped without finishing a candidate");
+    if (dbg_ticks) {
+        std::vector<uint64_t> ticks(n_cfg);
+        if (!estbe::d2h(ticks.data(), dbg_ticks, n_cfg * 8, stream) && !estbe::sync(stream)) {
+            if (FILE *f = fopen(dbg_path, "wb")) {
+                fwrite(ticks.data(), 8, n_cfg, f);
+                fwrite(st2.dbg_cnt, 8, sizeof st2.dbg_cnt / 8, f);  // then the diagnostic counters
+                fclose(f);
+            }
+        }
+    }
     if (mode == MODE_P99) {
         if (estbe::d2d(d_p99, s_p99, n_cfg * 4, stream) || estbe::d2d(d_miss, s_miss, n_cfg * 4, stream) ||
             estbe::d2d(d_cost, s_cost, n_cfg * 8, stream) || estbe::sync(stream))
@@ -436,12 +448,9 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     }
     est_stats_t &ss = h->stats;
     memset(&ss, 0, sizeof ss);
-    ss.n_tiles = n_tiles;
-    ss.tile_configs = (uint32_t)tile;
-    for (size_t i = 0; i + 2 < tev.size(); i += 3) {
-        ss.sim_ms += estbe::event_ms(tev[i], tev[i + 1]);
-        ss.select_ms += estbe::event_ms(tev[i + 1], tev[i + 2]);
-    }
+    ss.n_launches = 1;
+    ss.n_slots = (uint32_t)n_slots;
+    ss.sim_ms = estbe::event_ms(e0, e1);
     ss.prep_ms = estbe::event_ms(ev_p0, ev_p1) + estbe::event_ms(ev_p2, ev_p3);
     for (uint32_t s = 0; s < S; ++s) ss.stage_visits += st.n_visit[s];
     ss.workspace_bytes = at;
@@ -457,17 +466,6 @@ int check_run_args(estimator *h, const est_trace_t *trace, const est_stage_cfg_t
     if (n_cfg > 0 && !configs) return fail(h, EST_EINVAL, "configs is NULL");
     return EST_OK;
 }
-
-struct DevBuf {
-    void *p = nullptr;
-    ~DevBuf() {
-        if (p) estbe::dfree(p);
-    }
-    bool alloc(size_t bytes) {
-        p = estbe::dmalloc(bytes ? bytes : 4);
-        return p != nullptr;
-    }
-};
 
 }  // namespace
 

@@ -18,15 +18,14 @@ int check(hipError_t e, const char *what) {
     return 1;
 }
 
-// One wavefront per candidate of the tile.
-__global__ __launch_bounds__(64) void est_sim_kernel(EstSimArgs a) {
-    extern __shared__ uint64_t lds[];  // a.lds_bytes: the larger of what a scan and a merge of this plan need
-    if (blockIdx.x < a.tile_n) estdev::sim_wave(a, blockIdx.x, lds);
-}
-
-__global__ __launch_bounds__(64) void est_select_kernel(EstSelectArgs a) {
-    __shared__ uint64_t lds[128];
-    if (blockIdx.x < a.tile_n) estdev::select_wave(a, blockIdx.x, lds);
+// Four wavefronts per workgroup; each wavefront owns one scratch slot and its own part of the LDS
+// and works through candidates until the launch's work counter runs out.
+#define EST_WAVES_PER_BLOCK 4
+__global__ __launch_bounds__(64 * EST_WAVES_PER_BLOCK) void est_sim_kernel(EstSimArgs a) {
+    extern __shared__ uint64_t lds[];  // EST_WAVES_PER_BLOCK x a.lds_bytes
+    const uint32_t wave = threadIdx.x >> 6;
+    const uint32_t slot = blockIdx.x * EST_WAVES_PER_BLOCK + wave;
+    if (slot < a.n_slots) estdev::slot_loop(a, slot, lds + (size_t)wave * (a.lds_bytes / 8));
 }
 
 __global__ __launch_bounds__(256) void est_prep1_kernel(EstPrepArgs a) {
@@ -126,12 +125,16 @@ int launch_prep2(const EstPrepArgs &a, void *stream) {
     return check(hipGetLastError(), "est_prep2_kernel");
 }
 int launch_sim(const EstSimArgs &a, void *stream) {
-    est_sim_kernel<<<a.tile_n, 64, a.lds_bytes, (hipStream_t)stream>>>(a);
+    const uint32_t blocks = (a.n_slots + EST_WAVES_PER_BLOCK - 1) / EST_WAVES_PER_BLOCK;
+    est_sim_kernel<<<blocks, 64 * EST_WAVES_PER_BLOCK, (size_t)a.lds_bytes * EST_WAVES_PER_BLOCK, (hipStream_t)stream>>>(a);
     return check(hipGetLastError(), "est_sim_kernel");
 }
-int launch_select(const EstSelectArgs &a, void *stream) {
-    est_select_kernel<<<a.tile_n, 64, 0, (hipStream_t)stream>>>(a);
-    return check(hipGetLastError(), "est_select_kernel");
+
+uint32_t max_resident_waves() {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    return (uint32_t)cus * 32u;
 }
 
 void *event_create() {
@@ -159,4 +162,14 @@ extern "C" int est_selftest_wave(uint32_t *host_out) {
     rc = rc || check(hipMemcpy(host_out, d, 12 * 64 * 4, hipMemcpyDeviceToHost), "hipMemcpy");
     (void)hipFree(d);
     return rc;
+}
+
+// Workgroups of the simulation kernel that the runtime expects to fit on one compute unit for a
+// given LDS size per wavefront (diagnostics).
+extern "C" int est_debug_occupancy(uint32_t lds_bytes_per_wave) {
+    int blocks = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_kernel, 64 * EST_WAVES_PER_BLOCK,
+                                                     (size_t)lds_bytes_per_wave * EST_WAVES_PER_BLOCK) != hipSuccess)
+        return -1;
+    return blocks;
 }

@@ -12,8 +12,8 @@
 #define EST_MAX_CONS 36         // consumers of one ring
 #define EST_TRACE_BIT 32        // bit of the "arrival trace" pseudo-source in a source set
 #define EST_SRC_TRACE (-1)
-#define EST_LDS_MERGE_BYTES(k) ((k) * 1280u)          // LDS of one wavefront for a k-source merge
-#define EST_LDS_SCAN_BYTES(rb) (3072u + 4u * (rb))      // ... for a scan whose replica slots hold rb members
+#define EST_LDS_MERGE_BYTES(k) ((k) * 1280u + 128u)   // LDS of one wavefront for a k-source merge
+#define EST_LDS_SCAN_BYTES(rb) (4096u + 4u * (rb))      // ... for a scan whose replica slots hold rb members
 
 enum { EST_OP_SCAN = 0, EST_OP_MERGE = 1, EST_OP_LAT = 2 };
 
@@ -40,12 +40,14 @@ struct EstOp {
     uint64_t slot_off;            // SCAN: word offset of the member slots inside one candidate's slot area
     uint32_t b_max;               // SCAN: slot width (largest max-batch of the stage in this run)
     uint32_t filtered;            // SCAN: only the source elements whose accept mask has bit 0 set visit the stage
+    uint32_t rp;                  // SCAN: r_max rounded up to a power of two
+    uint32_t pad;
 };
 
 struct EstPlan {
     uint32_t n_ops, n_rings, n_edges, state_words;
-    // state words of one candidate: wr[n_rings] | fin[n_rings] | rd[n_edges] | opdone[n_ops] | miss
-    uint32_t wr_off, fin_off, rd_off, done_off, miss_off, max_src, pad1, pad2;  // max_src: widest merge
+    // state words of one candidate: wr[n_rings] | fin[n_rings] | rd[n_edges] | opdone[n_ops] | miss, latency count | pub[n_rings]
+    uint32_t wr_off, fin_off, rd_off, done_off, miss_off, max_src, pub_off, pad2;  // max_src: widest merge; pub: published prefix of each ring
     EstOp ops[EST_MAX_OPS];
     EstRing rings[EST_MAX_RINGS];
 };
@@ -61,6 +63,12 @@ struct EstStatus {
     uint32_t bad_cfg;                        // a configuration entry is out of range
     uint32_t last_arrival;
     uint32_t sim_error;                      // set by the simulation kernel on an inconsistency
+    uint32_t next_cfg;                       // work counter: next candidate to hand to a free wavefront
+    uint32_t pad;
+    // diagnostics (only counted when per-candidate timing is requested)
+    uint64_t dbg_cnt[8 + 3 * EST_MAX_STAGES];  // general steps, shortcut steps, shortcut elements, B=1 steps, B=1 elements,
+                                             // merge rounds, merge elements, scan calls; then per stage: general steps,
+                                             // queries in general steps, queries in shortcut steps
 };
 
 struct EstStageCfg {  // same layout as est_stage_cfg_t
@@ -86,12 +94,14 @@ struct EstSimArgs {
     uint64_t acc_stride;           // n_pad
     const EstStageCfg *cfg;        // [n_cfg][S], already offset to the tile
     uint32_t n;                    // queries
-    uint32_t tile_n;               // candidates in this launch
+    uint32_t n_cfg;                // candidates in this launch
     uint32_t slo_us;
     uint32_t lat_by_qid;           // 1: latencies indexed by query (checking mode)
     uint32_t max_src;              // widest merge of the plan (sizes the LDS)
     uint32_t lds_bytes;            // LDS per wavefront
-    // per-candidate scratch, candidate t at base + t * stride
+    uint32_t n_slots;              // wavefronts that share the candidates of this launch, each with its own scratch
+    uint32_t have_lat;             // 1: select P99 from the slot's latency array after each candidate
+    // per-slot scratch, slot k at base + k * stride
     uint32_t *state;    uint64_t state_stride;   // words
     uint64_t *rings;    uint64_t ring_stride;    // elements
     uint32_t *rep;      uint64_t rep_stride;     // words
@@ -99,19 +109,8 @@ struct EstSimArgs {
     uint8_t *counters;  uint64_t cnt_stride;     // bytes
     uint32_t *lat;      uint64_t lat_stride;     // words
     EstStatus *status;
-};
-
-struct EstSelectArgs {
-    const EstPlan *plan;
-    const EstDag *dag;
-    const uint64_t *cost_uusd_hr;
-    const EstStageCfg *cfg;   // tile
-    const uint32_t *lat; uint64_t lat_stride;
-    const uint32_t *state; uint64_t state_stride;
-    uint32_t n, tile_n;
-    uint32_t have_lat;        // 0: only cost (checking mode or empty trace)
-    uint32_t pad;
-    uint32_t *p99; uint32_t *miss; uint64_t *cost;   // tile outputs
+    uint64_t *dbg_ticks;           // optional [n_cfg]: 100 MHz ticks each candidate took (diagnostics)
+    uint32_t *p99; uint32_t *miss; uint64_t *cost;   // [n_cfg] results
 };
 
 struct EstPrepArgs {

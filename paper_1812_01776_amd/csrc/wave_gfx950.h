@@ -9,7 +9,7 @@
 
 namespace wv {
 
-EST_DEV uint32_t lane() { return threadIdx.x; }
+EST_DEV uint32_t lane() { return threadIdx.x & 63u; }
 
 EST_DEV uint64_t ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
 
@@ -33,7 +33,7 @@ EST_DEV uint32_t xor8(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp
 EST_DEV uint32_t xor4(uint32_t v) {
     const uint32_t down = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x124, 0xF, 0xF, false);  // from lane-4 (mod 16)
     const uint32_t up = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x12C, 0xF, 0xF, false);    // from lane+4 (mod 16)
-    return (threadIdx.x & 4u) ? down : up;
+    return (lane() & 4u) ? down : up;
 }
 
 EST_DEV uint32_t uniform(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
@@ -77,5 +77,8 @@ EST_DEV void atomic_or_u64(uint64_t *p, uint64_t v) { atomicOr((unsigned long lo
 EST_DEV void atomic_or_u32(uint32_t *p, uint32_t v) { atomicOr(p, v); }
 EST_DEV void atomic_add_u32(uint32_t *p, uint32_t v) { atomicAdd(p, v); }
 EST_DEV void atomic_max_u32(uint32_t *p, uint32_t v) { atomicMax(p, v); }
+EST_DEV uint32_t fetch_add_u32(uint32_t *p, uint32_t v) { return atomicAdd(p, v); }
+EST_DEV uint64_t ticks() { return wall_clock64(); }
+EST_DEV void atomic_add_u64(uint64_t *p, uint64_t v) { atomicAdd((unsigned long long *)p, (unsigned long long)v); }
 
 }  // namespace wv

@@ -47,9 +47,8 @@ class _Result(ctypes.Structure):
 
 
 class Stats(ctypes.Structure):
-    _fields_ = [("n_tiles", ctypes.c_uint32), ("tile_configs", ctypes.c_uint32), ("sim_ms", ctypes.c_float),
-                ("select_ms", ctypes.c_float), ("prep_ms", ctypes.c_float), ("stage_visits", ctypes.c_uint64),
-                ("workspace_bytes", ctypes.c_uint64)]
+    _fields_ = [("n_launches", ctypes.c_uint32), ("n_slots", ctypes.c_uint32), ("sim_ms", ctypes.c_float),
+                ("prep_ms", ctypes.c_float), ("stage_visits", ctypes.c_uint64), ("workspace_bytes", ctypes.c_uint64)]
 
 
 def load_library(path=LIB_PATH):

@@ -113,17 +113,21 @@ int launch_prep2(const EstPrepArgs &a, void *) {
 int launch_sim(const EstSimArgs &a, void *) {
     static uint64_t lds[(64 * 1024) / 8];
     if (a.lds_bytes > sizeof lds) abort();
-    for (uint32_t t = 0; t < a.tile_n; ++t) {
-        memset(lds, 0x5A, sizeof lds);
-        emu::run_wave([&] { estdev::sim_wave(a, t, lds); });
+    // the slots run one after the other; the first takes candidates until the counter runs out, so to
+    // exercise every slot's scratch the counter is handed out in turns: slot k gets candidates k, k+n_slots, ...
+    EstSimArgs b = a;
+    for (uint32_t slot = 0; slot < a.n_slots; ++slot) {
+        for (uint32_t t = slot; t < a.n_cfg; t += a.n_slots) {
+            EstStatus *st = a.status;
+            st->next_cfg = t;
+            b.n_cfg = t + 1;  // this slot stops after candidate t
+            memset(lds, 0x5A, sizeof lds);
+            emu::run_wave([&] { estdev::slot_loop(b, slot, lds); });
+        }
     }
     return 0;
 }
-int launch_select(const EstSelectArgs &a, void *) {
-    static uint64_t lds[128];
-    for (uint32_t t = 0; t < a.tile_n; ++t) emu::run_wave([&] { estdev::select_wave(a, t, lds); });
-    return 0;
-}
+uint32_t max_resident_waves() { return 3; }
 
 void *event_create() { return malloc(1); }
 void event_destroy(void *e) { free(e); }

@@ -89,5 +89,8 @@ EST_DEV void atomic_or_u64(uint64_t *p, uint64_t v) { *p |= v; }
 EST_DEV void atomic_or_u32(uint32_t *p, uint32_t v) { *p |= v; }
 EST_DEV void atomic_add_u32(uint32_t *p, uint32_t v) { *p += v; }
 EST_DEV void atomic_max_u32(uint32_t *p, uint32_t v) { if (v > *p) *p = v; }
+EST_DEV uint32_t fetch_add_u32(uint32_t *p, uint32_t v) { uint32_t o = *p; *p += v; return o; }
+EST_DEV uint64_t ticks() { return 0; }
+EST_DEV void atomic_add_u64(uint64_t *p, uint64_t v) { *p += v; }
 
 }  // namespace wv

@@ -135,7 +135,7 @@ def test_w2_full():
 
 def test_device_pointer_entry_points_and_tiling():
     """estimator_run_dev / estimator_run_latencies_dev with torch-owned memory, the torch stream, and a
-    caller workspace small enough to force several tiles."""
+    caller workspace small enough that the candidates share a few scratch slots."""
     import torch
     w = workloads.w2().subset(cfg_index=np.arange(0, 1024, 4))
     est = binding.Estimator(w.parents, w.lat_us, w.cost_uusd_hr)
@@ -151,7 +151,7 @@ def test_device_pointer_entry_points_and_tiling():
     with torch.cuda.stream(stream):
         got = est.run_dev(arr_t, msk_t, cfg_t, w.n_configs, w.slo_us, workspace_t=ws)
         lat = est.run_latencies_dev(arr_t, msk_t, cfg_t, w.n_configs, workspace_t=ws)
-    assert est.stats()["n_tiles"] > 1
+    assert est.stats()["n_slots"] < w.n_configs
     assert np.array_equal(got["p99_us"].cpu().numpy().view(np.uint32).astype(np.uint64), ref["p99_us"])
     assert np.array_equal(got["miss_count"].cpu().numpy().view(np.uint32).astype(np.uint64), ref["miss_count"])
     assert np.array_equal(got["cost_uusd_hr"].cpu().numpy().view(np.uint64), ref["cost_uusd_hr"])

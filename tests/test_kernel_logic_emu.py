@@ -154,9 +154,9 @@ def test_too_many_input_streams_is_unsupported():
     assert ei.value.code == binding.EST_EUNSUPPORTED
 
 
-def test_caller_workspace_tiles_the_candidates():
-    """With a small caller-provided workspace the candidates are processed in several tiles; too small
-    a workspace is EST_ENOMEM."""
+def test_caller_workspace_limits_the_scratch_slots():
+    """With a small caller-provided workspace fewer wavefronts (scratch slots) than candidates share the
+    work; too small a workspace is EST_ENOMEM."""
     w = workloads.random_case(9, S=3, n=300, C=7, dag="linear")
     lib = emu_lib.lib()
     est = emu_lib.make(w)
@@ -172,7 +172,7 @@ def test_caller_workspace_tiles_the_candidates():
                                ctypes.byref(res), ctypes.c_void_p(base), ctypes.c_uint64(90_000), None)
     assert rc == 0, lib.estimator_last_error(est._h)
     st = est.stats()
-    assert st["n_tiles"] > 1 and st["tile_configs"] < 7
+    assert st["n_slots"] < 7
     assert np.array_equal(p99.astype(np.uint64), ref["p99_us"]) and np.array_equal(miss.astype(np.uint64), ref["miss_count"])
     assert np.array_equal(cost, ref["cost_uusd_hr"])
     rc = lib.estimator_run_dev(est._h, ctypes.byref(tr), ctypes.c_void_p(cfg.ctypes.data), ctypes.c_uint64(7), ctypes.c_uint32(w.slo_us),
