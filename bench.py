@@ -20,14 +20,23 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
+# HBM bytes per launch of est_sim_kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes summarised in
+# profiles/est_sim_kernel_W4.md, keyed by (workload, candidates per call).  Valid for the kernel those
+# passes profiled; an entry is removed when the kernel changes and put back after re-profiling.
+MEASURED_TRAFFIC_BYTES = {("W4", 32768): 7.528e12}
+
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1)
     ap.add_argument("--warmup", type=int, default=0)
-    ap.add_argument("--workload", default="W5", choices=["W1", "W2", "W3", "W4", "W5"])
+    ap.add_argument("--workload", default="W4", choices=["W1", "W2", "W3", "W4", "W5"])
+    ap.add_argument("--chunk", type=int, default=32768, help="candidates per library call (a progress line is printed after each)")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="configs timed on the CPU oracle (0 = skip)")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="before the timed region, copy this many MiB device to device once (a kernel of known "
+                         "traffic, to scale hardware counters read under rocprofv3)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: candidate configurations are independent, so more GPUs would each take "
@@ -48,18 +57,40 @@ def main():
     cfg_t = torch.from_numpy(cfg.view(np.uint8).reshape(-1)).to(dev)
     torch.cuda.synchronize()
 
-    for _ in range(args.warmup):
-        est.run_dev(arr_t, msk_t, cfg_t, w.n_configs, w.slo_us)
+    if args.copy_probe_mib > 0:
+        src = torch.ones(args.copy_probe_mib * (1 << 20) // 4, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    S = w.n_stages
+    stats = {"sim_ms": 0.0, "launches": 0}
+
+    def one_pass(tag, timed):
+        """The whole hot path over every candidate, a chunk of candidates per library call."""
+        parts = []
+        for lo in range(0, w.n_configs, args.chunk):
+            hi = min(lo + args.chunk, w.n_configs)
+            parts.append(est.run_dev(arr_t, msk_t, cfg_t[lo * S * 4:hi * S * 4], hi - lo, w.slo_us))
+            st = est.stats()  # HIP-event durations of this call's kernels, on the stream they ran on
+            if timed:
+                stats["sim_ms"] += st["sim_ms"]; stats["launches"] += st["n_launches"]
+            stats["last"] = st
+            print("[bench] %s: candidates %d..%d of %d done, simulation kernel %.1f ms" % (tag, lo, hi, w.n_configs, st["sim_ms"]),
+                  file=sys.stderr, flush=True)
+        return {k: torch.cat([p_[k] for p_ in parts]) for k in parts[0]}
+
+    for i in range(args.warmup):
+        one_pass("warmup %d" % i, False)
     torch.cuda.synchronize()
-    sim_ms = 0.0
-    launches = 0
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        res = est.run_dev(arr_t, msk_t, cfg_t, w.n_configs, w.slo_us)
-        st = est.stats()  # HIP-event durations of this step's kernels, on the stream they ran on
-        sim_ms += st["sim_ms"]; launches += st["n_launches"]
+    for i in range(args.steps):
+        res = one_pass("step %d" % i, True)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    st = stats["last"]
+    sim_ms, launches = stats["sim_ms"], stats["launches"]
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     sims = w.n_configs * w.n_queries
     value = sims / (ms_per_step * 1e-3)
@@ -98,9 +129,11 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32", "data": "synthetic",
         "config": {"workload": args.workload, "n_configs": w.n_configs, "n_queries": w.n_queries, "n_stages": w.n_stages,
-                   "stage_visits_per_config": visits, "scratch_slots": st["n_slots"], "feasible_configs": feasible},
+                   "stage_visits_per_config": visits, "scratch_slots": st["n_slots"], "candidates_per_call": min(args.chunk, w.n_configs),
+                   "feasible_configs": feasible},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "kernel": "est_sim_kernel", "avg_launch_ms": avg_launch_s * 1e3},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, min(args.chunk, w.n_configs))),
+                     "kernel": "est_sim_kernel", "avg_launch_ms": avg_launch_s * 1e3},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

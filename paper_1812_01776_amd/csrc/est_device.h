@@ -706,7 +706,8 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
 // ------------------------------------------------------------------------------------------ driver
 
 // One wavefront = one candidate.  Every loop ends: an operation that consumes or emits nothing
-// reports no progress, and a full round without progress stops the candidate with an error flag.
+// reports no progress, and a full pass over the operations without progress stops the candidate with
+// an error flag.
 EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *lds) {
     const uint32_t ln = wv::lane();
     const EstPlan &P = *a.plan;
@@ -740,7 +741,13 @@ EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *
         for (uint32_t opi = 0; opi < P.n_ops; ++opi) {
             if (c.st[P.done_off + opi]) continue;
             const EstOp &op = P.ops[opi];
+            const uint64_t k0 = a.dbg_ticks ? wv::ticks() : 0;
             bool p = op.type == EST_OP_SCAN ? scan_run(c, op, opi) : merge_run(c, op, opi);
+            if (a.dbg_ticks && ln == 0) {
+                const uint32_t at = op.type == EST_OP_SCAN ? 8 + 3 * EST_MAX_STAGES + op.stage
+                                                           : 8 + 4 * EST_MAX_STAGES + (op.type == EST_OP_LAT ? 1 : 0);
+                wv::atomic_add_u64(a.status->dbg_cnt + at, wv::ticks() - k0);
+            }
             progress = progress || p;
             alldone = alldone && c.st[P.done_off + opi] != 0;
         }
@@ -820,8 +827,10 @@ EST_DEV void slot_loop(const EstSimArgs &a, uint32_t slot, uint64_t *lds) {
         const uint64_t t0 = a.dbg_ticks ? wv::ticks() : 0;
         if (a.n > 0) sim_wave(a, t, slot, lds);
         wv::sync();
+        const uint64_t k1 = a.dbg_ticks ? wv::ticks() : 0;
         if (!a.lat_by_qid) select_wave(a, t, slot, lds);
         wv::sync();
+        if (a.dbg_ticks && wv::lane() == 0) wv::atomic_add_u64(a.status->dbg_cnt + 8 + 4 * EST_MAX_STAGES + 2, wv::ticks() - k1);
         if (a.dbg_ticks && wv::lane() == 0) a.dbg_ticks[t] = wv::ticks() - t0;
     }
 }

@@ -66,9 +66,10 @@ struct EstStatus {
     uint32_t next_cfg;                       // work counter: next candidate to hand to a free wavefront
     uint32_t pad;
     // diagnostics (only counted when per-candidate timing is requested)
-    uint64_t dbg_cnt[8 + 3 * EST_MAX_STAGES];  // general steps, shortcut steps, shortcut elements, B=1 steps, B=1 elements,
+    uint64_t dbg_cnt[8 + 4 * EST_MAX_STAGES + 8];  // general steps, shortcut steps, shortcut elements, B=1 steps, B=1 elements,
                                              // merge rounds, merge elements, scan calls; then per stage: general steps,
-                                             // queries in general steps, queries in shortcut steps
+                                             // queries in general steps, queries in shortcut steps, ticks in the
+                                             // stage's scan; then ticks in merges, in the sink, in the selection
 };
 
 struct EstStageCfg {  // same layout as est_stage_cfg_t

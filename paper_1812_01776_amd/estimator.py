@@ -54,6 +54,12 @@ class Stats(ctypes.Structure):
 def load_library(path=LIB_PATH):
     if not os.path.exists(path):
         raise RuntimeError("the HIP library %s is not built; run `python -c 'import __graft_entry__ as g; g.build()'`" % path)
+    # PyTorch ships its own copy of the HIP runtime; load it first so that this library binds to the
+    # same runtime instance (two instances in one process do not both see the GPU).
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(path)
     lib.estimator_create.restype = ctypes.c_int
     lib.estimator_run.restype = ctypes.c_int

@@ -10,8 +10,8 @@ time-varying workload moves between Gamma distributions over time, batching rais
 throughput and latency of a model profile (Section 2.1, model-profile figure), and some
 pipeline branches are taken conditionally (Section 2).  The paper defines
 CV = sigma^2 / mu^2 (Section 2.1), so the Gamma shape is k = 1/CV and the scale is CV/lambda.
-The five workloads W1..W5 are the five benchmark configurations of this repository; their
-recipe is written out in the design doc.
+The five workloads W1..W5 are the five benchmark configurations of this repository; each
+function's docstring states its recipe.
 """
 from dataclasses import dataclass
 
