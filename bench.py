@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 # HBM bytes per launch of est_sim_kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes summarised in
 # profiles/est_sim_kernel_W4.md, keyed by (workload, candidates per call).  Valid for the kernel those
 # passes profiled; an entry is removed when the kernel changes and put back after re-profiling.
-MEASURED_TRAFFIC_BYTES = {("W4", 32768): 7.528e12}
+MEASURED_TRAFFIC_BYTES = {}
 
 
 def main():
@@ -32,7 +32,7 @@ def main():
     ap.add_argument("--steps", type=int, default=1)
     ap.add_argument("--warmup", type=int, default=0)
     ap.add_argument("--workload", default="W4", choices=["W1", "W2", "W3", "W4", "W5"])
-    ap.add_argument("--chunk", type=int, default=32768, help="candidates per library call (a progress line is printed after each)")
+    ap.add_argument("--chunk", type=int, default=65536, help="candidates per library call (a progress line is printed after each)")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="configs timed on the CPU oracle (0 = skip)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="before the timed region, copy this many MiB device to device once (a kernel of known "

@@ -128,6 +128,26 @@ EST_DEV uint32_t sort_lanes(uint32_t v, uint32_t width) {
     return v;
 }
 
+// Ascending bitonic sort of one 64-bit key per lane over all 64 lanes.
+EST_DEV uint64_t cmpx64(uint64_t v, uint32_t ohi, uint32_t olo, uint32_t ln, uint32_t k, uint32_t j) {
+    const uint64_t o = ((uint64_t)ohi << 32) | olo;
+    const bool up = (ln & k) == 0, lower = (ln & j) == 0;
+    const bool take_min = lower == up;
+    return ((o < v) == take_min) ? o : v;
+}
+EST_DEV uint64_t sort_lanes64(uint64_t v) {
+    const uint32_t ln = wv::lane();
+    for (uint32_t k = 2; k <= 64; k <<= 1) {
+        for (uint32_t j = k >> 1; j >= 16; j >>= 1)
+            v = cmpx64(v, wv::shfl((uint32_t)(v >> 32), ln ^ j), wv::shfl((uint32_t)v, ln ^ j), ln, k, j);
+        if (k >= 16) v = cmpx64(v, wv::xor8((uint32_t)(v >> 32)), wv::xor8((uint32_t)v), ln, k, 8);
+        if (k >= 8) v = cmpx64(v, wv::xor4((uint32_t)(v >> 32)), wv::xor4((uint32_t)v), ln, k, 4);
+        if (k >= 4) v = cmpx64(v, wv::xor2((uint32_t)(v >> 32)), wv::xor2((uint32_t)v), ln, k, 2);
+        v = cmpx64(v, wv::xor1((uint32_t)(v >> 32)), wv::xor1((uint32_t)v), ln, k, 1);
+    }
+    return v;
+}
+
 // ------------------------------------------------------------------------------------------ SCAN
 //
 // Per-wavefront working set of a scan, in LDS:
@@ -222,8 +242,8 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     uint32_t *g_slots = c.slots + op.slot_off;
     uint64_t *lkey = c.lds;
     uint32_t *lpos = (uint32_t *)(c.lds + SCAN_INRING);
-    uint32_t *ltab = lpos + SCAN_INRING;   // 4 x 64 words: staging for re-sorting the replica table, group ends
-    uint32_t *lslots = ltab + 256;
+    uint32_t *ltab = lpos + SCAN_INRING;   // 6 x 64 words: staging for re-sorting the replica table, per-group values
+    uint32_t *lslots = ltab + 384;
     const uint8_t *acc = c.a->acc + (uint64_t)op.acc_idx * c.a->acc_stride;
     const uint64_t below = lanes_below(ln);
 
@@ -248,6 +268,26 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     uint32_t wr = c.st[P.wr_off + op.out_ring];
     uint32_t space = ring_space(c, op.out_ring, wr);
     bool progress = false, finished = false;
+#ifdef EST_EMU_CHECKS
+    uint32_t chk_wr = wr;  // everything written from here on is verified to be in order, step by step
+    int chk_path = 0;
+#define EST_CHK_ORDER(tag)                                                                             \
+    do {                                                                                               \
+        wv::sync();                                                                                    \
+        if (ln == 0)                                                                                   \
+            for (uint32_t i_ = chk_wr > 0 ? chk_wr : 1; i_ < wr; ++i_) {                               \
+                const uint64_t a_ = out[(i_ - 1) & omask], b_ = out[i_ & omask];                       \
+                if ((uint32_t)(b_ >> 32) != 0xFFFFFFFFu && !(a_ < b_)) {                               \
+                    fprintf(stderr, "order violated by path %d at out[%u]: %llx then %llx (stage %u)\n", tag, i_, (unsigned long long)a_, (unsigned long long)b_, s); \
+                    abort();                                                                           \
+                }                                                                                      \
+            }                                                                                          \
+        chk_wr = wr;                                                                                   \
+        (void)chk_path;                                                                                \
+    } while (0)
+#else
+#define EST_CHK_ORDER(tag) ((void)0)
+#endif
     uint32_t fp_skip = 0;  // general batches still to do before the light-load shortcut is tried again
     uint32_t d_gen = 0, d_gene = 0, d_fp = 0, d_fpe = 0, d_b1 = 0, d_b1e = 0;  // diagnostics
 
@@ -290,6 +330,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         const uint64_t key = ln < w ? lkey[(lhead + ln) & (SCAN_INRING - 1)] : ~0ull;
         const uint32_t rdy = (uint32_t)(key >> 32);
         uint32_t q = (uint32_t)key;
+        EST_CHECK(ln == 0 || ln >= w || rdy == 0xFFFFFFFFu || key > lkey[(lhead + ln - 1) & (SCAN_INRING - 1)]);  // input is ordered
         if (B == 1) {
             // Maximum batch size 1: every query is its own batch and the service time is the constant
             // L(1), so completions keep the input order and query i runs on the replica that served
@@ -324,6 +365,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 space -= m;
                 // the table becomes the last R completion times
                 ++d_b1; d_b1e += m;
+                EST_CHK_ORDER(1);
                 const uint32_t keep = R > m ? R - m : 0u;  // old entries that stay
                 const uint32_t told = wv::shfl(rend, ln + m);
                 const uint32_t tnew = wv::shfl(x, ln + m - R);
@@ -337,17 +379,22 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         } else if (mono && fp_skip == 0) {
             // Light load: as long as every group of queries that become ready at the same instant
             // finds an idle replica at that instant and fits one batch, each group is one batch started
-            // at its ready time r and finished at r + L(group size).  If each batch also finishes
-            // before any later one possibly can, the output keeps the input order, and a whole run of
-            // groups is evaluated at once and written out immediately (nothing waits in slots).  The p replicas idle at the first
-            // ready time serve the groups in turn; replicas still busy are left alone, and the run
-            // stops before it would overtake a busy replica's unwritten batch.
+            // at its ready time r and finished at r + L(group size).  A whole run of groups is
+            // evaluated at once.  Let tau = (ready time of the first query after the run) + L(1): no
+            // later batch can finish before tau.  Batches of the run that finish before tau are
+            // written out right away, ordered by (completion time, query index), together with older
+            // waiting batches that finish before tau; the others wait in their replica's slot like any
+            // dispatched batch.  The p replicas idle at the first ready time serve the groups in turn
+            // (group k takes the replica of group k-p, which must be free again by then); replicas
+            // still busy are left alone.
             const uint32_t r0 = wv::uniform(rdy);
             const uint64_t E0 = wv::ballot(isrep && rcnt > 0 && rend <= r0);
             if (E0 && !scan_emit(op, lslots, E0, rend, rcnt, rslot, out, omask, wr, space, progress)) break;
+            EST_CHK_ORDER(5);
             const uint32_t p = popc64(wv::ballot(isrep && rend <= r0));  // a prefix of the sorted table
             uint32_t m = 0;
             if (p > 0) {
+                uint32_t *lend = ltab + 192, *lg = ltab + 256, *luns = ltab + 320;  // per group: end, size, waits
                 const uint32_t rprev = wv::shr1(rdy);
                 const uint64_t heads = wv::ballot(ln < w && (ln == 0 || rdy != rprev));  // first query of each group
                 const uint64_t upto = below | (1ull << ln);
@@ -358,13 +405,11 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 const uint32_t g = nh - start;
                 const bool final = staged <= 64 && rraw == in.wr && in.fin;
                 const uint32_t e = sat_add(rdy, wv::shfl(Lmine, g - 1));       // (L is 0 beyond B: rejected below)
-                uint32_t *lend = ltab + 192;                                   // completion time of each group
-                if (ln < w && ln == start) lend[bid] = e;
+                if (ln < w && ln == start) { lend[bid] = e; lg[bid] = g; }
                 wv::sync();
-                // Batches of busy replicas that still wait to be written (all end after r0) are woven
-                // into the output where their completion time falls.  Equal completion times would have
-                // to be ordered by query index: the run stops short of any such tie.
-                const uint64_t busyp = wv::ballot(isrep && rcnt > 0);
+                // a tie between two older waiting batches caps the run (their order is settled elsewhere),
+                // and no new completion time may equal an older waiting one
+                const uint64_t busyp = wv::ballot(isrep && rcnt > 0);  // all of these end after r0
                 const uint32_t rend_next = wv::shl1(rend);
                 const uint32_t rcnt_next = wv::shl1(rcnt);
                 const uint64_t tiep = wv::ballot(isrep && ln + 1 < R && rend > r0 && rend == rend_next && (rcnt > 0 || rcnt_next > 0));
@@ -375,66 +420,128 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                     ok = ok && e != ep;
                 }
                 ok = ok && (nh < w || final);                            // the whole group is in view
-                ok = ok && (bid < p || lend[bid - p] <= rdy);            // an idle replica, first come first served
-                // written out at once, so it must finish before anything later possibly can: any later
-                // batch starts no earlier than the next group's ready time and takes at least L(1)
-                const uint32_t rnh = wv::shfl(rdy, nh);
-                ok = ok && (nh >= w || e < sat_add(rnh, L1));
+                ok = ok && (bid < p || lend[bid - p] <= rdy);            // its replica is free again
                 const uint64_t okm = wv::ballot(ok);
                 m = okm == ~0ull ? 64u : ctz64(~okm);                    // (a group is accepted or rejected as a whole)
-                // waiting batches that complete before the last accepted completion go out with the run
-                uint32_t shift = 0, extra = 0;
-                uint64_t woven = 0;
-                if (m > 0 && busyp) {
-                    const uint32_t elast = wv::bcast(e, m - 1);
+                if (m > 0) {
+                    const bool tau_inf = m >= w;                         // (only at the very end of the input)
+                    const uint32_t tau = tau_inf ? 0xFFFFFFFFu : sat_add(wv::bcast(rdy, umin(m, 63u)), L1);
+                    const bool safe = ln < m && (tau_inf || e < tau);
+                    const uint64_t safem = wv::ballot(safe);
+                    const uint32_t ns = popc64(safem);
+                    // older waiting batches that finish before tau go out with the run
+                    uint32_t extra = 0;
+                    uint64_t woven = 0;
                     for (uint64_t pm = busyp; pm; pm &= pm - 1) {
                         const uint32_t j = ctz64(pm);
                         const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j);
-                        if (ej >= elast) break;  // sorted: the rest complete later and keep waiting
+                        if ((!tau_inf && ej >= tau) || ej >= ecap) break;  // sorted: the rest finish later (or tie) and keep waiting
                         woven |= 1ull << j;
                         extra += cj;
-                        if (ej < e) shift += cj;
                     }
-                }
-                if (m + extra > space) m = 0;  // leave it to the general path (or to the consumer)
-                if (m > 0) {
-                    if (ln < m) out[(wr + ln + shift) & omask] = ((uint64_t)e << 32) | q;
-                    uint32_t before = 0;
-                    for (uint64_t pm = woven; pm; pm &= pm - 1) {
-                        const uint32_t j = ctz64(pm);
-                        const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j), sj = wv::bcast(rslot, j);
-                        const uint32_t pos = wr + before + popc64(wv::ballot(ln < m && e < ej));
-                        if (ln < cj) out[(pos + ln) & omask] = ((uint64_t)ej << 32) | lslots[sj * bm + ln];
-                        before += cj;
+#ifdef EST_DBG_NOWAIT
+                    const bool dbg_fail = wv::ballot(ln < m && !safe) != 0;
+#else
+                    const bool dbg_fail = false;
+#endif
+                    if (ns + extra > space || dbg_fail) {
+                        m = 0;  // leave it to the general path (or to the consumer)
+                    } else {
+                        // order the run's own output: usually already ordered
+                        uint64_t key = safe ? (((uint64_t)e << 32) | q) : ~0ull;
+                        // cheap test first: completion times never decrease along the run and differ
+                        // between groups -> the safe ones are already in output order
+                        const uint32_t eprev1 = wv::shr1(e);
+                        const uint32_t bprev = wv::shr1(bid);
+                        uint64_t inv = wv::ballot(ln > 0 && ln < m && (eprev1 > e || (eprev1 == e && bprev != bid)));
+                        if (inv) {
+                            // exact test: an earlier safe query finishes later, or at the same time in another group
+                            uint32_t pmax = safe ? e : 0u;               // inclusive prefix maximum of e over safe lanes
+                            for (uint32_t d = 1; d < 64; d <<= 1) {
+                                const uint32_t y = wv::shfl(pmax, ln - d);
+                                if (ln >= d) pmax = umax(pmax, y);
+                            }
+                            const uint32_t pbefore = wv::shr1(pmax);
+                            inv = wv::ballot(safe && ln > 0 && (pbefore > e || (pbefore == e && bprev != bid)));
+                        }
+                        uint32_t orank = popc64(safem & below);
+                        if (inv) {
+                            key = sort_lanes64(key);
+                            orank = ln;
+                        }
+                        const bool emit_me = inv ? ln < ns : safe;
+                        const uint32_t ke = (uint32_t)(key >> 32);
+                        uint32_t shift = 0;
+                        for (uint64_t pm = woven; pm; pm &= pm - 1) {
+                            const uint32_t j = ctz64(pm);
+                            const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j);
+                            if (ej < ke) shift += cj;
+                        }
+                        if (emit_me) out[(wr + orank + shift) & omask] = key;
+                        uint32_t before = 0;
+                        for (uint64_t pm = woven; pm; pm &= pm - 1) {
+                            const uint32_t j = ctz64(pm);
+                            const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j), sj = wv::bcast(rslot, j);
+                            const uint32_t pos = wr + before + popc64(wv::ballot(emit_me && ke < ej));
+                            if (ln < cj) out[(pos + ln) & omask] = ((uint64_t)ej << 32) | lslots[sj * bm + ln];
+                            before += cj;
+                        }
+                        if ((woven >> ln) & 1ull) rcnt = 0;
+                        wr += ns + extra;
+                        space -= ns + extra;
+                        EST_CHK_ORDER(inv ? 3 : 2);
+                        // the run's batches that finish at or after tau wait in the slot of their replica
+                        const uint32_t inv_p = (65536u + p - 1u) / p;            // floor(x / p) = x * inv_p >> 16 for x < 64
+                        const uint32_t kmod = bid - p * ((bid * inv_p) >> 16);   // the replica (idle-table lane) of my group
+                        const uint32_t myslot = wv::shfl(rslot, kmod);
+                        const bool waits = ln < m && !safe;
+                        if (waits) lslots[myslot * bm + (ln - start)] = q;
+                        if (ln < m && ln == start) luns[bid] = waits ? 1u : 0u;
+                        wv::sync();
+                        // new table: every idle replica that served a group holds its last group's completion
+                        // time (and its members, if they wait); then everything is put back in order of time
+                        const uint32_t nb = popc64(heads & lanes_below(m));      // groups accepted
+                        uint32_t cend = rend, ccnt = rcnt, cslot = rslot;
+                        if (ln < p && ln < nb) {
+                            const uint32_t x = nb - 1u - ln;
+                            const uint32_t klast = ln + p * ((x * inv_p) >> 16);
+                            cend = lend[klast];
+                            ccnt = luns[klast] ? lg[klast] : 0u;
+                        }
+                        uint32_t trank = 0;
+                        if (!inv && !wv::ballot(waits)) {
+                            // common case: nothing waits and the new completion times ascend with the group
+                            // index, so lanes [0,p) hold, in order, the unused idle entries (still <= r0,
+                            // lanes nb..p-1) and then the served ones in ascending time; only the busy
+                            // entries have to be slotted in
+                            const uint32_t nn = umin(nb, p), na = p - nn;
+                            // served lane j holds group klast(j); in time order these are lanes
+                            // (nb mod p), (nb mod p)+1, ..., wrapping: position = (j - nb) mod p
+                            const uint32_t nbm = nb - p * ((nb * inv_p) >> 16);
+                            const bool is_n = ln < nn, is_a = ln >= nn && ln < p, is_b = isrep && ln >= p;
+                            uint32_t rank_n = na + (nb >= p ? (ln >= nbm ? ln - nbm : ln + p - nbm) : ln);
+                            uint32_t rank_b = na + nn + (ln - p);
+                            for (uint64_t bm2 = wv::ballot(is_b); bm2; bm2 &= bm2 - 1) {
+                                const uint32_t j = ctz64(bm2);
+                                const uint32_t ej = wv::bcast(cend, j);
+                                const uint32_t more_new = popc64(wv::ballot(is_n && cend > ej));  // new entries after this busy one
+                                if (ln == j) rank_b -= more_new;
+                                if (is_n && cend > ej) rank_n += 1;
+                            }
+                            trank = is_a ? ln - nn : is_n ? rank_n : rank_b;
+                        } else {
+                            for (uint32_t j = 0; j < R; ++j) {
+                                const uint32_t ej = wv::bcast(cend, j);
+                                if (ej < cend || (ej == cend && j < ln)) ++trank;
+                            }
+                        }
+                        if (isrep) { ltab[trank] = cend; ltab[64 + trank] = ccnt; ltab[128 + trank] = cslot; }
+                        wv::sync();
+                        if (isrep) { rend = ltab[ln]; rcnt = ltab[64 + ln]; rslot = ltab[128 + ln]; }
+                        wv::sync();
+                        lhead += m;
+                        progress = true;
                     }
-                    if ((woven >> ln) & 1ull) rcnt = 0;
-                    wr += m + extra;
-                    space -= m + extra;
-                    // new table: the idle replicas not used (still <= r0), then the last min(nb,p) new
-                    // completion times merged with the busy replicas by time
-                    const uint32_t nb = popc64(heads & lanes_below(m));      // groups accepted
-                    const uint32_t nn = umin(nb, p), na = p - nn, first_new = nb - nn;
-                    const bool is_a = ln >= nn && ln < p;                 // unused idle entry
-                    const bool is_b = isrep && ln >= p;                   // busy entry
-                    const bool is_n = ln < nn;                            // k-th of the last nn new completions
-                    const uint32_t en = is_n ? lend[first_new + ln] : 0u;
-                    uint32_t rank_n = na + ln, rank_b = na + (ln - p);
-                    for (uint64_t bm2 = wv::ballot(is_b); bm2; bm2 &= bm2 - 1) {
-                        const uint32_t j = ctz64(bm2);
-                        const uint32_t ej = wv::bcast(rend, j);
-                        const uint32_t less_new = popc64(wv::ballot(is_n && en < ej));
-                        if (ln == j) rank_b += less_new;
-                        if (is_n && ej <= en) rank_n += 1;
-                    }
-                    // (lane k < nn holds idle entry k, whose slot the k-th new entry inherits)
-                    if (is_a) { ltab[ln - nn] = rend; ltab[64 + ln - nn] = 0; ltab[128 + ln - nn] = rslot; }
-                    if (is_b) { ltab[rank_b] = rend; ltab[64 + rank_b] = rcnt; ltab[128 + rank_b] = rslot; }
-                    if (is_n) { ltab[rank_n] = en; ltab[64 + rank_n] = 0; ltab[128 + rank_n] = rslot; }
-                    wv::sync();
-                    if (isrep) { rend = ltab[ln]; rcnt = ltab[64 + ln]; rslot = ltab[128 + ln]; }
-                    wv::sync();
-                    lhead += m;
-                    progress = true;
                 }
             }
             ++d_fp; d_fpe += m;
@@ -457,6 +564,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         // everything that completes by T leaves before this batch is dispatched
         const uint64_t E = wv::ballot(isrep && rcnt > 0 && rend <= T);
         if (E && !scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress)) break;
+        EST_CHK_ORDER(4);
         // members wait in the replica's slot sorted by query index
         if (b > 1) {
             const uint32_t prev = wv::shr1(q);
@@ -551,6 +659,39 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     uint32_t miss = 0;
     bool progress = false, finished = false;
 
+    if (K == 1 && !op.has_cnt) {
+        // one source, every query fed by it alone: filter and copy, window by window
+        const View sv = view_of(c, op.src_ring[0]);
+        uint32_t rc = raw[0];
+        for (;;) {
+            if (!is_lat && space < 64u) break;  // wait for the consumer
+            if (rc == sv.wr) {
+                finished = sv.fin != 0;
+                break;
+            }
+            const uint32_t w = umin(64u, sv.wr - rc);
+            const uint64_t key = ln < w ? sv.base[(rc + ln) & sv.mask] : 0ull;
+            const uint32_t q = (uint32_t)key;
+            const bool a = ln < w && (acc[q] & 1u);
+            const uint64_t A = wv::ballot(a);
+            const uint32_t pos = wr + popc64(A & below);
+            if (a) {
+                if (is_lat) {
+                    const uint32_t l = (uint32_t)(key >> 32) - c.a->arrival[q];
+                    c.lat[c.a->lat_by_qid ? q : pos] = l;
+                    miss += l > c.a->slo_us;
+                } else {
+                    out[pos & omask] = key;
+                }
+            }
+            const uint32_t na = popc64(A);
+            wr += na;
+            if (!is_lat) space -= na;
+            rc += w;
+            progress = true;
+        }
+        raw[0] = rc;
+    } else
     for (;;) {
         if (!is_lat && space < 64u * K) break;  // wait for the consumer
         // ---- stage up to 64 accepted elements of every source

@@ -18,7 +18,7 @@ def build():
         [os.path.join(os.path.dirname(_HERE), "include", "estimator.h")]
     if os.path.exists(_LIB) and all(os.path.getmtime(_LIB) >= os.path.getmtime(d) for d in deps):
         return _LIB
-    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-parameter",
+    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fPIC", "-shared", "-DEST_EMU_CHECKS", "-Wall", "-Wno-unused-parameter",
                            "-o", _LIB] + srcs)
     return _LIB
 
