@@ -242,8 +242,8 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     uint32_t *g_slots = c.slots + op.slot_off;
     uint64_t *lkey = c.lds;
     uint32_t *lpos = (uint32_t *)(c.lds + SCAN_INRING);
-    uint32_t *ltab = lpos + SCAN_INRING;   // 6 x 64 words: staging for re-sorting the replica table, per-group values
-    uint32_t *lslots = ltab + 384;
+    uint32_t *ltab = lpos + SCAN_INRING;   // 7 x 64 words: staging for re-sorting the replica table, per-group values
+    uint32_t *lslots = ltab + 448;
     const uint8_t *acc = c.a->acc + (uint64_t)op.acc_idx * c.a->acc_stride;
     const uint64_t below = lanes_below(ln);
 
@@ -391,13 +391,19 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             const uint64_t E0 = wv::ballot(isrep && rcnt > 0 && rend <= r0);
             if (E0 && !scan_emit(op, lslots, E0, rend, rcnt, rslot, out, omask, wr, space, progress)) break;
             EST_CHK_ORDER(5);
-            const uint32_t p = popc64(wv::ballot(isrep && rend <= r0));  // a prefix of the sorted table
+            const uint32_t pidle = popc64(wv::ballot(isrep && rend <= r0));  // idle now: a prefix of the sorted table
             uint32_t m = 0;
-            if (p > 0) {
+            if (pidle > 0) {
                 uint32_t *lend = ltab + 192, *lg = ltab + 256, *luns = ltab + 320;  // per group: end, size, waits
+                // groups: queries with the same ready time, cut into pieces of B (a piece of B queries is
+                // a full batch; the queries of a run are in query-index order, so piece j holds its
+                // members j*B .. j*B+B-1, as the queue would hand them out)
                 const uint32_t rprev = wv::shr1(rdy);
-                const uint64_t heads = wv::ballot(ln < w && (ln == 0 || rdy != rprev));  // first query of each group
                 const uint64_t upto = below | (1ull << ln);
+                const uint64_t runs = wv::ballot(ln < w && (ln == 0 || rdy != rprev));
+                const uint32_t off = ln - (63u - (uint32_t)__builtin_clzll((runs & upto) | 1ull));
+                const uint32_t inv_b = (65536u + B - 1u) / B;                  // floor(x / B) = x * inv_b >> 16 for x < 64
+                const uint64_t heads = wv::ballot(ln < w && off == B * ((off * inv_b) >> 16));  // first query of each group
                 const uint32_t bid = popc64(heads & upto) - 1u;                // group index of this lane
                 const uint32_t start = 63u - (uint32_t)__builtin_clzll(heads & upto);
                 const uint64_t later = ln == 63 ? 0ull : (heads >> (ln + 1));
@@ -405,8 +411,14 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 const uint32_t g = nh - start;
                 const bool final = staged <= 64 && rraw == in.wr && in.fin;
                 const uint32_t e = sat_add(rdy, wv::shfl(Lmine, g - 1));       // (L is 0 beyond B: rejected below)
-                if (ln < w && ln == start) { lend[bid] = e; lg[bid] = g; }
+                uint32_t *lrdy = ltab + 384;                                   // per group: ready time
+                if (ln < w && ln == start) { lend[bid] = e; lg[bid] = g; lrdy[bid] = rdy; }
                 wv::sync();
+                // replicas that serve the run: the table's first p entries, each free by the time its turn
+                // comes (group l takes entry l); later groups take the replica of the group p before them
+                const uint32_t ngroups = popc64(heads);
+                const uint64_t usable = wv::ballot(isrep && ln < ngroups && rend <= lrdy[ln < ngroups ? ln : 0]);
+                const uint32_t p = usable == ~0ull ? 64u : ctz64(~usable);     // >= 1: entry 0 is idle now
                 // a tie between two older waiting batches caps the run (their order is settled elsewhere),
                 // and no new completion time may equal an older waiting one
                 const uint64_t busyp = wv::ballot(isrep && rcnt > 0);  // all of these end after r0
@@ -419,13 +431,15 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                     const uint32_t ep = wv::bcast(rend, ctz64(pm));
                     ok = ok && e != ep;
                 }
-                ok = ok && (nh < w || final);                            // the whole group is in view
+                ok = ok && (nh < w || final || g == B);                  // the whole group is in view (or it is full)
                 ok = ok && (bid < p || lend[bid - p] <= rdy);            // its replica is free again
                 const uint64_t okm = wv::ballot(ok);
                 m = okm == ~0ull ? 64u : ctz64(~okm);                    // (a group is accepted or rejected as a whole)
                 if (m > 0) {
-                    const bool tau_inf = m >= w;                         // (only at the very end of the input)
-                    const uint32_t tau = tau_inf ? 0xFFFFFFFFu : sat_add(wv::bcast(rdy, umin(m, 63u)), L1);
+                    // the next batch starts no earlier than the next query's ready time; if the run took
+                    // the whole window, that is at least the window's last ready time
+                    const bool tau_inf = m >= w && final;                // nothing follows at all
+                    const uint32_t tau = tau_inf ? 0xFFFFFFFFu : sat_add(wv::bcast(rdy, umin(m, w - 1u)), L1);
                     const bool safe = ln < m && (tau_inf || e < tau);
                     const uint64_t safem = wv::ballot(safe);
                     const uint32_t ns = popc64(safem);
@@ -452,8 +466,9 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                         // cheap test first: completion times never decrease along the run and differ
                         // between groups -> the safe ones are already in output order
                         const uint32_t eprev1 = wv::shr1(e);
+                        const uint32_t qprev = wv::shr1(q);
                         const uint32_t bprev = wv::shr1(bid);
-                        uint64_t inv = wv::ballot(ln > 0 && ln < m && (eprev1 > e || (eprev1 == e && bprev != bid)));
+                        uint64_t inv = wv::ballot(ln > 0 && ln < m && (eprev1 > e || (eprev1 == e && qprev > q)));
                         if (inv) {
                             // exact test: an earlier safe query finishes later, or at the same time in another group
                             uint32_t pmax = safe ? e : 0u;               // inclusive prefix maximum of e over safe lanes
@@ -509,7 +524,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                             ccnt = luns[klast] ? lg[klast] : 0u;
                         }
                         uint32_t trank = 0;
-                        if (!inv && !wv::ballot(waits)) {
+                        if (!inv && !wv::ballot(waits) && p == pidle) {
                             // common case: nothing waits and the new completion times ascend with the group
                             // index, so lanes [0,p) hold, in order, the unused idle entries (still <= r0,
                             // lanes nb..p-1) and then the served ones in ascending time; only the busy
