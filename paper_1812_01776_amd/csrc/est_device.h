@@ -57,6 +57,7 @@ struct Ctx {
     uint32_t *lat;
     const EstStageCfg *cfg;
     uint64_t *lds;
+    uint32_t t;  // candidate index
 };
 
 struct View {
@@ -288,8 +289,9 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
 #else
 #define EST_CHK_ORDER(tag) ((void)0)
 #endif
-    uint32_t fp_skip = 0;  // general batches still to do before the light-load shortcut is tried again
-    uint32_t d_gen = 0, d_gene = 0, d_fp = 0, d_fpe = 0, d_b1 = 0, d_b1e = 0;  // diagnostics
+    uint32_t fp_skip = 0;   // general batches still to do before the light-load shortcut is tried again
+    uint32_t sat_skip = 0;  // the same for the backlog shortcut
+    uint32_t d_gen = 0, d_gene = 0, d_fp = 0, d_fpe = 0, d_b1 = 0, d_b1e = 0, d_sat = 0, d_sate = 0, d_hz = 0;  // diagnostics
 
     for (;;) {
         uint32_t staged = ltail - lhead;
@@ -331,51 +333,136 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         const uint32_t rdy = (uint32_t)(key >> 32);
         uint32_t q = (uint32_t)key;
         EST_CHECK(ln == 0 || ln >= w || rdy == 0xFFFFFFFFu || key > lkey[(lhead + ln - 1) & (SCAN_INRING - 1)]);  // input is ordered
-        if (B == 1) {
+        const uint32_t f0 = wv::uniform(rend);  // earliest free replica = lane 0
+        if (f0 == 0xFFFFFFFFu) {
+            // Every replica is busy up to the horizon: whatever is still queued starts and ends at the
+            // horizon, where order no longer matters.  Waiting batches leave first, then the window.
+            const uint64_t E = wv::ballot(rcnt > 0);
+            if (E && !scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress)) break;
+            const uint32_t m = umin(w, space);
+            if (m == 0) break;
+            if (ln < m) out[(wr + ln) & omask] = 0xFFFFFFFF00000000ull | q;
+            wr += m;
+            space -= m;
+            lhead += m;
+            d_hz += m;
+            progress = true;
+            continue;
+        }
+        if (B >= 2) {
+            if (sat_skip == 0 && B <= 32 && w >= 2 * B && wv::bcast(rdy, B - 1) <= f0) {
+                // Backlog: while the queue holds a full batch whenever a replica frees, the replicas take
+                // full batches in rotation.  With the free times f_0 <= ... <= f_{R-1} < f_0 + L(B), batch k
+                // (queries kB .. kB+B-1 of the window) starts at f_k, where f_k = f_{k-R} + L(B) for k >= R,
+                // provided its last member is ready by then.  The leading batches that satisfy this are all
+                // dispatched at once; as in the general step, everything that completes by the last of
+                // these dispatch times leaves, the rest waits in the slots of the replicas.
+                const uint32_t LB = wv::bcast(Lmine, B - 1);
+                const uint32_t tl = wv::bcast(rend, R - 1);
+                uint32_t nacc = 0;
+                if (tl < sat_add(f0, LB)) {
+                    const uint32_t inv_b = (65536u + B - 1u) / B;  // floor(x / B) = x * inv_b >> 16 for x <= 64
+                    const uint32_t inv_r = (65536u + R - 1u) / R;
+                    const uint32_t kb = (ln * inv_b) >> 16;        // my batch
+                    const uint32_t kd = (kb * inv_r) >> 16, km = kb - kd * R;
+                    const uint64_t ft = (uint64_t)wv::shfl(rend, km) + (uint64_t)kd * LB;
+                    const uint32_t fk = ft >= 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)ft;
+                    const uint32_t e = sat_add(fk, LB);
+                    const uint32_t nfull = (w * inv_b) >> 16;
+                    const uint32_t lastr = wv::shfl(rdy, kb * B + B - 1u);
+                    const uint64_t okm = wv::ballot(ln < nfull * B && lastr <= fk && e != 0xFFFFFFFFu);
+                    const uint32_t nl = okm == ~0ull ? 64u : ctz64(~okm);  // a multiple of B: the test is per batch
+                    nacc = (nl * inv_b) >> 16;
+                    if (nacc >= 2) {
+                        const uint32_t na = nacc * B;
+                        const uint32_t Tlast = wv::bcast(fk, na - 1u);
+                        const uint64_t E = wv::ballot(isrep && rcnt > 0 && rend <= Tlast);
+                        const bool direct = ln < na && e <= Tlast;  // replaced again inside this step: never waits
+                        const uint32_t nd = popc64(wv::ballot(direct));
+                        if (popc64(E) * B + nd > space) {
+                            nacc = 0;  // tight output ring: batch by batch
+                        } else {
+                            scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress);
+                            const uint32_t eprev = wv::shr1(e), qprev = wv::shr1(q), kprev = wv::shr1(kb);
+                            uint64_t okey = direct ? (((uint64_t)e << 32) | q) : ~0ull;
+                            if (wv::ballot(direct && ln > 0 && eprev == e && qprev > q)) okey = sort_lanes64(okey);
+                            if (ln < nd) out[(wr + ln) & omask] = okey;  // (times ascend with the batch: a prefix)
+                            wr += nd;
+                            space -= nd;
+                            EST_CHK_ORDER(6);
+                            // members wait sorted by query index
+                            uint32_t qs = q;
+                            if (wv::ballot(ln >= nd && ln < na && ln > 0 && kprev == kb && qprev > q))
+                                qs = (uint32_t)sort_lanes64(ln < na ? (((uint64_t)kb << 32) | q) : ~0ull);
+                            const uint32_t myslot = wv::shfl(rslot, km);
+                            if (ln >= nd && ln < na) lslots[myslot * bm + (ln - kb * B)] = qs;
+                            // new table: the entries not replaced, then the last min(nacc, R) batches
+                            const uint32_t nn = umin(nacc, R);
+                            const uint32_t src = (nacc - R + ln) * B;  // first lane of the batch that lands in table lane ln
+                            const uint32_t oe = wv::shfl(rend, ln + nn), oc = wv::shfl(rcnt, ln + nn), os = wv::shfl(rslot, ln + nn);
+                            const uint32_t ne = wv::shfl(e, src), ns = wv::shfl(myslot, src);
+                            if (isrep) {
+                                if (ln + nn < R) {
+                                    rend = oe; rcnt = oc; rslot = os;
+                                } else {
+                                    rend = ne; rcnt = ne > Tlast ? B : 0u; rslot = ns;
+                                }
+                            }
+                            wv::sync();
+                            lhead += na;
+                            ++d_sat; d_sate += na;
+                            progress = true;
+                            continue;
+                        }
+                    }
+                }
+                if (nacc < 2) sat_skip = 4;
+            }
+        }
+        if (B == 1 && L1 > 0) {
             // Maximum batch size 1: every query is its own batch and the service time is the constant
             // L(1), so completions keep the input order and query i runs on the replica that served
             // query i-R:  end_i = max(ready_i, end_{i-R}) + L(1).  The sorted replica table is exactly
             // (end_{i-R}, ..., end_{i-1}), so a whole window is evaluated at once with a max-plus
             // scan of stride R.  Nothing waits in slots: results are written out immediately.
+            EST_CHECK(wv::ballot(rcnt > 0) == 0);
             uint32_t x = sat_add(umax(rdy, isrep ? rend : 0u), L1);
             for (uint32_t d = R, mul = 1; d < 64; d <<= 1, mul <<= 1) {
                 const uint32_t y = wv::shfl(x, ln - d);
                 const uint32_t inc = (uint64_t)mul * L1 > 0xFFFFFFFFull ? 0xFFFFFFFFu : mul * L1;
                 if (ln >= d) x = umax(x, sat_add(y, inc));
             }
-            // Batches left waiting by a general step complete no later than anything that follows
-            // (constant service time), so they can be written out now -- except those that tie with
-            // the first new completion time, which have to be merged with it by query index.
-            const uint32_t x0 = wv::uniform(x);
-            const uint64_t pend = wv::ballot(rcnt > 0);
-            const uint64_t early = wv::ballot(rcnt > 0 && rend < x0);
-            if (early && !scan_emit(op, lslots, early, rend, rcnt, rslot, out, omask, wr, space, progress)) break;
-            // keep back the trailing run of equal completion times (it may continue in the next
-            // window and has to come out ordered by query index), unless this is the very end
+            // Queries that complete at the same time leave ordered by query index.  Since
+            // end_i > end_{i-R}, such a run has at most R members; a shorter run at the end of what can
+            // be written now may continue with the next query, and is kept back until that is known
+            // (times clamped at the horizon need no order).
             const uint32_t xp = wv::shr1(x);
             const uint32_t qp = wv::shr1(q);
             const uint64_t bnd = wv::ballot(ln > 0 && ln < w && x != xp) | 1ull;  // starts of runs
             const bool last = staged <= 64 && rraw == in.wr && in.fin;
             uint32_t m = umin(w, space);
-            if (!(last && m == w)) m = 63u - (uint32_t)__builtin_clzll(bnd & lanes_below(m + 1));
-            const uint64_t inv = wv::ballot(ln > 0 && ln < m && x == xp && q < qp);
-            if (m > 0 && inv == 0 && pend == early) {
-                if (ln < m) out[(wr + ln) & omask] = ((uint64_t)x << 32) | q;
-                wr += m;
-                space -= m;
-                // the table becomes the last R completion times
-                ++d_b1; d_b1e += m;
-                EST_CHK_ORDER(1);
-                const uint32_t keep = R > m ? R - m : 0u;  // old entries that stay
-                const uint32_t told = wv::shfl(rend, ln + m);
-                const uint32_t tnew = wv::shfl(x, ln + m - R);
-                if (isrep) rend = ln < keep ? told : tnew;
-                lhead += m;
-                progress = true;
-                continue;
+            if (m > 0) {
+                const uint32_t s0 = 63u - (uint32_t)__builtin_clzll(bnd & lanes_below(m));  // start of the run of lane m-1
+                const uint32_t xl = wv::bcast(x, m - 1u);
+                const bool complete = m < w ? wv::bcast(x, m) != xl : (last || xl == 0xFFFFFFFFu || m - s0 >= R);
+                if (!complete) m = s0;
             }
-            if (space == 0) break;
-            // a whole window of equal times, or equal times out of query order: one general step
+            if (m == 0) break;  // wait for the consumer, or for the rest of the run
+            uint64_t okey = ln < m ? (((uint64_t)x << 32) | q) : ~0ull;
+            if (wv::ballot(ln > 0 && ln < m && x == xp && q < qp && x != 0xFFFFFFFFu)) okey = sort_lanes64(okey);
+            if (ln < m) out[(wr + ln) & omask] = okey;
+            wr += m;
+            space -= m;
+            ++d_b1; d_b1e += m;
+            EST_CHK_ORDER(1);
+            // the table becomes the last R completion times
+            const uint32_t keep = R > m ? R - m : 0u;  // old entries that stay
+            const uint32_t told = wv::shfl(rend, ln + m);
+            const uint32_t tnew = wv::shfl(x, ln + m - R);
+            if (isrep) rend = ln < keep ? told : tnew;
+            lhead += m;
+            progress = true;
+            continue;
         } else if (mono && fp_skip == 0) {
             // Light load: as long as every group of queries that become ready at the same instant
             // finds an idle replica at that instant and fits one batch, each group is one batch started
@@ -565,6 +652,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             if (space == 0) break;
         }
         if (fp_skip) --fp_skip;
+        if (sat_skip) --sat_skip;
         ++d_gen;
         const uint32_t f = wv::uniform(rend);  // earliest free replica = lane 0
         const uint32_t r0 = wv::uniform(rdy);
@@ -611,7 +699,11 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         wv::atomic_add_u64(dc + 0, d_gen); wv::atomic_add_u64(dc + 1, d_fp); wv::atomic_add_u64(dc + 2, d_fpe);
         wv::atomic_add_u64(dc + 3, d_b1); wv::atomic_add_u64(dc + 4, d_b1e); wv::atomic_add_u64(dc + 7, 1);
         wv::atomic_add_u64(dc + 8 + s, d_gen); wv::atomic_add_u64(dc + 8 + EST_MAX_STAGES + s, d_gene);
-        wv::atomic_add_u64(dc + 8 + 2 * EST_MAX_STAGES + s, d_fpe + d_b1e);
+        wv::atomic_add_u64(dc + 8 + 2 * EST_MAX_STAGES + s, d_fpe + d_b1e + d_sate + d_hz);
+        wv::atomic_add_u64(dc + 8 + 4 * EST_MAX_STAGES + 3, d_sat); wv::atomic_add_u64(dc + 8 + 4 * EST_MAX_STAGES + 4, d_sate);
+        wv::atomic_add_u64(dc + 8 + 4 * EST_MAX_STAGES + 5, d_hz);
+        uint64_t *pc = c.a->dbg_ticks + c.a->n_cfg + ((uint64_t)c.t * EST_MAX_STAGES + s) * 4;  // per candidate and stage
+        pc[0] += d_gen; pc[1] += d_gene; pc[2] += d_fp + d_b1 + d_sat; pc[3] += d_fpe + d_b1e + d_sate + d_hz;
     }
     // back to memory: the table, the members still waiting, the cursors
     if (isrep) {
@@ -878,6 +970,7 @@ EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *
     c.lat = a.lat + (uint64_t)(a.lat_by_qid ? t : slot) * a.lat_stride;
     c.cfg = a.cfg + (uint64_t)t * a.dag->S;
     c.lds = lds;
+    c.t = t;
 
     for (uint32_t i = ln; i < P.state_words; i += 64) c.st[i] = 0;
     for (uint64_t i = ln; i < a.rep_stride; i += 64) c.rep[i] = 0;

@@ -385,7 +385,8 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     const char *dbg_path = getenv("EST_DEBUG_TICKS");
     DevBuf dbg_buf;
     uint64_t *dbg_ticks = nullptr;
-    if (dbg_path && n > 0 && dbg_buf.alloc(n_cfg * 8)) dbg_ticks = (uint64_t *)dbg_buf.p;
+    const uint64_t dbg_words = n_cfg * (1 + 4 * EST_MAX_STAGES);  // per candidate: ticks, then 4 counters per stage
+    if (dbg_path && n > 0 && dbg_buf.alloc(dbg_words * 8) && !estbe::zero(dbg_buf.p, dbg_words * 8, stream)) dbg_ticks = (uint64_t *)dbg_buf.p;
     void *e0 = evs.make(), *e1 = evs.make();
     if (!e0 || !e1) return dev_fail(h, "event create");
     estbe::event_record(e0, stream);
@@ -432,10 +433,10 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     if (estbe::d2h(&st2, h->d_status, sizeof st2, stream) || estbe::sync(stream)) return dev_fail(h, "run");
     if (st2.sim_error) return fail(h, EST_EINTERNAL, "the simulation kernel stopped without finishing a candidate");
     if (dbg_ticks) {
-        std::vector<uint64_t> ticks(n_cfg);
-        if (!estbe::d2h(ticks.data(), dbg_ticks, n_cfg * 8, stream) && !estbe::sync(stream)) {
+        std::vector<uint64_t> ticks(dbg_words);
+        if (!estbe::d2h(ticks.data(), dbg_ticks, dbg_words * 8, stream) && !estbe::sync(stream)) {
             if (FILE *f = fopen(dbg_path, "wb")) {
-                fwrite(ticks.data(), 8, n_cfg, f);
+                fwrite(ticks.data(), 8, dbg_words, f);
                 fwrite(st2.dbg_cnt, 8, sizeof st2.dbg_cnt / 8, f);  // then the diagnostic counters
                 fclose(f);
             }

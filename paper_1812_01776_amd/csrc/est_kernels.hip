@@ -19,9 +19,12 @@ int check(hipError_t e, const char *what) {
 }
 
 // Four wavefronts per workgroup; each wavefront owns one scratch slot and its own part of the LDS
-// and works through candidates until the launch's work counter runs out.
+// and works through candidates until the launch's work counter runs out.  The register budget is
+// pinned at 128 per lane (four wavefronts per SIMD): one register more would cost a quarter of the
+// resident wavefronts, which costs more than the few spills this forces.
 #define EST_WAVES_PER_BLOCK 4
-__global__ __launch_bounds__(64 * EST_WAVES_PER_BLOCK) void est_sim_kernel(EstSimArgs a) {
+__global__ __launch_bounds__(64 * EST_WAVES_PER_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void est_sim_kernel(EstSimArgs a) {
     extern __shared__ uint64_t lds[];  // EST_WAVES_PER_BLOCK x a.lds_bytes
     const uint32_t wave = threadIdx.x >> 6;
     const uint32_t slot = blockIdx.x * EST_WAVES_PER_BLOCK + wave;

@@ -320,3 +320,43 @@ def random_case(seed, S=None, n=None, C=None, max_b=8, max_r=4, H=2, small_times
     rp = rng.integers(1, max_r + 1, size=(C, S)).astype(np.uint16)
     slo = int(lat.max()) * 2
     return Workload("rand%d" % seed, parents, lat, cost, arr, mask, hw, bt, rp, slo)
+
+
+def backlog_case(seed):
+    """A small overloaded pipeline: service times far above the arrival gaps, so queues stay long,
+    batches run full and replicas rotate.  Every fourth seed quantises all times (replicas fall
+    into lock step and completions tie), every seventh starts so late that queueing runs into the
+    2^32-1 us horizon, every third has stages with maximum batch size 1."""
+    rng = np.random.default_rng(1000 + seed)
+    S = int(rng.integers(1, 4))
+    n = int(rng.integers(500, 3000))
+    C, H, Bmax = 4, 1, 32
+    if seed % 4 == 3:
+        parents = [[], [0], [0], [1, 2]]
+        S = 4
+    else:
+        parents = [[]] + [[s - 1] for s in range(1, S)]
+    quantum = [1, 10, 100, 1000][seed % 4] if seed % 2 == 0 else 1
+    a = rng.integers(50, 3000, size=(S, H))
+    c = rng.integers(1, 200, size=(S, H))
+    lat = (a[:, :, None] + c[:, :, None] * np.arange(1, Bmax + 1)[None, None, :]).astype(np.uint32)
+    lat = np.maximum(lat // quantum * quantum, quantum).astype(np.uint32)
+    g = int(rng.integers(2, 400))
+    gaps = rng.integers(0, g, size=n)
+    if quantum > 1 and rng.random() < 0.5:
+        gaps = gaps // quantum * quantum
+    base = 0
+    if seed % 7 == 3:
+        base = 2**32 - 2 - int(gaps.sum()) - 2 * S * int(lat.max()) - 1
+    arr = (base + np.cumsum(gaps)).astype(np.uint32)
+    mask = np.zeros(n, np.uint32)
+    for s in range(S):
+        p = 1.0 if rng.random() < 0.6 else rng.uniform(0.3, 1.0)
+        mask |= (rng.random(n) < p).astype(np.uint32) << np.uint32(s)
+    cost = np.full((S, H), 5, np.uint64)
+    hw = np.zeros((C, S), np.uint8)
+    sizes = [2, 2, 3, 4, 4, 5, 8, 8, 16, 32] if seed % 3 else [1, 1, 1, 2, 4, 16]
+    bt = rng.choice(sizes, size=(C, S)).astype(np.uint8)
+    rp = rng.choice([1, 1, 2, 2, 3, 4, 5, 8], size=(C, S)).astype(np.uint16)
+    return Workload("backlog%d" % seed, parents, lat, cost, arr, mask, hw, bt, rp, int(lat.max()))
+

@@ -74,6 +74,13 @@ def test_random_dags(seed):
     _compare(workloads.random_case(seed, tie_heavy=(seed % 2 == 0)))
 
 
+@pytest.mark.parametrize("seed", range(56))
+def test_backlog_lockstep_and_horizon_cases(seed):
+    """Overloaded pipelines: full batches in rotation, replicas in lock step (tied completions), maximum
+    batch size 1 with ties out of query order, queueing that runs into the horizon."""
+    _compare(workloads.backlog_case(seed))
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_wide_batches_many_replicas_ties(seed):
     """R up to 16, B up to 64, several thousand queries (bounded rings wrap, ragged tails), times on a

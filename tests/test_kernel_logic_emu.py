@@ -56,6 +56,13 @@ def test_random_dags_match_oracle(seed):
     _compare(workloads.random_case(seed, tie_heavy=(seed % 2 == 0)))
 
 
+@pytest.mark.parametrize("seed", range(28))
+def test_backlog_lockstep_and_horizon_cases_match_oracle(seed):
+    # long queues: full batches in rotation, replicas in lock step (tied completions), maximum batch
+    # size 1 with ties out of query order, queueing that runs into the horizon
+    _compare(workloads.backlog_case(seed))
+
+
 def test_wide_batches_many_replicas_and_ring_wrap():
     """R up to 16, B up to 64 and enough queries for the bounded rings to wrap several times; every
     time a multiple of 10 so that batches complete together and have to be merged by query index."""
