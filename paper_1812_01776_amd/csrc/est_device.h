@@ -227,6 +227,7 @@ EST_DEV bool scan_emit(const EstOp &op, const uint32_t *lslots, uint64_t E, uint
     return true;
 }
 
+template <bool DIAG>
 EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     const uint32_t ln = wv::lane();
     const EstPlan &P = *c.P;
@@ -238,7 +239,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     const uint32_t Lmine = ln < B ? Ltab[ln] : 0u;  // lane l holds L(l+1)
     const uint32_t L1 = wv::bcast(Lmine, 0);
     // the light-load shortcut below needs: no batch is faster than a single query
-    const bool mono = wv::ballot(ln < B && Lmine < L1) == 0;
+    const bool mono = (lanes_below(B) & wv::ballot(Lmine < L1)) == 0;
     uint32_t *g_end = c.rep + op.rep_off, *g_cnt = g_end + op.r_max, *g_slot = g_cnt + op.r_max;
     uint32_t *g_slots = c.slots + op.slot_off;
     uint64_t *lkey = c.lds;
@@ -250,6 +251,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
 
     // replica table, sorted by the time the replica is free again
     const bool isrep = ln < R;
+    const uint64_t REP = lanes_below(R);  // (lanes beyond the table hold end = 2^32-1, count 0)
     uint32_t rend = isrep ? g_end[ln] : 0xFFFFFFFFu;
     uint32_t rcnt = isrep ? g_cnt[ln] : 0u;
     uint32_t rslot = isrep ? g_slot[ln] : 0u;
@@ -291,6 +293,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
 #endif
     uint32_t fp_skip = 0;   // general batches still to do before the light-load shortcut is tried again
     uint32_t sat_skip = 0;  // the same for the backlog shortcut
+    uint32_t single_skip = 0;  // and for the one-query-per-batch shortcut
     uint32_t d_gen = 0, d_gene = 0, d_fp = 0, d_fpe = 0, d_b1 = 0, d_b1e = 0, d_sat = 0, d_sate = 0, d_hz = 0;  // diagnostics
 
     for (;;) {
@@ -303,13 +306,14 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             const uint64_t k0 = ln < w0 ? in.base[(rraw + ln) & in.mask] : 0ull;
             const uint64_t k1 = ln < w1 ? in.base[(rraw + 64 + ln) & in.mask] : 0ull;
             const uint64_t k2 = ln < w2 ? in.base[(rraw + 128 + ln) & in.mask] : 0ull;
+            // (lane masks are combined as scalars: one vector compare per term)
+            uint64_t A0 = lanes_below(w0), A1 = lanes_below(w1), A2 = lanes_below(w2);
             bool a0 = ln < w0, a1 = ln < w1, a2 = ln < w2;
-            if (op.filtered) {
-                a0 = a0 && (acc[(uint32_t)k0] & 1u);
-                a1 = a1 && (acc[(uint32_t)k1] & 1u);
-                a2 = a2 && (acc[(uint32_t)k2] & 1u);
+            if (op.filtered) {  // (lanes beyond a window hold key 0: query 0 exists)
+                const bool f0 = (acc[(uint32_t)k0] & 1u) != 0u, f1 = (acc[(uint32_t)k1] & 1u) != 0u, f2 = (acc[(uint32_t)k2] & 1u) != 0u;
+                A0 &= wv::ballot(f0); A1 &= wv::ballot(f1); A2 &= wv::ballot(f2);
+                a0 = a0 && f0; a1 = a1 && f1; a2 = a2 && f2;
             }
-            const uint64_t A0 = wv::ballot(a0), A1 = wv::ballot(a1), A2 = wv::ballot(a2);
             if (a0) { const uint32_t i = (ltail + popc64(A0 & below)) & (SCAN_INRING - 1); lkey[i] = k0; lpos[i] = rraw + ln; }
             ltail += popc64(A0);
             if (a1) { const uint32_t i = (ltail + popc64(A1 & below)) & (SCAN_INRING - 1); lkey[i] = k1; lpos[i] = rraw + 64 + ln; }
@@ -370,29 +374,30 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                     const uint32_t e = sat_add(fk, LB);
                     const uint32_t nfull = (w * inv_b) >> 16;
                     const uint32_t lastr = wv::shfl(rdy, kb * B + B - 1u);
-                    const uint64_t okm = wv::ballot(ln < nfull * B && lastr <= fk && e != 0xFFFFFFFFu);
+                    const uint64_t okm = lanes_below(nfull * B) & wv::ballot(lastr <= fk) & wv::ballot(e != 0xFFFFFFFFu);
                     const uint32_t nl = okm == ~0ull ? 64u : ctz64(~okm);  // a multiple of B: the test is per batch
                     nacc = (nl * inv_b) >> 16;
                     if (nacc >= 2) {
                         const uint32_t na = nacc * B;
                         const uint32_t Tlast = wv::bcast(fk, na - 1u);
-                        const uint64_t E = wv::ballot(isrep && rcnt > 0 && rend <= Tlast);
-                        const bool direct = ln < na && e <= Tlast;  // replaced again inside this step: never waits
-                        const uint32_t nd = popc64(wv::ballot(direct));
+                        const uint64_t E = wv::ballot(rcnt > 0) & wv::ballot(rend <= Tlast);
+                        const uint64_t D = lanes_below(na) & wv::ballot(e <= Tlast);  // replaced again inside this step: never wait
+                        const bool direct = ln < na && e <= Tlast;
+                        const uint32_t nd = popc64(D);
                         if (popc64(E) * B + nd > space) {
                             nacc = 0;  // tight output ring: batch by batch
                         } else {
                             scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress);
                             const uint32_t eprev = wv::shr1(e), qprev = wv::shr1(q), kprev = wv::shr1(kb);
                             uint64_t okey = direct ? (((uint64_t)e << 32) | q) : ~0ull;
-                            if (wv::ballot(direct && ln > 0 && eprev == e && qprev > q)) okey = sort_lanes64(okey);
+                            if (D & ~1ull & wv::ballot(eprev == e) & wv::ballot(qprev > q)) okey = sort_lanes64(okey);
                             if (ln < nd) out[(wr + ln) & omask] = okey;  // (times ascend with the batch: a prefix)
                             wr += nd;
                             space -= nd;
                             EST_CHK_ORDER(6);
                             // members wait sorted by query index
                             uint32_t qs = q;
-                            if (wv::ballot(ln >= nd && ln < na && ln > 0 && kprev == kb && qprev > q))
+                            if (lanes_below(na) & ~lanes_below(umax(nd, 1u)) & wv::ballot(kprev == kb) & wv::ballot(qprev > q))
                                 qs = (uint32_t)sort_lanes64(ln < na ? (((uint64_t)kb << 32) | q) : ~0ull);
                             const uint32_t myslot = wv::shfl(rslot, km);
                             if (ln >= nd && ln < na) lslots[myslot * bm + (ln - kb * B)] = qs;
@@ -419,7 +424,11 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 if (nacc < 2) sat_skip = 4;
             }
         }
-        if (B == 1 && L1 > 0) {
+        const bool b1 = B == 1 && L1 > 0;
+        // With larger batch sizes the same evaluation holds as long as no query waits and no two become
+        // ready together: then every query is a batch of its own, started on arrival.
+        const bool single = !b1 && B > 1 && mono && L1 > 0 && single_skip == 0 && w >= 16 && wv::ballot(rcnt > 0) == 0;
+        if (b1 || single) {
             // Maximum batch size 1: every query is its own batch and the service time is the constant
             // L(1), so completions keep the input order and query i runs on the replica that served
             // query i-R:  end_i = max(ready_i, end_{i-R}) + L(1).  The sorted replica table is exactly
@@ -432,38 +441,61 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 const uint32_t inc = (uint64_t)mul * L1 > 0xFFFFFFFFull ? 0xFFFFFFFFu : mul * L1;
                 if (ln >= d) x = umax(x, sat_add(y, inc));
             }
-            // Queries that complete at the same time leave ordered by query index.  Since
-            // end_i > end_{i-R}, such a run has at most R members; a shorter run at the end of what can
-            // be written now may continue with the next query, and is kept back until that is known
-            // (times clamped at the horizon need no order).
-            const uint32_t xp = wv::shr1(x);
-            const uint32_t qp = wv::shr1(q);
-            const uint64_t bnd = wv::ballot(ln > 0 && ln < w && x != xp) | 1ull;  // starts of runs
             const bool last = staged <= 64 && rraw == in.wr && in.fin;
             uint32_t m = umin(w, space);
-            if (m > 0) {
-                const uint32_t s0 = 63u - (uint32_t)__builtin_clzll(bnd & lanes_below(m));  // start of the run of lane m-1
-                const uint32_t xl = wv::bcast(x, m - 1u);
-                const bool complete = m < w ? wv::bcast(x, m) != xl : (last || xl == 0xFFFFFFFFu || m - s0 >= R);
-                if (!complete) m = s0;
+            bool sorted = true;
+            if (single) {
+                // the leading queries that start on arrival, each alone at its ready time (the one after
+                // it must be seen to become ready later); completion times then ascend strictly, and
+                // whatever is dispatched later finishes later still
+                const uint32_t rnext = wv::shl1(rdy);
+                const uint64_t gm = lanes_below(w) & wv::ballot(x == sat_add(rdy, L1)) & wv::ballot(x != 0xFFFFFFFFu) &
+                                    ((wv::ballot(rdy != rnext) & lanes_below(w - 1u)) | (last ? 1ull << (w - 1u) : 0ull));
+                const uint32_t m1 = gm == ~0ull ? 64u : ctz64(~gm);
+                if (m1 < 12) {
+                    single_skip = 6;  // not the regime: leave it alone for a few steps
+                    m = 0;
+                } else {
+                    m = umin(m1, space);
+                    if (m == 0) break;  // wait for the consumer
+                }
+            } else {
+                // Queries that complete at the same time leave ordered by query index.  Since
+                // end_i > end_{i-R}, such a run has at most R members; a shorter run at the end of what
+                // can be written now may continue with the next query, and is kept back until that is
+                // known (times clamped at the horizon need no order).
+                const uint32_t xp = wv::shr1(x);
+                const uint32_t qp = wv::shr1(q);
+                const uint64_t bnd = (lanes_below(w) & wv::ballot(x != xp)) | 1ull;  // starts of runs
+                if (m > 0) {
+                    const uint32_t s0 = 63u - (uint32_t)__builtin_clzll(bnd & lanes_below(m));  // start of the run of lane m-1
+                    const uint32_t xl = wv::bcast(x, m - 1u);
+                    const bool complete = m < w ? wv::bcast(x, m) != xl : (last || xl == 0xFFFFFFFFu || m - s0 >= R);
+                    if (!complete) m = s0;
+                }
+                if (m == 0) break;  // wait for the consumer, or for the rest of the run
+                sorted = (lanes_below(m) & ~1ull & wv::ballot(x == xp) & wv::ballot(q < qp) & wv::ballot(x != 0xFFFFFFFFu)) == 0;
             }
-            if (m == 0) break;  // wait for the consumer, or for the rest of the run
-            uint64_t okey = ln < m ? (((uint64_t)x << 32) | q) : ~0ull;
-            if (wv::ballot(ln > 0 && ln < m && x == xp && q < qp && x != 0xFFFFFFFFu)) okey = sort_lanes64(okey);
-            if (ln < m) out[(wr + ln) & omask] = okey;
-            wr += m;
-            space -= m;
-            ++d_b1; d_b1e += m;
-            EST_CHK_ORDER(1);
-            // the table becomes the last R completion times
-            const uint32_t keep = R > m ? R - m : 0u;  // old entries that stay
-            const uint32_t told = wv::shfl(rend, ln + m);
-            const uint32_t tnew = wv::shfl(x, ln + m - R);
-            if (isrep) rend = ln < keep ? told : tnew;
-            lhead += m;
-            progress = true;
-            continue;
-        } else if (mono && fp_skip == 0) {
+            if (m > 0) {
+                uint64_t okey = ln < m ? (((uint64_t)x << 32) | q) : ~0ull;
+                if (!sorted) okey = sort_lanes64(okey);
+                if (ln < m) out[(wr + ln) & omask] = okey;
+                wr += m;
+                space -= m;
+                ++d_b1; d_b1e += m;
+                EST_CHK_ORDER(1);
+                // the table becomes the last R completion times
+                const uint32_t keep = R > m ? R - m : 0u;  // old entries that stay
+                const uint32_t told = wv::shfl(rend, ln + m);
+                const uint32_t tnew = wv::shfl(x, ln + m - R);
+                if (isrep) rend = ln < keep ? told : tnew;
+                lhead += m;
+                progress = true;
+                continue;
+            }
+        }
+        if (single_skip) --single_skip;
+        if (mono && fp_skip == 0) {
             // Light load: as long as every group of queries that become ready at the same instant
             // finds an idle replica at that instant and fits one batch, each group is one batch started
             // at its ready time r and finished at r + L(group size).  A whole run of groups is
@@ -475,10 +507,11 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             // (group k takes the replica of group k-p, which must be free again by then); replicas
             // still busy are left alone.
             const uint32_t r0 = wv::uniform(rdy);
-            const uint64_t E0 = wv::ballot(isrep && rcnt > 0 && rend <= r0);
+            const uint64_t idle0 = REP & wv::ballot(rend <= r0);
+            const uint64_t E0 = idle0 & wv::ballot(rcnt > 0);
             if (E0 && !scan_emit(op, lslots, E0, rend, rcnt, rslot, out, omask, wr, space, progress)) break;
             EST_CHK_ORDER(5);
-            const uint32_t pidle = popc64(wv::ballot(isrep && rend <= r0));  // idle now: a prefix of the sorted table
+            const uint32_t pidle = popc64(idle0);  // idle now: a prefix of the sorted table
             uint32_t m = 0;
             if (pidle > 0) {
                 uint32_t *lend = ltab + 192, *lg = ltab + 256, *luns = ltab + 320;  // per group: end, size, waits
@@ -487,10 +520,11 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 // members j*B .. j*B+B-1, as the queue would hand them out)
                 const uint32_t rprev = wv::shr1(rdy);
                 const uint64_t upto = below | (1ull << ln);
-                const uint64_t runs = wv::ballot(ln < w && (ln == 0 || rdy != rprev));
+                const uint64_t WM = lanes_below(w);
+                const uint64_t runs = WM & (wv::ballot(rdy != rprev) | 1ull);
                 const uint32_t off = ln - (63u - (uint32_t)__builtin_clzll((runs & upto) | 1ull));
                 const uint32_t inv_b = (65536u + B - 1u) / B;                  // floor(x / B) = x * inv_b >> 16 for x < 64
-                const uint64_t heads = wv::ballot(ln < w && off == B * ((off * inv_b) >> 16));  // first query of each group
+                const uint64_t heads = WM & wv::ballot(off == B * ((off * inv_b) >> 16));  // first query of each group
                 const uint32_t bid = popc64(heads & upto) - 1u;                // group index of this lane
                 const uint32_t start = 63u - (uint32_t)__builtin_clzll(heads & upto);
                 const uint64_t later = ln == 63 ? 0ull : (heads >> (ln + 1));
@@ -504,31 +538,30 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 // replicas that serve the run: the table's first p entries, each free by the time its turn
                 // comes (group l takes entry l); later groups take the replica of the group p before them
                 const uint32_t ngroups = popc64(heads);
-                const uint64_t usable = wv::ballot(isrep && ln < ngroups && rend <= lrdy[ln < ngroups ? ln : 0]);
+                const uint64_t usable = REP & lanes_below(ngroups) & wv::ballot(rend <= lrdy[ln < ngroups ? ln : 0]);
                 const uint32_t p = usable == ~0ull ? 64u : ctz64(~usable);     // >= 1: entry 0 is idle now
                 // a tie between two older waiting batches caps the run (their order is settled elsewhere),
                 // and no new completion time may equal an older waiting one
-                const uint64_t busyp = wv::ballot(isrep && rcnt > 0);  // all of these end after r0
+                const uint64_t busyp = wv::ballot(rcnt > 0);  // all of these end after r0
                 const uint32_t rend_next = wv::shl1(rend);
                 const uint32_t rcnt_next = wv::shl1(rcnt);
-                const uint64_t tiep = wv::ballot(isrep && ln + 1 < R && rend > r0 && rend == rend_next && (rcnt > 0 || rcnt_next > 0));
+                const uint64_t tiep = lanes_below(R - 1u) & wv::ballot(rend > r0) & wv::ballot(rend == rend_next) & (busyp | wv::ballot(rcnt_next > 0));
                 const uint32_t ecap = tiep ? wv::bcast(rend, ctz64(tiep)) : 0xFFFFFFFFu;
-                bool ok = ln < w && e < ecap && g <= B;  // (ecap <= 2^32-1: a clamped time never passes)
+                uint64_t okm = WM & wv::ballot(e < ecap) & wv::ballot(g <= B);  // (ecap <= 2^32-1: a clamped time never passes)
                 for (uint64_t pm = busyp; pm; pm &= pm - 1) {
                     const uint32_t ep = wv::bcast(rend, ctz64(pm));
-                    ok = ok && e != ep;
+                    okm &= wv::ballot(e != ep);
                 }
-                ok = ok && (nh < w || final || g == B);                  // the whole group is in view (or it is full)
-                ok = ok && (bid < p || lend[bid - p] <= rdy);            // its replica is free again
-                const uint64_t okm = wv::ballot(ok);
+                okm &= final ? ~0ull : (wv::ballot(nh < w) | wv::ballot(g == B));                    // the whole group is in view (or it is full)
+                okm &= wv::ballot(bid < p) | wv::ballot(lend[bid >= p ? bid - p : 0u] <= rdy);     // its replica is free again
                 m = okm == ~0ull ? 64u : ctz64(~okm);                    // (a group is accepted or rejected as a whole)
                 if (m > 0) {
                     // the next batch starts no earlier than the next query's ready time; if the run took
                     // the whole window, that is at least the window's last ready time
                     const bool tau_inf = m >= w && final;                // nothing follows at all
                     const uint32_t tau = tau_inf ? 0xFFFFFFFFu : sat_add(wv::bcast(rdy, umin(m, w - 1u)), L1);
+                    const uint64_t safem = lanes_below(m) & (tau_inf ? ~0ull : wv::ballot(e < tau));
                     const bool safe = ln < m && (tau_inf || e < tau);
-                    const uint64_t safem = wv::ballot(safe);
                     const uint32_t ns = popc64(safem);
                     // older waiting batches that finish before tau go out with the run
                     uint32_t extra = 0;
@@ -540,12 +573,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                         woven |= 1ull << j;
                         extra += cj;
                     }
-#ifdef EST_DBG_NOWAIT
-                    const bool dbg_fail = wv::ballot(ln < m && !safe) != 0;
-#else
-                    const bool dbg_fail = false;
-#endif
-                    if (ns + extra > space || dbg_fail) {
+                    if (ns + extra > space) {
                         m = 0;  // leave it to the general path (or to the consumer)
                     } else {
                         // order the run's own output: usually already ordered
@@ -555,7 +583,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                         const uint32_t eprev1 = wv::shr1(e);
                         const uint32_t qprev = wv::shr1(q);
                         const uint32_t bprev = wv::shr1(bid);
-                        uint64_t inv = wv::ballot(ln > 0 && ln < m && (eprev1 > e || (eprev1 == e && qprev > q)));
+                        uint64_t inv = lanes_below(m) & ~1ull & (wv::ballot(eprev1 > e) | (wv::ballot(eprev1 == e) & wv::ballot(qprev > q)));
                         if (inv) {
                             // exact test: an earlier safe query finishes later, or at the same time in another group
                             uint32_t pmax = safe ? e : 0u;               // inclusive prefix maximum of e over safe lanes
@@ -564,7 +592,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                                 if (ln >= d) pmax = umax(pmax, y);
                             }
                             const uint32_t pbefore = wv::shr1(pmax);
-                            inv = wv::ballot(safe && ln > 0 && (pbefore > e || (pbefore == e && bprev != bid)));
+                            inv = safem & ~1ull & (wv::ballot(pbefore > e) | (wv::ballot(pbefore == e) & wv::ballot(bprev != bid)));
                         }
                         uint32_t orank = popc64(safem & below);
                         if (inv) {
@@ -572,6 +600,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                             orank = ln;
                         }
                         const bool emit_me = inv ? ln < ns : safe;
+                        const uint64_t emitm = inv ? lanes_below(ns) : safem;
                         const uint32_t ke = (uint32_t)(key >> 32);
                         uint32_t shift = 0;
                         for (uint64_t pm = woven; pm; pm &= pm - 1) {
@@ -584,7 +613,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                         for (uint64_t pm = woven; pm; pm &= pm - 1) {
                             const uint32_t j = ctz64(pm);
                             const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j), sj = wv::bcast(rslot, j);
-                            const uint32_t pos = wr + before + popc64(wv::ballot(emit_me && ke < ej));
+                            const uint32_t pos = wr + before + popc64(emitm & wv::ballot(ke < ej));
                             if (ln < cj) out[(pos + ln) & omask] = ((uint64_t)ej << 32) | lslots[sj * bm + ln];
                             before += cj;
                         }
@@ -611,7 +640,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                             ccnt = luns[klast] ? lg[klast] : 0u;
                         }
                         uint32_t trank = 0;
-                        if (!inv && !wv::ballot(waits) && p == pidle) {
+                        if (!inv && !(lanes_below(m) & ~safem) && p == pidle) {
                             // common case: nothing waits and the new completion times ascend with the group
                             // index, so lanes [0,p) hold, in order, the unused idle entries (still <= r0,
                             // lanes nb..p-1) and then the served ones in ascending time; only the busy
@@ -620,13 +649,13 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                             // served lane j holds group klast(j); in time order these are lanes
                             // (nb mod p), (nb mod p)+1, ..., wrapping: position = (j - nb) mod p
                             const uint32_t nbm = nb - p * ((nb * inv_p) >> 16);
-                            const bool is_n = ln < nn, is_a = ln >= nn && ln < p, is_b = isrep && ln >= p;
+                            const bool is_n = ln < nn, is_a = ln >= nn && ln < p;
                             uint32_t rank_n = na + (nb >= p ? (ln >= nbm ? ln - nbm : ln + p - nbm) : ln);
                             uint32_t rank_b = na + nn + (ln - p);
-                            for (uint64_t bm2 = wv::ballot(is_b); bm2; bm2 &= bm2 - 1) {
+                            for (uint64_t bm2 = REP & ~lanes_below(p); bm2; bm2 &= bm2 - 1) {
                                 const uint32_t j = ctz64(bm2);
                                 const uint32_t ej = wv::bcast(cend, j);
-                                const uint32_t more_new = popc64(wv::ballot(is_n && cend > ej));  // new entries after this busy one
+                                const uint32_t more_new = popc64(lanes_below(nn) & wv::ballot(cend > ej));  // new entries after this busy one
                                 if (ln == j) rank_b -= more_new;
                                 if (is_n && cend > ej) rank_n += 1;
                             }
@@ -657,7 +686,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         const uint32_t f = wv::uniform(rend);  // earliest free replica = lane 0
         const uint32_t r0 = wv::uniform(rdy);
         const uint32_t T = umax(f, r0);  // dispatch time of the next batch
-        const uint64_t mm = wv::ballot(ln < umin(w, B) && rdy <= T);
+        const uint64_t mm = lanes_below(umin(w, B)) & wv::ballot(rdy <= T);
         const uint32_t b = popc64(mm);
         EST_CHECK(b >= 1 && mm == lanes_below(b));
         // The batch is known once it is full, or a later query is seen to be ready only after T,
@@ -665,13 +694,13 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         const bool decidable = (b == B) || (b < w) || in.fin;
         if (!decidable) break;
         // everything that completes by T leaves before this batch is dispatched
-        const uint64_t E = wv::ballot(isrep && rcnt > 0 && rend <= T);
+        const uint64_t E = wv::ballot(rcnt > 0) & wv::ballot(rend <= T);
         if (E && !scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress)) break;
         EST_CHK_ORDER(4);
         // members wait in the replica's slot sorted by query index
         if (b > 1) {
             const uint32_t prev = wv::shr1(q);
-            if (wv::ballot(ln > 0 && ln < b && q < prev)) {
+            if (lanes_below(b) & ~1ull & wv::ballot(q < prev)) {
                 uint32_t width = 2;
                 while (width < b) width <<= 1;
                 q = sort_lanes(ln < b ? q : 0xFFFFFFFFu, width);
@@ -682,7 +711,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         if (ln < b) lslots[slot * bm + ln] = q;
         const uint32_t end = sat_add(T, wv::bcast(Lmine, b - 1));
         // drop lane 0 from the table and insert the new entry so that the table stays sorted
-        const uint32_t p = popc64(wv::ballot(ln >= 1 && isrep && rend <= end));
+        const uint32_t p = popc64(REP & ~1ull & wv::ballot(rend <= end));
         const uint32_t nend = wv::shl1(rend), ncnt = wv::shl1(rcnt), nslot = wv::shl1(rslot);
         if (ln < p) {
             rend = nend; rcnt = ncnt; rslot = nslot;
@@ -694,7 +723,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         progress = true;
     }
 
-    if (c.a->dbg_ticks && ln == 0) {
+    if (DIAG && c.a->dbg_ticks && ln == 0) {
         uint64_t *dc = c.a->status->dbg_cnt;
         wv::atomic_add_u64(dc + 0, d_gen); wv::atomic_add_u64(dc + 1, d_fp); wv::atomic_add_u64(dc + 2, d_fpe);
         wv::atomic_add_u64(dc + 3, d_b1); wv::atomic_add_u64(dc + 4, d_b1e); wv::atomic_add_u64(dc + 7, 1);
@@ -737,6 +766,7 @@ EST_DEV uint64_t eff_key(uint64_t key, uint32_t j, uint32_t l) {
     return (uint32_t)(key >> 32) == 0xFFFFFFFFu ? (0xFFFFFFFF00000000ull | (uint64_t)(j << 8) | l) : key;
 }
 
+template <bool DIAG>
 EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     const uint32_t ln = wv::lane();
     const EstPlan &P = *c.P;
@@ -779,8 +809,9 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             const uint32_t w = umin(64u, sv.wr - rc);
             const uint64_t key = ln < w ? sv.base[(rc + ln) & sv.mask] : 0ull;
             const uint32_t q = (uint32_t)key;
-            const bool a = ln < w && (acc[q] & 1u);
-            const uint64_t A = wv::ballot(a);
+            const bool fa = (acc[q] & 1u) != 0u;  // (idle lanes look at query 0)
+            const uint64_t A = lanes_below(w) & wv::ballot(fa);
+            const bool a = ln < w && fa;
             const uint32_t pos = wr + popc64(A & below);
             if (a) {
                 if (is_lat) {
@@ -859,7 +890,7 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             const uint64_t rk = have ? skey[j * 64 + ln] : 0ull;
             const uint64_t x = eff_key(rk, j, ln);
             const bool emit = have && x <= bound;
-            m_src[j] = popc64(wv::ballot(emit));
+            m_src[j] = popc64(lanes_below(nst[j]) & wv::ballot(x <= bound));
             if (emit) {
                 uint32_t rank = ln;
                 for (uint32_t j2 = 0; j2 < K; ++j2) {
@@ -879,7 +910,7 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             m_total += m_src[j];
         }
         EST_CHECK(m_total >= 1);
-        if (c.a->dbg_ticks && ln == 0) { wv::atomic_add_u64(c.a->status->dbg_cnt + 5, 1); wv::atomic_add_u64(c.a->status->dbg_cnt + 6, m_total); }
+        if (DIAG && c.a->dbg_ticks && ln == 0) { wv::atomic_add_u64(c.a->status->dbg_cnt + 5, 1); wv::atomic_add_u64(c.a->status->dbg_cnt + 6, m_total); }
         wv::sync();
         // ---- walk the merged run; a query fed by several sources is passed on at its last appearance
         for (uint32_t base = 0; base < m_total; base += 64) {
@@ -897,7 +928,7 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                     for (uint64_t todo = MM; todo;) {
                         const uint32_t l = ctz64(todo);
                         const uint32_t sq = wv::bcast(q, l);
-                        const uint64_t same = wv::ballot(multi && q == sq);
+                        const uint64_t same = MM & wv::ballot(q == sq);
                         if (multi && q == sq) {
                             duprank = popc64(same & below);
                             duptotal = popc64(same);
@@ -956,6 +987,7 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
 // One wavefront = one candidate.  Every loop ends: an operation that consumes or emits nothing
 // reports no progress, and a full pass over the operations without progress stops the candidate with
 // an error flag.
+template <bool DIAG>
 EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *lds) {
     const uint32_t ln = wv::lane();
     const EstPlan &P = *a.plan;
@@ -990,9 +1022,9 @@ EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *
         for (uint32_t opi = 0; opi < P.n_ops; ++opi) {
             if (c.st[P.done_off + opi]) continue;
             const EstOp &op = P.ops[opi];
-            const uint64_t k0 = a.dbg_ticks ? wv::ticks() : 0;
-            bool p = op.type == EST_OP_SCAN ? scan_run(c, op, opi) : merge_run(c, op, opi);
-            if (a.dbg_ticks && ln == 0) {
+            const uint64_t k0 = (DIAG && a.dbg_ticks) ? wv::ticks() : 0;
+            bool p = op.type == EST_OP_SCAN ? scan_run<DIAG>(c, op, opi) : merge_run<DIAG>(c, op, opi);
+            if (DIAG && a.dbg_ticks && ln == 0) {
                 const uint32_t at = op.type == EST_OP_SCAN ? 8 + 3 * EST_MAX_STAGES + op.stage
                                                            : 8 + 4 * EST_MAX_STAGES + (op.type == EST_OP_LAT ? 1 : 0);
                 wv::atomic_add_u64(a.status->dbg_cnt + at, wv::ticks() - k0);
@@ -1067,20 +1099,21 @@ EST_DEV void select_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_
 // A wavefront takes candidates from the launch's work counter until none is left, simulating each
 // in its own scratch slot and, unless per-query latencies were asked for, selecting the P99 right
 // away from the slot's latency array.
+template <bool DIAG>
 EST_DEV void slot_loop(const EstSimArgs &a, uint32_t slot, uint64_t *lds) {
     for (;;) {
         uint32_t t = 0;
         if (wv::lane() == 0) t = wv::fetch_add_u32(&a.status->next_cfg, 1u);
         t = wv::bcast(t, 0);
         if (t >= a.n_cfg) break;
-        const uint64_t t0 = a.dbg_ticks ? wv::ticks() : 0;
-        if (a.n > 0) sim_wave(a, t, slot, lds);
+        const uint64_t t0 = (DIAG && a.dbg_ticks) ? wv::ticks() : 0;
+        if (a.n > 0) sim_wave<DIAG>(a, t, slot, lds);
         wv::sync();
-        const uint64_t k1 = a.dbg_ticks ? wv::ticks() : 0;
+        const uint64_t k1 = (DIAG && a.dbg_ticks) ? wv::ticks() : 0;
         if (!a.lat_by_qid) select_wave(a, t, slot, lds);
         wv::sync();
-        if (a.dbg_ticks && wv::lane() == 0) wv::atomic_add_u64(a.status->dbg_cnt + 8 + 4 * EST_MAX_STAGES + 2, wv::ticks() - k1);
-        if (a.dbg_ticks && wv::lane() == 0) a.dbg_ticks[t] = wv::ticks() - t0;
+        if (DIAG && a.dbg_ticks && wv::lane() == 0) wv::atomic_add_u64(a.status->dbg_cnt + 8 + 4 * EST_MAX_STAGES + 2, wv::ticks() - k1);
+        if (DIAG && a.dbg_ticks && wv::lane() == 0) a.dbg_ticks[t] = wv::ticks() - t0;
     }
 }
 

@@ -23,12 +23,12 @@ int check(hipError_t e, const char *what) {
 // pinned at 128 per lane (four wavefronts per SIMD): one register more would cost a quarter of the
 // resident wavefronts, which costs more than the few spills this forces.
 #define EST_WAVES_PER_BLOCK 4
-__global__ __launch_bounds__(64 * EST_WAVES_PER_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4)))
-void est_sim_kernel(EstSimArgs a) {
+template <bool DIAG>
+__global__ __launch_bounds__(64 * EST_WAVES_PER_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4))) void est_sim_kernel(EstSimArgs a) {
     extern __shared__ uint64_t lds[];  // EST_WAVES_PER_BLOCK x a.lds_bytes
     const uint32_t wave = threadIdx.x >> 6;
     const uint32_t slot = blockIdx.x * EST_WAVES_PER_BLOCK + wave;
-    if (slot < a.n_slots) estdev::slot_loop(a, slot, lds + (size_t)wave * (a.lds_bytes / 8));
+    if (slot < a.n_slots) estdev::slot_loop<DIAG>(a, slot, lds + (size_t)wave * (a.lds_bytes / 8));
 }
 
 __global__ __launch_bounds__(256) void est_prep1_kernel(EstPrepArgs a) {
@@ -129,7 +129,11 @@ int launch_prep2(const EstPrepArgs &a, void *stream) {
 }
 int launch_sim(const EstSimArgs &a, void *stream) {
     const uint32_t blocks = (a.n_slots + EST_WAVES_PER_BLOCK - 1) / EST_WAVES_PER_BLOCK;
-    est_sim_kernel<<<blocks, 64 * EST_WAVES_PER_BLOCK, (size_t)a.lds_bytes * EST_WAVES_PER_BLOCK, (hipStream_t)stream>>>(a);
+    // (the variant that keeps diagnostic counters is launched only when they are asked for)
+    if (a.dbg_ticks)
+        est_sim_kernel<true><<<blocks, 64 * EST_WAVES_PER_BLOCK, (size_t)a.lds_bytes * EST_WAVES_PER_BLOCK, (hipStream_t)stream>>>(a);
+    else
+        est_sim_kernel<false><<<blocks, 64 * EST_WAVES_PER_BLOCK, (size_t)a.lds_bytes * EST_WAVES_PER_BLOCK, (hipStream_t)stream>>>(a);
     return check(hipGetLastError(), "est_sim_kernel");
 }
 
@@ -171,7 +175,7 @@ extern "C" int est_selftest_wave(uint32_t *host_out) {
 // given LDS size per wavefront (diagnostics).
 extern "C" int est_debug_occupancy(uint32_t lds_bytes_per_wave) {
     int blocks = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_kernel, 64 * EST_WAVES_PER_BLOCK,
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_kernel<false>, 64 * EST_WAVES_PER_BLOCK,
                                                      (size_t)lds_bytes_per_wave * EST_WAVES_PER_BLOCK) != hipSuccess)
         return -1;
     return blocks;
