@@ -244,10 +244,14 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     uint32_t *g_slots = c.slots + op.slot_off;
     uint64_t *lkey = c.lds;
     uint32_t *lpos = (uint32_t *)(c.lds + SCAN_INRING);
-    uint32_t *ltab = lpos + SCAN_INRING;   // 7 x 64 words: staging for re-sorting the replica table, per-group values
-    uint32_t *lslots = ltab + 448;
+    uint32_t *ltab = lpos + SCAN_INRING;   // 10 x 64 words: staging for re-sorting the replica table, per-group values
+    uint32_t *lstart = ltab + 448;         // 65: first lane of each group of a window (+ the end)
+    uint32_t *linv = ltab + 576;           // 64: linv[d-1] = ceil(65536 / d), so that floor(x / d) = x * linv[d-1] >> 16 for x <= 64
+    uint32_t *lslots = ltab + 640;
     const uint8_t *acc = c.a->acc + (uint64_t)op.acc_idx * c.a->acc_stride;
     const uint64_t below = lanes_below(ln);
+    linv[ln] = (65536u + ln) / (ln + 1u);
+    const uint32_t inv_b = (65536u + B - 1u) / B, inv_r = (65536u + R - 1u) / R;
 
     // replica table, sorted by the time the replica is free again
     const bool isrep = ln < R;
@@ -314,12 +318,15 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 A0 &= wv::ballot(f0); A1 &= wv::ballot(f1); A2 &= wv::ballot(f2);
                 a0 = a0 && f0; a1 = a1 && f1; a2 = a2 && f2;
             }
-            if (a0) { const uint32_t i = (ltail + popc64(A0 & below)) & (SCAN_INRING - 1); lkey[i] = k0; lpos[i] = rraw + ln; }
+            const uint32_t i0 = (ltail + wv::rank_below(A0)) & (SCAN_INRING - 1);
             ltail += popc64(A0);
-            if (a1) { const uint32_t i = (ltail + popc64(A1 & below)) & (SCAN_INRING - 1); lkey[i] = k1; lpos[i] = rraw + 64 + ln; }
+            const uint32_t i1 = (ltail + wv::rank_below(A1)) & (SCAN_INRING - 1);
             ltail += popc64(A1);
-            if (a2) { const uint32_t i = (ltail + popc64(A2 & below)) & (SCAN_INRING - 1); lkey[i] = k2; lpos[i] = rraw + 128 + ln; }
+            const uint32_t i2 = (ltail + wv::rank_below(A2)) & (SCAN_INRING - 1);
             ltail += popc64(A2);
+            if (a0) { lkey[i0] = k0; lpos[i0] = rraw + ln; }
+            if (a1) { lkey[i1] = k1; lpos[i1] = rraw + 64 + ln; }
+            if (a2) { lkey[i2] = k2; lpos[i2] = rraw + 128 + ln; }
             rraw += w0 + w1 + w2;
             EST_CHECK(ltail - lhead <= SCAN_INRING);
             wv::sync();
@@ -365,8 +372,6 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 const uint32_t tl = wv::bcast(rend, R - 1);
                 uint32_t nacc = 0;
                 if (tl < sat_add(f0, LB)) {
-                    const uint32_t inv_b = (65536u + B - 1u) / B;  // floor(x / B) = x * inv_b >> 16 for x <= 64
-                    const uint32_t inv_r = (65536u + R - 1u) / R;
                     const uint32_t kb = (ln * inv_b) >> 16;        // my batch
                     const uint32_t kd = (kb * inv_r) >> 16, km = kb - kd * R;
                     const uint64_t ft = (uint64_t)wv::shfl(rend, km) + (uint64_t)kd * LB;
@@ -519,16 +524,27 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 // a full batch; the queries of a run are in query-index order, so piece j holds its
                 // members j*B .. j*B+B-1, as the queue would hand them out)
                 const uint32_t rprev = wv::shr1(rdy);
-                const uint64_t upto = below | (1ull << ln);
                 const uint64_t WM = lanes_below(w);
                 const uint64_t runs = WM & (wv::ballot(rdy != rprev) | 1ull);
-                const uint32_t off = ln - (63u - (uint32_t)__builtin_clzll((runs & upto) | 1ull));
-                const uint32_t inv_b = (65536u + B - 1u) / B;                  // floor(x / B) = x * inv_b >> 16 for x < 64
-                const uint64_t heads = WM & wv::ballot(off == B * ((off * inv_b) >> 16));  // first query of each group
-                const uint32_t bid = popc64(heads & upto) - 1u;                // group index of this lane
-                const uint32_t start = 63u - (uint32_t)__builtin_clzll(heads & upto);
-                const uint64_t later = ln == 63 ? 0ull : (heads >> (ln + 1));
-                const uint32_t nh = later ? ln + 1 + ctz64(later) : w;         // where the next group starts
+                // first lane of every run through LDS (run r starts at lstart[r]; lstart[number of runs] = w)
+                const uint32_t nruns = popc64(runs);
+                const uint32_t rid = wv::rank_below(runs >> 1);  // my run (lane 0 always starts one)
+                if (ln < w && (ln == 0 || rdy != rprev)) lstart[rid] = ln;
+                if (ln == 0) lstart[nruns] = w;
+                wv::sync();
+                uint64_t heads = runs;
+                uint32_t bid = rid, start = lstart[rid], nh = lstart[rid + 1u];
+                const uint32_t rlen = ln < nruns ? lstart[ln + 1u] - lstart[ln] : 0u;
+                if (wv::ballot(rlen > B)) {
+                    // some run is longer than a batch: cut the runs into pieces of B
+                    const uint64_t upto = below | (1ull << ln);
+                    const uint32_t off = ln - start;
+                    heads = WM & wv::ballot(off == B * ((off * inv_b) >> 16));  // first query of each group
+                    bid = popc64(heads & upto) - 1u;                               // group index of this lane
+                    start = 63u - (uint32_t)__builtin_clzll(heads & upto);
+                    const uint64_t later = ln == 63 ? 0ull : (heads >> (ln + 1));
+                    nh = later ? ln + 1 + ctz64(later) : w;                        // where the next group starts
+                }
                 const uint32_t g = nh - start;
                 const bool final = staged <= 64 && rraw == in.wr && in.fin;
                 const uint32_t e = sat_add(rdy, wv::shfl(Lmine, g - 1));       // (L is 0 beyond B: rejected below)
@@ -594,7 +610,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                             const uint32_t pbefore = wv::shr1(pmax);
                             inv = safem & ~1ull & (wv::ballot(pbefore > e) | (wv::ballot(pbefore == e) & wv::ballot(bprev != bid)));
                         }
-                        uint32_t orank = popc64(safem & below);
+                        uint32_t orank = wv::rank_below(safem);
                         if (inv) {
                             key = sort_lanes64(key);
                             orank = ln;
@@ -622,7 +638,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                         space -= ns + extra;
                         EST_CHK_ORDER(inv ? 3 : 2);
                         // the run's batches that finish at or after tau wait in the slot of their replica
-                        const uint32_t inv_p = (65536u + p - 1u) / p;            // floor(x / p) = x * inv_p >> 16 for x < 64
+                        const uint32_t inv_p = linv[p - 1u];                      // floor(x / p) = x * inv_p >> 16 for x < 64
                         const uint32_t kmod = bid - p * ((bid * inv_p) >> 16);   // the replica (idle-table lane) of my group
                         const uint32_t myslot = wv::shfl(rslot, kmod);
                         const bool waits = ln < m && !safe;
@@ -812,7 +828,7 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             const bool fa = (acc[q] & 1u) != 0u;  // (idle lanes look at query 0)
             const uint64_t A = lanes_below(w) & wv::ballot(fa);
             const bool a = ln < w && fa;
-            const uint32_t pos = wr + popc64(A & below);
+            const uint32_t pos = wr + wv::rank_below(A);
             if (a) {
                 if (is_lat) {
                     const uint32_t l = (uint32_t)(key >> 32) - c.a->arrival[q];
@@ -843,7 +859,7 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 const bool a = ln < w && ((acc[(uint32_t)key] >> j) & 1u);
                 const uint64_t A = wv::ballot(a);
                 const uint32_t room = 64 - n;
-                const uint32_t myrank = popc64(A & below);
+                const uint32_t myrank = wv::rank_below(A);
                 if (a && myrank < room) {
                     skey[j * 64 + n + myrank] = key;
                     spos[j * 64 + n + myrank] = rc + ln;
@@ -945,7 +961,7 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 }
             }
             const uint64_t Em = wv::ballot(emitf);
-            const uint32_t pos = wr + popc64(Em & below);
+            const uint32_t pos = wr + wv::rank_below(Em);
             if (emitf) {
                 if (is_lat) {
                     const uint32_t l = (uint32_t)(key >> 32) - c.a->arrival[q];

@@ -59,6 +59,7 @@ __global__ __launch_bounds__(64) void est_wave_selftest_kernel(uint32_t *out) {
     uint32_t i = 6;
     for (uint32_t width = 2; width <= 64; width <<= 1, ++i)
         out[i * 64 + ln] = estdev::sort_lanes(ln < width ? scr : 0xFFFFFFFFu, width);
+    out[12 * 64 + ln] = wv::rank_below(0xF0F0A5A5C3C3FF01ull);
 }
 
 uint32_t blocks_for(uint64_t items, uint32_t per_block, uint32_t max_blocks) {
@@ -159,14 +160,14 @@ float event_ms(void *start, void *stop) {
 
 }  // namespace estbe
 
-// Runs the lane-layout check kernel and copies its 12 x 64 results to host memory.  Returns 0 on
+// Runs the lane-layout check kernel and copies its 13 x 64 results to host memory.  Returns 0 on
 // success.  Used by the GPU tests only.
 extern "C" int est_selftest_wave(uint32_t *host_out) {
     uint32_t *d = nullptr;
-    if (check(hipMalloc((void **)&d, 12 * 64 * 4), "hipMalloc")) return 1;
+    if (check(hipMalloc((void **)&d, 13 * 64 * 4), "hipMalloc")) return 1;
     est_wave_selftest_kernel<<<1, 64>>>(d);
     int rc = check(hipGetLastError(), "est_wave_selftest_kernel");
-    rc = rc || check(hipMemcpy(host_out, d, 12 * 64 * 4, hipMemcpyDeviceToHost), "hipMemcpy");
+    rc = rc || check(hipMemcpy(host_out, d, 13 * 64 * 4, hipMemcpyDeviceToHost), "hipMemcpy");
     (void)hipFree(d);
     return rc;
 }

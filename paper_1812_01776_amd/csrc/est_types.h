@@ -13,7 +13,7 @@
 #define EST_TRACE_BIT 32        // bit of the "arrival trace" pseudo-source in a source set
 #define EST_SRC_TRACE (-1)
 #define EST_LDS_MERGE_BYTES(k) ((k) * 1280u + 128u)   // LDS of one wavefront for a k-source merge
-#define EST_LDS_SCAN_BYTES(rb) (4864u + 4u * (rb))      // ... for a scan whose replica slots hold rb members
+#define EST_LDS_SCAN_BYTES(rb) (5632u + 4u * (rb))      // ... for a scan whose replica slots hold rb members
 
 enum { EST_OP_SCAN = 0, EST_OP_MERGE = 1, EST_OP_LAT = 2 };
 

@@ -36,6 +36,11 @@ EST_DEV uint32_t xor4(uint32_t v) {
     return (lane() & 4u) ? down : up;
 }
 
+// number of set bits of m below this lane's position (m must be the same in every lane)
+EST_DEV uint32_t rank_below(uint64_t m) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
 EST_DEV uint32_t uniform(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
 
 EST_DEV uint32_t min_u32(uint32_t v) {

@@ -59,6 +59,14 @@ EST_DEV uint32_t xor2(uint32_t v) { return (uint32_t)emu::exchange(v, 12)[emu::l
 EST_DEV uint32_t xor4(uint32_t v) { return (uint32_t)emu::exchange(v, 13)[emu::lane() ^ 4u]; }
 EST_DEV uint32_t xor8(uint32_t v) { return (uint32_t)emu::exchange(v, 14)[emu::lane() ^ 8u]; }
 
+// (every lane must pass the same mask: checked like any other wave-uniform argument)
+EST_DEV uint32_t rank_below(uint64_t m) {
+    const uint64_t *x = emu::exchange(m, 15);
+    EST_CHECK(x[0] == m);
+    const uint32_t l = emu::lane();
+    return (uint32_t)__builtin_popcountll(m & (l >= 64 ? ~0ull : ((1ull << l) - 1ull)));
+}
+
 EST_DEV uint32_t uniform(uint32_t v) { return (uint32_t)emu::exchange(v, 4)[0]; }
 
 EST_DEV uint32_t min_u32(uint32_t v) {

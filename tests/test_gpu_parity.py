@@ -37,7 +37,7 @@ def test_wave_primitive_lane_layout():
     network built from them, checked lane by lane on the device (in-bounds, one wavefront)."""
     import ctypes
     lib = binding.load_library()
-    out = np.zeros((12, 64), np.uint32)
+    out = np.zeros((13, 64), np.uint32)
     assert lib.est_selftest_wave(ctypes.c_void_p(out.ctypes.data)) == 0
     ln = np.arange(64)
     v = 7 * ln + 3
@@ -48,6 +48,8 @@ def test_wave_primitive_lane_layout():
     scr = (ln * 37 + 11) & 63
     for i, width in enumerate((2, 4, 8, 16, 32, 64)):
         assert out[6 + i][:width].tolist() == sorted(scr[:width].tolist()), width
+    m = 0xF0F0A5A5C3C3FF01
+    assert out[12].tolist() == [bin(m & ((1 << i) - 1)).count("1") for i in range(64)]
 
 
 def _hand_examples():
