@@ -298,7 +298,8 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     uint32_t fp_skip = 0;   // general batches still to do before the light-load shortcut is tried again
     uint32_t sat_skip = 0;  // the same for the backlog shortcut
     uint32_t single_skip = 0;  // and for the one-query-per-batch shortcut
-    uint32_t d_gen = 0, d_gene = 0, d_fp = 0, d_fpe = 0, d_b1 = 0, d_b1e = 0, d_sat = 0, d_sate = 0, d_hz = 0;  // diagnostics
+    uint32_t blk_skip = 0;     // and for the block of batches
+    uint32_t d_gen = 0, d_gene = 0, d_fp = 0, d_fpe = 0, d_b1 = 0, d_b1e = 0, d_sat = 0, d_sate = 0, d_hz = 0, d_blk = 0, d_blke = 0;  // diagnostics
 
     for (;;) {
         uint32_t staged = ltail - lhead;
@@ -698,6 +699,125 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         }
         if (fp_skip) --fp_skip;
         if (sat_skip) --sat_skip;
+        if (B >= 2 && mono && L1 > 0 && blk_skip == 0 && w >= 4) {
+            // A block of batches: the batch-by-batch recurrence (start = max(earliest free replica,
+            // first ready time), members = those ready by then, up to B) needs only scalars and one
+            // vector compare per batch, so it is run ahead for as many batches as the window decides,
+            // on a copy of the table; emission, slots and the new table are then done once for the
+            // whole block, with the same rule as the light-load step: whatever finishes before
+            // tau = (earliest possible next start) + L(1) is written out now in (completion, query)
+            // order, older waiting batches that finish before tau are woven in, the rest waits.  A
+            // batch replaced on its replica inside the block finished by that later start, hence before tau.
+            const uint64_t WM = lanes_below(w);
+            const bool final = staged <= 64 && rraw == in.wr && in.fin;
+            const uint32_t rend_next = wv::shl1(rend), rcnt_next = wv::shl1(rcnt);
+            const uint64_t busyp = wv::ballot(rcnt > 0);
+            const uint64_t tiep = lanes_below(R - 1u) & wv::ballot(rend == rend_next) & (busyp | wv::ballot(rcnt_next > 0));
+            const uint32_t ecap = tiep ? wv::bcast(rend, ctz64(tiep)) : 0xFFFFFFFFu;  // two older batches tie there: settled elsewhere
+            uint32_t trend = rend, tslot = rslot, tcnt = rcnt, tk = 0xFFu;  // working table; tk = batch of this block on the entry
+            uint32_t vE = 0, vS = 0, vA = 0, vB = 0;                          // per batch (lane k): end, slot, first lane, size
+            uint64_t heads = 0;
+            uint32_t a = 0, K = 0;
+            while (a < w) {
+                const uint32_t f = wv::uniform(trend);
+                const uint32_t T = umax(f, wv::bcast(rdy, a));
+                const uint32_t ready = popc64(WM & wv::ballot(rdy <= T));
+                const uint32_t b = umin(B, ready - a);
+                if (!(b == B || ready < w || final)) break;  // more members may still arrive
+                const uint32_t e = sat_add(T, wv::bcast(Lmine, b - 1u));
+                if (e >= ecap) break;                       // (ecap <= 2^32-1: a clamped time never passes)
+                if (wv::ballot(tcnt > 0) & wv::ballot(trend == e)) break;  // would tie with an older waiting batch
+                const uint32_t slot0 = wv::uniform(tslot);
+                const bool mine = ln == K;
+                vE = mine ? e : vE; vS = mine ? slot0 : vS; vA = mine ? a : vA; vB = mine ? b : vB;
+                // the earliest entry leaves the table, the new one goes in behind everything that ends no later
+                const uint32_t p = popc64(REP & ~1ull & wv::ballot(trend <= e));
+                const uint32_t ne = wv::shl1(trend), ns = wv::shl1(tslot), nc = wv::shl1(tcnt), nk = wv::shl1(tk);
+                if (ln < p) {
+                    trend = ne; tslot = ns; tcnt = nc; tk = nk;
+                } else if (ln == p) {
+                    trend = e; tslot = slot0; tcnt = 0; tk = K;
+                }
+                heads |= 1ull << a;
+                a += b;
+                ++K;
+            }
+            bool done = false;
+            if (K >= 2) {
+                const uint32_t f_next = wv::uniform(trend);
+                const bool tau_inf = final && a >= w;
+                const uint32_t r_next = wv::bcast(rdy, a < w ? a : w - 1u);  // what follows is ready no earlier
+                const uint32_t tau = tau_inf ? 0xFFFFFFFFu : sat_add(umax(f_next, r_next), L1);
+                const uint32_t kb = wv::rank_below(heads >> 1);             // my batch (lane 0 starts batch 0)
+                const uint32_t e = wv::shfl(vE, kb), st = wv::shfl(vA, kb), myslot = wv::shfl(vS, kb);
+                const uint64_t AM = lanes_below(a);
+                const uint64_t safem = AM & (tau_inf ? ~0ull : wv::ballot(e < tau));
+                const bool safe = ln < a && (tau_inf || e < tau);
+                const uint32_t nsafe = popc64(safem);
+                uint32_t extra = 0;
+                uint64_t woven = 0;
+                for (uint64_t pm = busyp; pm; pm &= pm - 1) {
+                    const uint32_t j = ctz64(pm);
+                    const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j);
+                    if ((!tau_inf && ej >= tau) || ej >= ecap) break;  // sorted: the rest finish later (or tie) and keep waiting
+                    woven |= 1ull << j;
+                    extra += cj;
+                }
+                if (nsafe + extra <= space) {
+                    const uint32_t eprev = wv::shr1(e), qprev = wv::shr1(q), kprev = wv::shr1(kb);
+                    uint64_t key = safe ? (((uint64_t)e << 32) | q) : ~0ull;
+                    // in output order already?  (only checked when the safe queries are the leading ones)
+                    const bool ordered = safem == lanes_below(nsafe) &&
+                                         (safem & ~1ull & (wv::ballot(eprev > e) | (wv::ballot(eprev == e) & wv::ballot(qprev > q)))) == 0;
+                    if (!ordered) key = sort_lanes64(key);
+                    const bool emit_me = ln < nsafe;
+                    const uint32_t ke = (uint32_t)(key >> 32);
+                    uint32_t shift = 0;
+                    for (uint64_t pm = woven; pm; pm &= pm - 1) {
+                        const uint32_t j = ctz64(pm);
+                        const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j);
+                        if (ej < ke) shift += cj;
+                    }
+                    if (emit_me) out[(wr + ln + shift) & omask] = key;
+                    uint32_t before = 0;
+                    for (uint64_t pm = woven; pm; pm &= pm - 1) {
+                        const uint32_t j = ctz64(pm);
+                        const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j), sj = wv::bcast(rslot, j);
+                        const uint32_t pos = wr + before + popc64(lanes_below(nsafe) & wv::ballot(ke < ej));
+                        if (ln < cj) out[(pos + ln) & omask] = ((uint64_t)ej << 32) | lslots[sj * bm + ln];
+                        before += cj;
+                    }
+                    wr += nsafe + extra;
+                    space -= nsafe + extra;
+                    EST_CHK_ORDER(7);
+                    wv::sync();  // the slots of woven batches have been read: they may be written again
+                    // members of batches that wait go to their replica's slot, sorted by query index
+                    const uint64_t waitm = AM & ~safem;
+                    uint32_t qs = q;
+                    if (waitm & ~1ull & wv::ballot(kprev == kb) & wv::ballot(qprev > q))
+                        qs = (uint32_t)sort_lanes64(ln < a ? (((uint64_t)kb << 32) | q) : ~0ull);
+                    if (ln < a && !safe) lslots[myslot * bm + (ln - st)] = qs;
+                    // the working table becomes the table: older entries written out lose their members,
+                    // entries of this block keep theirs if they wait
+                    const uint32_t bsz = wv::shfl(vB, tk);
+                    const bool late = !tau_inf && trend >= tau;
+                    if (isrep) {
+                        rend = trend;
+                        rslot = tslot;
+                        rcnt = tk == 0xFFu ? ((late || trend >= ecap) ? tcnt : 0u) : (late ? bsz : 0u);
+                    }
+                    wv::sync();
+                    lhead += a;
+                    ++d_blk; d_blke += a;
+                    progress = true;
+                    done = true;
+                }
+            }
+            if (done) continue;
+            blk_skip = 4;
+        } else if (blk_skip) {
+            --blk_skip;
+        }
         ++d_gen;
         const uint32_t f = wv::uniform(rend);  // earliest free replica = lane 0
         const uint32_t r0 = wv::uniform(rdy);
@@ -744,11 +864,12 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         wv::atomic_add_u64(dc + 0, d_gen); wv::atomic_add_u64(dc + 1, d_fp); wv::atomic_add_u64(dc + 2, d_fpe);
         wv::atomic_add_u64(dc + 3, d_b1); wv::atomic_add_u64(dc + 4, d_b1e); wv::atomic_add_u64(dc + 7, 1);
         wv::atomic_add_u64(dc + 8 + s, d_gen); wv::atomic_add_u64(dc + 8 + EST_MAX_STAGES + s, d_gene);
-        wv::atomic_add_u64(dc + 8 + 2 * EST_MAX_STAGES + s, d_fpe + d_b1e + d_sate + d_hz);
+        wv::atomic_add_u64(dc + 8 + 2 * EST_MAX_STAGES + s, d_fpe + d_b1e + d_sate + d_hz + d_blke);
         wv::atomic_add_u64(dc + 8 + 4 * EST_MAX_STAGES + 3, d_sat); wv::atomic_add_u64(dc + 8 + 4 * EST_MAX_STAGES + 4, d_sate);
         wv::atomic_add_u64(dc + 8 + 4 * EST_MAX_STAGES + 5, d_hz);
+        wv::atomic_add_u64(dc + 8 + 4 * EST_MAX_STAGES + 6, d_blk); wv::atomic_add_u64(dc + 8 + 4 * EST_MAX_STAGES + 7, d_blke);
         uint64_t *pc = c.a->dbg_ticks + c.a->n_cfg + ((uint64_t)c.t * EST_MAX_STAGES + s) * 4;  // per candidate and stage
-        pc[0] += d_gen; pc[1] += d_gene; pc[2] += d_fp + d_b1 + d_sat; pc[3] += d_fpe + d_b1e + d_sate + d_hz;
+        pc[0] += d_gen; pc[1] += d_gene; pc[2] += d_fp + d_b1 + d_sat + d_blk; pc[3] += d_fpe + d_b1e + d_sate + d_hz + d_blke;
     }
     // back to memory: the table, the members still waiting, the cursors
     if (isrep) {
