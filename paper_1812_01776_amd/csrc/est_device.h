@@ -575,9 +575,25 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 if (m > 0) {
                     // the next batch starts no earlier than the next query's ready time; if the run took
                     // the whole window, that is at least the window's last ready time
-                    const bool tau_inf = m >= w && final;                // nothing follows at all
-                    const uint32_t tau = tau_inf ? 0xFFFFFFFFu : sat_add(wv::bcast(rdy, umin(m, w - 1u)), L1);
-                    const uint64_t safem = lanes_below(m) & (tau_inf ? ~0ull : wv::ballot(e < tau));
+                    bool tau_inf = m >= w && final;                      // nothing follows at all
+                    uint32_t tau = tau_inf ? 0xFFFFFFFFu : sat_add(wv::bcast(rdy, umin(m, w - 1u)), L1);
+                    uint64_t safem = lanes_below(m) & (tau_inf ? ~0ull : wv::ballot(e < tau));
+                    if (safem != lanes_below(m)) {
+                        // Some batch of the run would have to wait.  Waiting batches cost slot traffic and
+                        // weaving in the steps that follow; if the run up to the first of them is long and
+                        // nothing in it has to wait once the run ends there, stop the run there: the rest is
+                        // looked at again with more of the input in view.
+                        const uint32_t m2 = ctz64(~safem);               // (the first query of its group)
+                        if (m2 >= 16) {
+                            const uint32_t tau2 = sat_add(wv::bcast(rdy, m2), L1);
+                            if ((lanes_below(m2) & ~wv::ballot(e < tau2)) == 0) {
+                                m = m2;
+                                tau = tau2;
+                                tau_inf = false;
+                                safem = lanes_below(m2);
+                            }
+                        }
+                    }
                     const bool safe = ln < m && (tau_inf || e < tau);
                     const uint32_t ns = popc64(safem);
                     // older waiting batches that finish before tau go out with the run
@@ -714,7 +730,8 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             const uint64_t busyp = wv::ballot(rcnt > 0);
             const uint64_t tiep = lanes_below(R - 1u) & wv::ballot(rend == rend_next) & (busyp | wv::ballot(rcnt_next > 0));
             const uint32_t ecap = tiep ? wv::bcast(rend, ctz64(tiep)) : 0xFFFFFFFFu;  // two older batches tie there: settled elsewhere
-            uint32_t trend = rend, tslot = rslot, tcnt = rcnt, tk = 0xFFu;  // working table; tk = batch of this block on the entry
+            // working table: free time, and packed (members waiting << 16 | batch of this block on the entry, 0xFF = none, << 8 | slot)
+            uint32_t trend = rend, tinfo = (rcnt << 16) | 0xFF00u | rslot;
             uint32_t vE = 0, vS = 0, vA = 0, vB = 0;                          // per batch (lane k): end, slot, first lane, size
             uint64_t heads = 0;
             uint32_t a = 0, K = 0;
@@ -726,17 +743,17 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 if (!(b == B || ready < w || final)) break;  // more members may still arrive
                 const uint32_t e = sat_add(T, wv::bcast(Lmine, b - 1u));
                 if (e >= ecap) break;                       // (ecap <= 2^32-1: a clamped time never passes)
-                if (wv::ballot(tcnt > 0) & wv::ballot(trend == e)) break;  // would tie with an older waiting batch
-                const uint32_t slot0 = wv::uniform(tslot);
+                if (wv::ballot(tinfo >= 0x10000u) & wv::ballot(trend == e)) break;  // would tie with an older waiting batch
+                const uint32_t slot0 = wv::uniform(tinfo) & 0xFFu;
                 const bool mine = ln == K;
                 vE = mine ? e : vE; vS = mine ? slot0 : vS; vA = mine ? a : vA; vB = mine ? b : vB;
                 // the earliest entry leaves the table, the new one goes in behind everything that ends no later
                 const uint32_t p = popc64(REP & ~1ull & wv::ballot(trend <= e));
-                const uint32_t ne = wv::shl1(trend), ns = wv::shl1(tslot), nc = wv::shl1(tcnt), nk = wv::shl1(tk);
+                const uint32_t ne = wv::shl1(trend), ni = wv::shl1(tinfo);
                 if (ln < p) {
-                    trend = ne; tslot = ns; tcnt = nc; tk = nk;
+                    trend = ne; tinfo = ni;
                 } else if (ln == p) {
-                    trend = e; tslot = slot0; tcnt = 0; tk = K;
+                    trend = e; tinfo = (K << 8) | slot0;
                 }
                 heads |= 1ull << a;
                 a += b;
@@ -799,12 +816,13 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                     if (ln < a && !safe) lslots[myslot * bm + (ln - st)] = qs;
                     // the working table becomes the table: older entries written out lose their members,
                     // entries of this block keep theirs if they wait
+                    const uint32_t tk = (tinfo >> 8) & 0xFFu;
                     const uint32_t bsz = wv::shfl(vB, tk);
                     const bool late = !tau_inf && trend >= tau;
                     if (isrep) {
                         rend = trend;
-                        rslot = tslot;
-                        rcnt = tk == 0xFFu ? ((late || trend >= ecap) ? tcnt : 0u) : (late ? bsz : 0u);
+                        rslot = tinfo & 0xFFu;
+                        rcnt = tk == 0xFFu ? ((late || trend >= ecap) ? tinfo >> 16 : 0u) : (late ? bsz : 0u);
                     }
                     wv::sync();
                     lhead += a;
@@ -869,7 +887,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         wv::atomic_add_u64(dc + 8 + 4 * EST_MAX_STAGES + 5, d_hz);
         wv::atomic_add_u64(dc + 8 + 4 * EST_MAX_STAGES + 6, d_blk); wv::atomic_add_u64(dc + 8 + 4 * EST_MAX_STAGES + 7, d_blke);
         uint64_t *pc = c.a->dbg_ticks + c.a->n_cfg + ((uint64_t)c.t * EST_MAX_STAGES + s) * 4;  // per candidate and stage
-        pc[0] += d_gen; pc[1] += d_gene; pc[2] += d_fp + d_b1 + d_sat + d_blk; pc[3] += d_fpe + d_b1e + d_sate + d_hz + d_blke;
+        pc[0] += d_gen; pc[2] += d_fp + d_b1 + d_sat + d_blk; pc[3] += d_fpe + d_b1e + d_sate + d_hz + d_blke;
     }
     // back to memory: the table, the members still waiting, the cursors
     if (isrep) {
@@ -1164,7 +1182,9 @@ EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *
             if (DIAG && a.dbg_ticks && ln == 0) {
                 const uint32_t at = op.type == EST_OP_SCAN ? 8 + 3 * EST_MAX_STAGES + op.stage
                                                            : 8 + 4 * EST_MAX_STAGES + (op.type == EST_OP_LAT ? 1 : 0);
-                wv::atomic_add_u64(a.status->dbg_cnt + at, wv::ticks() - k0);
+                const uint64_t dt = wv::ticks() - k0;
+                wv::atomic_add_u64(a.status->dbg_cnt + at, dt);
+                if (op.type == EST_OP_SCAN) a.dbg_ticks[a.n_cfg + ((uint64_t)t * EST_MAX_STAGES + op.stage) * 4 + 1] += dt;  // per candidate and stage
             }
             progress = progress || p;
             alldone = alldone && c.st[P.done_off + opi] != 0;
