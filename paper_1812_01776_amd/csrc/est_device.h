@@ -936,6 +936,9 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
 
     // small per-source tables (the same values in every lane) kept in LDS rather than in private memory
     uint32_t *raw = spos + P.max_src * 64, *nst = raw + EST_KMAX, *cur = nst + EST_KMAX, *m_src = cur + EST_KMAX;
+    uint32_t *dupc = m_src + EST_KMAX;  // EST_DUP_BUCKETS counters: queries of a window per hash bucket (zero between windows)
+    if (op.has_cnt)
+        for (uint32_t i = ln; i < EST_DUP_BUCKETS; i += 64) dupc[i] = 0;
     for (uint32_t j = 0; j < K; ++j) raw[j] = c.st[P.rd_off + op.src_edge[j]];
     uint64_t *out = nullptr;
     uint32_t omask = 0, wr, space = 0xFFFFFFFFu;
@@ -1040,6 +1043,8 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         }
         // ---- rank every staged element up to the bound among all staged elements
         uint32_t m_total = 0;
+        bool clamped = false;  // some staged key sits at the horizon (a source's keys ascend: look at its last)
+        for (uint32_t j = 0; j < K; ++j) clamped = clamped || (nst[j] > 0 && (uint32_t)(skey[j * 64 + nst[j] - 1u] >> 32) == 0xFFFFFFFFu);
         for (uint32_t j = 0; j < K; ++j) {
             const bool have = ln < nst[j];
             const uint64_t rk = have ? skey[j * 64 + ln] : 0ull;
@@ -1051,11 +1056,20 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 for (uint32_t j2 = 0; j2 < K; ++j2) {
                     if (j2 == j) continue;
                     uint32_t lo = 0, hi = nst[j2];
-                    while (lo < hi) {
-                        uint32_t mid = (lo + hi) >> 1;
-                        uint64_t y = eff_key(skey[j2 * 64 + mid], j2, mid);
-                        bool less = y < x || (y == x && j2 < j);
-                        if (less) lo = mid + 1; else hi = mid;
+                    if (!clamped) {
+                        // (keys of different sources never coincide: a query appears once per source, and
+                        // equal keys mean the same query)  -- ties are still broken by source for safety
+                        while (lo < hi) {
+                            const uint32_t mid = (lo + hi) >> 1;
+                            const uint64_t y = skey[j2 * 64 + mid];
+                            if (y < rk || (y == rk && j2 < j)) lo = mid + 1; else hi = mid;
+                        }
+                    } else {
+                        while (lo < hi) {
+                            const uint32_t mid = (lo + hi) >> 1;
+                            const uint64_t y = eff_key(skey[j2 * 64 + mid], j2, mid);
+                            if (y < x || (y == x && j2 < j)) lo = mid + 1; else hi = mid;
+                        }
                     }
                     rank += lo;
                 }
@@ -1080,7 +1094,15 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 if (MM) {
                     const uint32_t c0 = multi ? cnt[q] : 0u;
                     uint32_t duprank = 0, duptotal = 1;
-                    for (uint64_t todo = MM; todo;) {
+                    // Only a query that appears twice in this window needs its appearances counted
+                    // together.  Candidates: lanes that share a hash bucket with another lane.
+                    const uint32_t hb = q & (EST_DUP_BUCKETS - 1u);
+                    if (multi) wv::lds_add(&dupc[hb], 1u);
+                    wv::sync();
+                    const uint32_t shared = multi ? dupc[hb] : 0u;
+                    wv::sync();
+                    if (multi) dupc[hb] = 0;
+                    for (uint64_t todo = wv::ballot(shared > 1u); todo;) {
                         const uint32_t l = ctz64(todo);
                         const uint32_t sq = wv::bcast(q, l);
                         const uint64_t same = MM & wv::ballot(q == sq);

@@ -12,7 +12,8 @@
 #define EST_MAX_CONS 36         // consumers of one ring
 #define EST_TRACE_BIT 32        // bit of the "arrival trace" pseudo-source in a source set
 #define EST_SRC_TRACE (-1)
-#define EST_LDS_MERGE_BYTES(k) ((k) * 1280u + 128u)   // LDS of one wavefront for a k-source merge
+#define EST_DUP_BUCKETS 128u                       // hash buckets for spotting one query twice in a window of a join
+#define EST_LDS_MERGE_BYTES(k) ((k) * 1280u + 128u + 4u * EST_DUP_BUCKETS)   // LDS of one wavefront for a k-source merge
 #define EST_LDS_SCAN_BYTES(rb) (5632u + 4u * (rb))      // ... for a scan whose replica slots hold rb members
 
 enum { EST_OP_SCAN = 0, EST_OP_MERGE = 1, EST_OP_LAT = 2 };
