@@ -91,62 +91,97 @@ EST_DEV uint32_t ring_space(const Ctx &c, int32_t ring, uint32_t wr) {
     return R.cap_mask + 1u - used;
 }
 
+// Lanes that keep the smaller value in the compare-exchange step (k, j) of a bitonic network:
+// those whose bit j and bit k are both clear or both set.
+constexpr uint64_t keep_min_mask(uint32_t k, uint32_t j) {
+    uint64_t m = 0;
+    for (uint32_t l = 0; l < 64; ++l)
+        if (((l & j) == 0) == ((l & k) == 0)) m |= 1ull << l;
+    return m;
+}
+
 // Ascending bitonic sort of the values of lanes 0 .. width-1 (width a power of two, the same in
 // every lane; lanes beyond it take part but their result is not used).
-EST_DEV uint32_t cmpx(uint32_t v, uint32_t o, uint32_t ln, uint32_t k, uint32_t j) {
-    const bool up = (ln & k) == 0, lower = (ln & j) == 0;
-    const uint32_t mn = umin(v, o), mx = umax(v, o);
-    return (lower == up) ? mn : mx;
+template <uint32_t K, uint32_t J>
+EST_DEV uint32_t cmpx(uint32_t v, uint32_t o) {
+    constexpr uint64_t M = keep_min_mask(K, J);
+    return wv::lane_in(M) ? umin(v, o) : umax(v, o);
 }
 EST_DEV uint32_t sort_lanes(uint32_t v, uint32_t width) {
     const uint32_t ln = wv::lane();
-    v = cmpx(v, wv::xor1(v), ln, 2, 1);
+    v = cmpx<2, 1>(v, wv::xor1(v));
     if (width <= 2) return v;
-    v = cmpx(v, wv::xor2(v), ln, 4, 2);
-    v = cmpx(v, wv::xor1(v), ln, 4, 1);
+    v = cmpx<4, 2>(v, wv::xor2(v));
+    v = cmpx<4, 1>(v, wv::xor1(v));
     if (width <= 4) return v;
-    v = cmpx(v, wv::xor4(v), ln, 8, 4);
-    v = cmpx(v, wv::xor2(v), ln, 8, 2);
-    v = cmpx(v, wv::xor1(v), ln, 8, 1);
+    v = cmpx<8, 4>(v, wv::xor4(v));
+    v = cmpx<8, 2>(v, wv::xor2(v));
+    v = cmpx<8, 1>(v, wv::xor1(v));
     if (width <= 8) return v;
-    v = cmpx(v, wv::xor8(v), ln, 16, 8);
-    v = cmpx(v, wv::xor4(v), ln, 16, 4);
-    v = cmpx(v, wv::xor2(v), ln, 16, 2);
-    v = cmpx(v, wv::xor1(v), ln, 16, 1);
+    v = cmpx<16, 8>(v, wv::xor8(v));
+    v = cmpx<16, 4>(v, wv::xor4(v));
+    v = cmpx<16, 2>(v, wv::xor2(v));
+    v = cmpx<16, 1>(v, wv::xor1(v));
     if (width <= 16) return v;
-    v = cmpx(v, wv::shfl(v, ln ^ 16), ln, 32, 16);
-    v = cmpx(v, wv::xor8(v), ln, 32, 8);
-    v = cmpx(v, wv::xor4(v), ln, 32, 4);
-    v = cmpx(v, wv::xor2(v), ln, 32, 2);
-    v = cmpx(v, wv::xor1(v), ln, 32, 1);
+    v = cmpx<32, 16>(v, wv::shfl(v, ln ^ 16));
+    v = cmpx<32, 8>(v, wv::xor8(v));
+    v = cmpx<32, 4>(v, wv::xor4(v));
+    v = cmpx<32, 2>(v, wv::xor2(v));
+    v = cmpx<32, 1>(v, wv::xor1(v));
     if (width <= 32) return v;
-    v = cmpx(v, wv::shfl(v, ln ^ 32), ln, 64, 32);
-    v = cmpx(v, wv::shfl(v, ln ^ 16), ln, 64, 16);
-    v = cmpx(v, wv::xor8(v), ln, 64, 8);
-    v = cmpx(v, wv::xor4(v), ln, 64, 4);
-    v = cmpx(v, wv::xor2(v), ln, 64, 2);
-    v = cmpx(v, wv::xor1(v), ln, 64, 1);
+    v = cmpx<64, 32>(v, wv::shfl(v, ln ^ 32));
+    v = cmpx<64, 16>(v, wv::shfl(v, ln ^ 16));
+    v = cmpx<64, 8>(v, wv::xor8(v));
+    v = cmpx<64, 4>(v, wv::xor4(v));
+    v = cmpx<64, 2>(v, wv::xor2(v));
+    v = cmpx<64, 1>(v, wv::xor1(v));
     return v;
 }
 
 // Ascending bitonic sort of one 64-bit key per lane over all 64 lanes.
-EST_DEV uint64_t cmpx64(uint64_t v, uint32_t ohi, uint32_t olo, uint32_t ln, uint32_t k, uint32_t j) {
+template <uint32_t K, uint32_t J>
+EST_DEV uint64_t cmpx64(uint64_t v, uint32_t ohi, uint32_t olo) {
+    constexpr uint64_t M = keep_min_mask(K, J);
     const uint64_t o = ((uint64_t)ohi << 32) | olo;
-    const bool up = (ln & k) == 0, lower = (ln & j) == 0;
-    const bool take_min = lower == up;
-    return ((o < v) == take_min) ? o : v;
+    return ((o < v) == wv::lane_in(M)) ? o : v;
+}
+template <uint32_t K>
+EST_DEV uint64_t sort_merge64(uint64_t v) {  // the compare-exchange steps (K, K/2), ..., (K, 1)
+    const uint32_t ln = wv::lane();
+    if (K >= 64) v = cmpx64<K, 32>(v, wv::shfl((uint32_t)(v >> 32), ln ^ 32), wv::shfl((uint32_t)v, ln ^ 32));
+    if (K >= 32) v = cmpx64<K, 16>(v, wv::shfl((uint32_t)(v >> 32), ln ^ 16), wv::shfl((uint32_t)v, ln ^ 16));
+    if (K >= 16) v = cmpx64<K, 8>(v, wv::xor8((uint32_t)(v >> 32)), wv::xor8((uint32_t)v));
+    if (K >= 8) v = cmpx64<K, 4>(v, wv::xor4((uint32_t)(v >> 32)), wv::xor4((uint32_t)v));
+    if (K >= 4) v = cmpx64<K, 2>(v, wv::xor2((uint32_t)(v >> 32)), wv::xor2((uint32_t)v));
+    return cmpx64<K, 1>(v, wv::xor1((uint32_t)(v >> 32)), wv::xor1((uint32_t)v));
 }
 EST_DEV uint64_t sort_lanes64(uint64_t v) {
+    v = sort_merge64<2>(v);
+    v = sort_merge64<4>(v);
+    v = sort_merge64<8>(v);
+    v = sort_merge64<16>(v);
+    v = sort_merge64<32>(v);
+    return sort_merge64<64>(v);
+}
+
+// Keys (e << 32 | q) of the lanes in VM, ascending, in lanes 0 .. popcount(VM)-1 (2^64-1 elsewhere).
+// Every e is at least base.  While the times span less than 2^26 the sort runs on 32-bit
+// (time - base, lane) pairs; equal times keep their lane order, and if that is not the order of the
+// query indices the full 64-bit sort is used after all.
+EST_DEV uint64_t sort_time_query(uint32_t e, uint32_t q, uint64_t VM, uint32_t base) {
     const uint32_t ln = wv::lane();
-    for (uint32_t k = 2; k <= 64; k <<= 1) {
-        for (uint32_t j = k >> 1; j >= 16; j >>= 1)
-            v = cmpx64(v, wv::shfl((uint32_t)(v >> 32), ln ^ j), wv::shfl((uint32_t)v, ln ^ j), ln, k, j);
-        if (k >= 16) v = cmpx64(v, wv::xor8((uint32_t)(v >> 32)), wv::xor8((uint32_t)v), ln, k, 8);
-        if (k >= 8) v = cmpx64(v, wv::xor4((uint32_t)(v >> 32)), wv::xor4((uint32_t)v), ln, k, 4);
-        if (k >= 4) v = cmpx64(v, wv::xor2((uint32_t)(v >> 32)), wv::xor2((uint32_t)v), ln, k, 2);
-        v = cmpx64(v, wv::xor1((uint32_t)(v >> 32)), wv::xor1((uint32_t)v), ln, k, 1);
+    const bool valid = wv::lane_in(VM);
+    const uint32_t d = e - base;
+    if ((VM & wv::ballot(d >= (1u << 26))) == 0) {
+        const uint32_t k = sort_lanes(valid ? ((d << 6) | ln) : 0xFFFFFFFFu, 64);
+        const uint32_t qs = wv::shfl(q, k & 63u);
+        const uint32_t ds = k >> 6;
+        const uint32_t dp = wv::shr1(ds), qp = wv::shr1(qs);
+        const uint32_t n = popc64(VM);
+        if ((lanes_below(n) & ~1ull & wv::ballot(dp == ds) & wv::ballot(qp > qs)) == 0)
+            return ln < n ? (((uint64_t)(base + ds) << 32) | qs) : ~0ull;
     }
-    return v;
+    return sort_lanes64(valid ? (((uint64_t)e << 32) | q) : ~0ull);
 }
 
 // ------------------------------------------------------------------------------------------ SCAN
@@ -629,7 +664,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                         }
                         uint32_t orank = wv::rank_below(safem);
                         if (inv) {
-                            key = sort_lanes64(key);
+                            key = sort_time_query(e, q, safem, r0);
                             orank = ln;
                         }
                         const bool emit_me = inv ? ln < ns : safe;
@@ -672,37 +707,26 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                             cend = lend[klast];
                             ccnt = luns[klast] ? lg[klast] : 0u;
                         }
-                        uint32_t trank = 0;
-                        if (!inv && !(lanes_below(m) & ~safem) && p == pidle) {
-                            // common case: nothing waits and the new completion times ascend with the group
-                            // index, so lanes [0,p) hold, in order, the unused idle entries (still <= r0,
-                            // lanes nb..p-1) and then the served ones in ascending time; only the busy
-                            // entries have to be slotted in
-                            const uint32_t nn = umin(nb, p), na = p - nn;
-                            // served lane j holds group klast(j); in time order these are lanes
-                            // (nb mod p), (nb mod p)+1, ..., wrapping: position = (j - nb) mod p
-                            const uint32_t nbm = nb - p * ((nb * inv_p) >> 16);
-                            const bool is_n = ln < nn, is_a = ln >= nn && ln < p;
-                            uint32_t rank_n = na + (nb >= p ? (ln >= nbm ? ln - nbm : ln + p - nbm) : ln);
-                            uint32_t rank_b = na + nn + (ln - p);
-                            for (uint64_t bm2 = REP & ~lanes_below(p); bm2; bm2 &= bm2 - 1) {
-                                const uint32_t j = ctz64(bm2);
-                                const uint32_t ej = wv::bcast(cend, j);
-                                const uint32_t more_new = popc64(lanes_below(nn) & wv::ballot(cend > ej));  // new entries after this busy one
-                                if (ln == j) rank_b -= more_new;
-                                if (is_n && cend > ej) rank_n += 1;
-                            }
-                            trank = is_a ? ln - nn : is_n ? rank_n : rank_b;
+                        // back in order of time: sort (time since r0, lane) pairs -- entries idle at r0 count
+                        // as 0 and keep their order -- and fetch each entry from the lane it was in
+                        const uint32_t dl = cend > r0 ? cend - r0 : 0u;
+                        if ((REP & wv::ballot(dl >= (1u << 26))) == 0) {
+                            uint32_t width = 2;
+                            while (width < R) width <<= 1;
+                            const uint32_t from = sort_lanes(isrep ? ((dl << 6) | ln) : 0xFFFFFFFFu, width) & 63u;
+                            const uint32_t se = wv::shfl(cend, from), sc = wv::shfl(ccnt, from), ss = wv::shfl(cslot, from);
+                            if (isrep) { rend = se; rcnt = sc; rslot = ss; }
                         } else {
+                            uint32_t trank = 0;
                             for (uint32_t j = 0; j < R; ++j) {
                                 const uint32_t ej = wv::bcast(cend, j);
                                 if (ej < cend || (ej == cend && j < ln)) ++trank;
                             }
+                            if (isrep) { ltab[trank] = cend; ltab[64 + trank] = ccnt; ltab[128 + trank] = cslot; }
+                            wv::sync();
+                            if (isrep) { rend = ltab[ln]; rcnt = ltab[64 + ln]; rslot = ltab[128 + ln]; }
+                            wv::sync();
                         }
-                        if (isrep) { ltab[trank] = cend; ltab[64 + trank] = ccnt; ltab[128 + trank] = cslot; }
-                        wv::sync();
-                        if (isrep) { rend = ltab[ln]; rcnt = ltab[64 + ln]; rslot = ltab[128 + ln]; }
-                        wv::sync();
                         lhead += m;
                         progress = true;
                     }
@@ -786,7 +810,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                     // in output order already?  (only checked when the safe queries are the leading ones)
                     const bool ordered = safem == lanes_below(nsafe) &&
                                          (safem & ~1ull & (wv::ballot(eprev > e) | (wv::ballot(eprev == e) & wv::ballot(qprev > q)))) == 0;
-                    if (!ordered) key = sort_lanes64(key);
+                    if (!ordered) key = sort_time_query(e, q, safem, wv::uniform(rdy));
                     const bool emit_me = ln < nsafe;
                     const uint32_t ke = (uint32_t)(key >> 32);
                     uint32_t shift = 0;

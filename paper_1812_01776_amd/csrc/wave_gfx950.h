@@ -26,15 +26,20 @@ EST_DEV uint32_t bcast(uint32_t v, uint32_t l) {
 // value of lane-1 (lane 0 keeps its own) / of lane+1 (lane 63 keeps its own)
 EST_DEV uint32_t shr1(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x138, 0xF, 0xF, false); }
 EST_DEV uint32_t shl1(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x130, 0xF, 0xF, false); }
-// value of lane ^ 1, ^ 2, ^ 4, ^ 8 (data-parallel-primitive moves inside a row of 16 lanes)
-EST_DEV uint32_t xor1(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xF, 0xF, false); }
-EST_DEV uint32_t xor2(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xF, 0xF, false); }
-EST_DEV uint32_t xor8(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x128, 0xF, 0xF, false); }
+// value of lane ^ 1, ^ 2, ^ 4, ^ 8 (data-parallel-primitive moves inside a row of 16 lanes; every
+// lane has a source, so no previous value is carried)
+EST_DEV uint32_t xor1(uint32_t v) { return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true); }
+EST_DEV uint32_t xor2(uint32_t v) { return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true); }
+EST_DEV uint32_t xor8(uint32_t v) { return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x128, 0xF, 0xF, true); }
 EST_DEV uint32_t xor4(uint32_t v) {
-    const uint32_t down = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x124, 0xF, 0xF, false);  // from lane-4 (mod 16)
-    const uint32_t up = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x12C, 0xF, 0xF, false);    // from lane+4 (mod 16)
-    return (lane() & 4u) ? down : up;
+    const uint32_t down = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x124, 0xF, 0xF, true);  // from lane-4 (mod 16)
+    const uint32_t up = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x12C, 0xF, 0xF, true);    // from lane+4 (mod 16)
+    return __builtin_amdgcn_inverse_ballot_w64(0xF0F0F0F0F0F0F0F0ull) ? down : up;
 }
+
+// is this lane's bit set in m?  (m must be the same in every lane; the mask is used as the lane
+// predicate directly, no vector instruction is spent on it)
+EST_DEV bool lane_in(uint64_t m) { return __builtin_amdgcn_inverse_ballot_w64(m); }
 
 // number of set bits of m below this lane's position (m must be the same in every lane)
 EST_DEV uint32_t rank_below(uint64_t m) {

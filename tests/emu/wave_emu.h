@@ -59,6 +59,8 @@ EST_DEV uint32_t xor2(uint32_t v) { return (uint32_t)emu::exchange(v, 12)[emu::l
 EST_DEV uint32_t xor4(uint32_t v) { return (uint32_t)emu::exchange(v, 13)[emu::lane() ^ 4u]; }
 EST_DEV uint32_t xor8(uint32_t v) { return (uint32_t)emu::exchange(v, 14)[emu::lane() ^ 8u]; }
 
+EST_DEV bool lane_in(uint64_t m) { return (m >> emu::lane()) & 1ull; }
+
 // (every lane must pass the same mask: checked like any other wave-uniform argument)
 EST_DEV uint32_t rank_below(uint64_t m) {
     const uint64_t *x = emu::exchange(m, 15);
