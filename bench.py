@@ -107,7 +107,7 @@ def main():
     feasible = int((p99 <= w.slo_us).sum())
 
     # CPU baseline: the oracle as it stands, single thread, on a bounded sample of the same workload
-    n_sample = args.cpu_sample if args.cpu_sample >= 0 else {"W1": 16, "W2": 256, "W3": 64, "W4": 6, "W5": 4}[args.workload]
+    n_sample = args.cpu_sample if args.cpu_sample >= 0 else {"W1": 16, "W2": 1024, "W3": 160, "W4": 16, "W5": 8}[args.workload]
     cpu = None
     if n_sample > 0:
         from oracle import oracle

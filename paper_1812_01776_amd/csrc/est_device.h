@@ -42,9 +42,9 @@ EST_DEV uint32_t sat_add(uint32_t t, uint32_t d) {
     return e < t ? 0xFFFFFFFFu : e;
 }
 
-// LDS of one wavefront, in 8-byte words, for a plan whose widest merge has k sources:
-// staged keys uint64 [k][64] | merged run uint64 [k*64] | staged positions uint32 [k][64].
-// Size: EST_LDS_WORDS64(k).
+// LDS of one wavefront while it merges, for a plan whose widest merge has k sources:
+// staged keys uint64 [k][64] | merged run uint64 [k*64] | staged positions uint32 [k][64] |
+// per-source cursors | duplicate-spotting counters.  Size: EST_LDS_MERGE_BYTES(k).
 
 struct Ctx {
     const EstSimArgs *a;

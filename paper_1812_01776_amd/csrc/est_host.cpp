@@ -323,7 +323,7 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     uint8_t *ws = (uint8_t *)workspace;
     uint64_t ws_bytes = workspace_bytes;
     if (!ws) {
-        const uint64_t max_slots = std::min<uint64_t>(n_cfg, std::max<uint32_t>(estbe::max_resident_waves(), 1));
+        const uint64_t max_slots = std::min<uint64_t>(n_cfg, std::max<uint32_t>(estbe::max_resident_waves(po.lds_bytes), 1));
         uint64_t want = fixed + per_cfg * max_slots + 8 * 256;
         uint64_t avail = (uint64_t)estbe::mem_free() + h->ws_bytes;
         uint64_t budget = std::min<uint64_t>(want, avail / 100 * 85);
@@ -345,7 +345,7 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     // scratch slots: one per wavefront that works on this launch; more than the device can hold at once
     // would only wait
     uint64_t n_slots = std::min<uint64_t>((ws_bytes - fixed - 8 * 256) / per_cfg, n_cfg);
-    n_slots = std::min<uint64_t>(n_slots, std::max<uint32_t>(estbe::max_resident_waves(), 1));
+    n_slots = std::min<uint64_t>(n_slots, std::max<uint32_t>(estbe::max_resident_waves(po.lds_bytes), 1));
     uint64_t at = fixed;
     auto area = [&](uint64_t bytes_per_cfg) {
         uint64_t a0 = at;

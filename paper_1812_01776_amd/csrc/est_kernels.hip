@@ -138,11 +138,18 @@ int launch_sim(const EstSimArgs &a, void *stream) {
     return check(hipGetLastError(), "est_sim_kernel");
 }
 
-uint32_t max_resident_waves() {
-    int dev = 0, cus = 0;
+// Wavefronts of the simulation kernel the device holds at once for a given LDS size per wavefront
+// (registers allow four per SIMD; LDS may allow fewer).  More scratch slots than that would only
+// hold memory: a wavefront that starts after the others have finished finds no candidates left.
+uint32_t max_resident_waves(uint32_t lds_bytes_per_wave) {
+    int dev = 0, cus = 0, blocks = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    return (uint32_t)cus * 32u;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_kernel<false>, 64 * EST_WAVES_PER_BLOCK,
+                                                     (size_t)lds_bytes_per_wave * EST_WAVES_PER_BLOCK) != hipSuccess ||
+        blocks < 1)
+        blocks = 8;  // unknown: assume the most a compute unit can hold
+    return (uint32_t)cus * (uint32_t)blocks * EST_WAVES_PER_BLOCK;
 }
 
 void *event_create() {

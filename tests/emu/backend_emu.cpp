@@ -127,7 +127,7 @@ int launch_sim(const EstSimArgs &a, void *) {
     }
     return 0;
 }
-uint32_t max_resident_waves() { return 3; }
+uint32_t max_resident_waves(uint32_t) { return 3; }
 
 void *event_create() { return malloc(1); }
 void event_destroy(void *e) { free(e); }

@@ -267,3 +267,15 @@ def test_w4_w5_many_configs_short_trace(name):
     w = workloads.WORKLOADS[name](n=2000) if name == "W4" else workloads.w5().subset(n_queries=2000)
     step = w.n_configs // 2048
     _compare(w.subset(cfg_index=np.arange(0, w.n_configs, step)), latencies=False)
+
+
+def test_diagnostics_variant_gives_the_same_results(tmp_path, monkeypatch):
+    """EST_DEBUG_TICKS=<file> launches the kernel variant compiled with step counters and dumps them:
+    per candidate the wavefront's run time, per candidate and stage four counters, then the totals."""
+    w = workloads.random_case(21, S=4, n=1500, C=6, max_b=8, max_r=4)
+    dump = tmp_path / "ticks.bin"
+    monkeypatch.setenv("EST_DEBUG_TICKS", str(dump))
+    _compare(w)
+    d = np.fromfile(dump, dtype=np.uint64)
+    assert d.size == w.n_configs * (1 + 4 * 32) + 8 + 4 * 32 + 8
+    assert (d[:w.n_configs] > 0).all()

@@ -186,3 +186,12 @@ def test_caller_workspace_limits_the_scratch_slots():
                                ctypes.byref(res), ctypes.c_void_p(base), ctypes.c_uint64(20_000), None)
     assert rc == binding.EST_ENOMEM
     assert est.workspace_bytes(300, 7) > 90_000
+
+
+def test_diagnostics_variant_gives_the_same_results(tmp_path, monkeypatch):
+    w = workloads.random_case(21, S=4, n=300, C=3, max_b=8, max_r=4)
+    dump = tmp_path / "ticks.bin"
+    monkeypatch.setenv("EST_DEBUG_TICKS", str(dump))
+    _compare(w)
+    d = np.fromfile(dump, dtype=np.uint64)
+    assert d.size == w.n_configs * (1 + 4 * 32) + 8 + 4 * 32 + 8
