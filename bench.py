@@ -37,6 +37,10 @@ def main():
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="before the timed region, copy this many MiB device to device once (a kernel of known "
                          "traffic, to scale hardware counters read under rocprofv3)")
+    ap.add_argument("--planner", action="store_true",
+                    help="instead of the sweep, time the greedy planner (estimator_plan) on the workload's pipeline, trace and SLO")
+    ap.add_argument("--planner-queries", type=int, default=50000, help="trace prefix the planner works on")
+    ap.add_argument("--planner-max-replicas", type=int, default=32)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: candidate configurations are independent, so more GPUs would each take "
@@ -63,6 +67,26 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.planner:
+        # the step above the hot path: Algorithms 1 and 2 driving the batched Estimator
+        n = min(args.planner_queries, w.n_queries)
+        est = estimator.Estimator(w.parents, w.lat_us, w.cost_uusd_hr)
+        t0 = time.perf_counter()
+        plan = est.plan(w.arrival_us[:n], w.visit_mask[:n], w.slo_us, max_replicas=args.planner_max_replicas)
+        t1 = time.perf_counter()
+        line = {"metric": "greedy planner wall time on 1 MI355X", "value": t1 - t0, "unit": "s", "n_gpus": 1, "steps": 1, "warmup": 0,
+                "ms_per_step": (t1 - t0) * 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u32",
+                "data": "synthetic",
+                "config": {"workload": args.workload + " pipeline, first %d queries, SLO %d us" % (n, w.slo_us), "max_replicas": args.planner_max_replicas,
+                           "feasible": plan is not None}}
+        if plan is not None:
+            line["config"].update({"accepted_steps": plan["n_steps"], "estimator_calls": plan["estimator_calls"],
+                                   "candidates_simulated": plan["candidates"], "cost_uusd_hr": plan["cost_uusd_hr"], "p99_us": plan["p99_us"],
+                                   "plan": [[int(x) for x in c] for c in plan["config"].tolist()],
+                                   "simulations_per_s": plan["candidates"] * n / (t1 - t0)})
+        print(json.dumps(line))
+        return
 
     S = w.n_stages
     stats = {"sim_ms": 0.0, "launches": 0}

@@ -149,6 +149,47 @@ int estimator_run_latencies_dev(estimator_t *h, const est_trace_t *trace,
  */
 uint64_t estimator_workspace_bytes(const estimator_t *h, uint64_t n, uint64_t n_cfg);
 
+/*
+ * The greedy planner of Section 4.3 on top of the batched Estimator: Algorithm 1 (Initialize: batch 1,
+ * one replica and the lowest-latency hardware everywhere; infeasible if the batch-1 service time of
+ * the longest DAG path exceeds the SLO; otherwise add a replica to the throughput bottleneck until
+ * the Estimator's P99 is within the SLO) followed by Algorithm 2 (MinimizeCost: repeatedly apply,
+ * among IncreaseBatch (x2), RemoveReplica (-1) and DowngradeHW (next cheaper hardware, that model
+ * re-initialised and locally re-optimised) on every model, the feasible result of lowest cost, until
+ * no action has a feasible result).  Throughput of a stage = replicas x batch / latency(batch) /
+ * fraction of the trace's queries that visit it.  Every feasibility test is one simulated candidate;
+ * the candidates of one step are simulated together.
+ */
+#define EST_PLAN_INIT 0           /* est_plan_step_t.action: the configuration Initialize returned */
+#define EST_PLAN_INCREASE_BATCH 1
+#define EST_PLAN_REMOVE_REPLICA 2
+#define EST_PLAN_DOWNGRADE_HW 3
+
+typedef struct {
+    uint32_t feasible;        /* 0: no configuration within the limits meets the SLO (config_out untouched) */
+    uint32_t n_steps;         /* accepted steps, the initial configuration included (may exceed steps_cap)   */
+    uint32_t estimator_calls; /* batched simulation calls made                                               */
+    uint32_t p99_us;          /* P99 of the returned configuration                                           */
+    uint64_t candidates;      /* configurations simulated in total                                           */
+    uint64_t cost_uusd_hr;    /* cost of the returned configuration                                          */
+} est_plan_result_t;
+
+typedef struct {
+    uint32_t action;       /* EST_PLAN_*                                   */
+    int32_t stage;         /* the model the action was applied to, -1 for EST_PLAN_INIT */
+    uint64_t cost_uusd_hr; /* cost of the configuration after the step     */
+} est_plan_step_t;
+
+/*
+ * Plan one pipeline for one trace and SLO.  trace holds HOST pointers.  max_replicas (1..EST_MAX_REPLICAS)
+ * bounds the replicas of a stage.  config_out is [S] and receives the plan; steps_out ([steps_cap],
+ * may be NULL when steps_cap is 0) receives the accepted steps in order.  Returns EST_OK also when
+ * no feasible configuration exists (result->feasible == 0).  Errors as for estimator_run.
+ */
+int estimator_plan(estimator_t *h, const est_trace_t *trace, uint32_t slo_us, uint32_t max_replicas,
+                   est_stage_cfg_t *config_out, est_plan_result_t *result, est_plan_step_t *steps_out,
+                   uint32_t steps_cap);
+
 /* Fill *out with the timing of the last successful run on this handle. */
 int estimator_last_stats(const estimator_t *h, est_stats_t *out);
 

@@ -19,7 +19,7 @@ CFG_DTYPE = np.dtype([("hw", "u1"), ("batch", "u1"), ("replicas", "<u2")])
 
 SYMBOLS = ["estimator_create", "estimator_run", "estimator_run_dev", "estimator_run_latencies",
            "estimator_run_latencies_dev", "estimator_workspace_bytes", "estimator_last_stats",
-           "estimator_last_error", "estimator_destroy"]
+           "estimator_last_error", "estimator_destroy", "estimator_plan"]
 
 
 class EstimatorError(RuntimeError):
@@ -46,6 +46,18 @@ class _Result(ctypes.Structure):
     _fields_ = [("p99_us", ctypes.c_void_p), ("miss_count", ctypes.c_void_p), ("cost_uusd_hr", ctypes.c_void_p)]
 
 
+class _PlanResult(ctypes.Structure):
+    _fields_ = [("feasible", ctypes.c_uint32), ("n_steps", ctypes.c_uint32), ("estimator_calls", ctypes.c_uint32),
+                ("p99_us", ctypes.c_uint32), ("candidates", ctypes.c_uint64), ("cost_uusd_hr", ctypes.c_uint64)]
+
+
+class _PlanStep(ctypes.Structure):
+    _fields_ = [("action", ctypes.c_uint32), ("stage", ctypes.c_int32), ("cost_uusd_hr", ctypes.c_uint64)]
+
+
+PLAN_ACTIONS = ("init", "batch", "replica", "hw")
+
+
 class Stats(ctypes.Structure):
     _fields_ = [("n_launches", ctypes.c_uint32), ("n_slots", ctypes.c_uint32), ("sim_ms", ctypes.c_float),
                 ("prep_ms", ctypes.c_float), ("stage_visits", ctypes.c_uint64), ("workspace_bytes", ctypes.c_uint64)]
@@ -70,6 +82,7 @@ def load_library(path=LIB_PATH):
     lib.estimator_last_stats.restype = ctypes.c_int
     lib.estimator_last_error.restype = ctypes.c_char_p
     lib.estimator_destroy.restype = None
+    lib.estimator_plan.restype = ctypes.c_int
     return lib
 
 
@@ -97,6 +110,7 @@ class Estimator:
         cost = np.ascontiguousarray(cost_uusd_hr, dtype=np.uint64)
         S, H, Bmax = lat.shape
         assert cost.shape == (S, H) and len(parents) == S
+        self.S = S
         off = np.zeros(S + 1, dtype=np.uint32)
         idx = []
         for s, ps in enumerate(parents):
@@ -150,6 +164,23 @@ class Estimator:
         tr = _Trace(n, _ptr(arr), _ptr(msk))
         self._check(self._lib.estimator_run_latencies(self._h, ctypes.byref(tr), _ptr(cfg), ctypes.c_uint64(C), _ptr(lat)))
         return lat[:C, :n]
+
+    def plan(self, arrival_us, visit_mask, slo_us, max_replicas=64, max_steps=4096):
+        """estimator_plan: returns None if no feasible configuration exists, else a dict with the
+        configuration ([S] records), its cost and P99, the accepted steps and the call counts."""
+        arr = np.ascontiguousarray(arrival_us, dtype=np.uint32)
+        msk = np.ascontiguousarray(visit_mask, dtype=np.uint32)
+        tr = _Trace(arr.shape[0], _ptr(arr), _ptr(msk))
+        cfg = np.zeros(self.S, dtype=CFG_DTYPE)
+        res = _PlanResult()
+        steps = (_PlanStep * max_steps)()
+        self._check(self._lib.estimator_plan(self._h, ctypes.byref(tr), ctypes.c_uint32(slo_us), ctypes.c_uint32(max_replicas),
+                                             _ptr(cfg), ctypes.byref(res), steps, ctypes.c_uint32(max_steps)))
+        if not res.feasible:
+            return None
+        log = [(PLAN_ACTIONS[steps[i].action], steps[i].stage, steps[i].cost_uusd_hr) for i in range(min(res.n_steps, max_steps))]
+        return {"config": cfg, "cost_uusd_hr": res.cost_uusd_hr, "p99_us": res.p99_us, "steps": log, "n_steps": res.n_steps,
+                "estimator_calls": res.estimator_calls, "candidates": res.candidates}
 
     # ---- device-pointer entry points (torch tensors on the GPU supply memory and the stream)
     def run_dev(self, arrival_t, mask_t, cfg_t, n_cfg, slo_us, workspace_t=None, stream=None):

@@ -360,3 +360,37 @@ def backlog_case(seed):
     rp = rng.choice([1, 1, 2, 2, 3, 4, 5, 8], size=(C, S)).astype(np.uint16)
     return Workload("backlog%d" % seed, parents, lat, cost, arr, mask, hw, bt, rp, int(lat.max()))
 
+
+def planner_case(seed, n=1500):
+    """A small pipeline for the greedy planner: three hardware types per stage (fast and expensive,
+    medium, slow and cheap -- in seeded index order), batching that amortises a fixed cost, an
+    SLO of a few service times, a Poisson-like trace that needs several replicas at batch 1."""
+    rng = np.random.default_rng(3000 + seed)
+    S = int(rng.integers(1, 5))
+    H, Bmax = 3, 16
+    if S >= 3 and seed % 2 == 0:
+        parents = [[], [0], [0]] + ([[1, 2]] if S == 4 else [])
+    else:
+        parents = [[]] + [[s - 1] for s in range(1, S)]
+    speed = np.array([1.0, 2.2, 5.0])
+    price = np.array([900_000, 300_000, 60_000], dtype=np.uint64)
+    lat = np.zeros((S, H, Bmax), np.uint32)
+    cost = np.zeros((S, H), np.uint64)
+    for s in range(S):
+        order = rng.permutation(H)
+        fixed = float(rng.integers(300, 2000))
+        per = float(rng.integers(20, 300))
+        for k, h in enumerate(order):
+            lat[s, h, :] = np.maximum(1, (speed[k] * (fixed + per * np.arange(1, Bmax + 1)))).astype(np.uint32)
+            cost[s, h] = price[k] + int(rng.integers(0, 1000))
+    gap = float(rng.integers(150, 900))
+    arr = np.cumsum(rng.exponential(gap, size=n)).astype(np.uint32)
+    mask = np.zeros(n, np.uint32)
+    for s in range(S):
+        p = 1.0 if (s == 0 or rng.random() < 0.5) else rng.uniform(0.3, 0.9)
+        mask |= (rng.random(n) < p).astype(np.uint32) << np.uint32(s)
+    fast = np.array([lat[s, :, 0].min() for s in range(S)], dtype=np.float64)
+    slo = int(fast.sum() * float(rng.uniform(2.0, 8.0)))
+    hw = np.zeros((1, S), np.uint8)
+    return Workload("plan%d" % seed, parents, lat, cost, arr, mask, hw, np.ones((1, S), np.uint8), np.ones((1, S), np.uint16), slo)
+

@@ -13,7 +13,7 @@ _LIB = os.path.join(_EMU, "libestimator_emu.so")
 
 
 def build():
-    srcs = [os.path.join(_EMU, "backend_emu.cpp"), os.path.join(_CSRC, "est_host.cpp")]
+    srcs = [os.path.join(_EMU, "backend_emu.cpp"), os.path.join(_CSRC, "est_host.cpp"), os.path.join(_CSRC, "est_planner.cpp")]
     deps = srcs + [os.path.join(_EMU, "wave_emu.h")] + [os.path.join(_CSRC, f) for f in os.listdir(_CSRC)] + \
         [os.path.join(os.path.dirname(_HERE), "include", "estimator.h")]
     if os.path.exists(_LIB) and all(os.path.getmtime(_LIB) >= os.path.getmtime(d) for d in deps):
