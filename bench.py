@@ -39,6 +39,8 @@ def main():
                          "traffic, to scale hardware counters read under rocprofv3)")
     ap.add_argument("--planner", action="store_true",
                     help="instead of the sweep, time the greedy planner (estimator_plan) on the workload's pipeline, trace and SLO")
+    ap.add_argument("--handoff", action="store_true",
+                    help="instead of the sweep, time estimator_tuner_handoff (traffic envelope + per-model ratios) on the workload's trace")
     ap.add_argument("--planner-queries", type=int, default=50000, help="trace prefix the planner works on")
     ap.add_argument("--planner-max-replicas", type=int, default=32)
     args = ap.parse_args()
@@ -67,6 +69,24 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.handoff:
+        # traffic envelope of the whole trace (one kernel) + per-model ratios (host arithmetic)
+        est = estimator.Estimator(w.parents, w.lat_us, w.cost_uusd_hr)
+        cfg = estimator.pack_configs(w.cfg_hw[:1], w.cfg_batch[:1], w.cfg_replicas[:1])[0]
+        ts = int(sum(int(w.lat_us[s, w.cfg_hw[0, s], 0]) for s in range(w.n_stages)))  # a service time: every stage at batch 1
+        est.tuner_handoff(w.arrival_us, w.visit_mask, cfg, ts)
+        reps = 5
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            out = est.tuner_handoff(w.arrival_us, w.visit_mask, cfg, ts)
+        dt = (time.perf_counter() - t0) / reps
+        print(json.dumps({"metric": "tuner hand-off (traffic envelope + ratios) wall time, host buffers in, on 1 MI355X", "value": dt, "unit": "s",
+                          "n_gpus": 1, "steps": reps, "warmup": 1, "ms_per_step": dt * 1e3, "higher_is_better": False, "scaling": "weak",
+                          "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+                          "config": {"workload": args.workload + " trace", "n_queries": w.n_queries, "service_time_us": ts,
+                                     "windows": len(out["window_us"]), "max_queries": out["max_queries"]}}))
+        return
 
     if args.planner:
         # the step above the hot path: Algorithms 1 and 2 driving the batched Estimator

@@ -190,6 +190,35 @@ int estimator_plan(estimator_t *h, const est_trace_t *trace, uint32_t slo_us, ui
                    est_stage_cfg_t *config_out, est_plan_result_t *result, est_plan_step_t *steps_out,
                    uint32_t steps_cap);
 
+/*
+ * What the planner hands to the high-frequency tuner (Section 5, "Initialization"): the traffic
+ * envelope of the sample trace and, per model, the single-replica throughput mu_m and the
+ * max-provisioning ratio rho_m of a configuration.
+ *   Envelope: window widths dT_i = service_time_us * 2^i for i = 0, 1, ... while dT_i <= 60 s (at
+ *   least dT_0); max_queries[i] = the largest number of arrivals in any half-open window
+ *   [t, t + dT_i) over the trace; the maximum rate r_i is max_queries[i] / dT_i.
+ *   mu_m  = batch / latency(hw, batch) queries per second  = mu_num / mu_den (mu_den in seconds x 10^6,
+ *           i.e. mu_num = batch * 10^6, mu_den = latency in us).
+ *   rho_m = lambda * s_m / (replicas * mu_m), lambda = n / (last arrival - first arrival), s_m = share
+ *           of the queries that visit the model (the tuner's replica rule k_m = ceil(r s_m / (mu_m rho_m))
+ *           gives back the planned replica count at r = lambda)  = rho_num / rho_den, rho_den == 0
+ *           when the trace spans no time.
+ * All ratios are exact integer pairs.  trace and config ([S]) are HOST pointers.
+ */
+#define EST_MAX_WINDOWS 32
+typedef struct {
+    uint32_t n_windows;
+    uint32_t reserved;
+    uint64_t window_us[EST_MAX_WINDOWS];
+    uint32_t max_queries[EST_MAX_WINDOWS];
+    uint64_t mu_num[EST_MAX_STAGES], mu_den[EST_MAX_STAGES];
+    uint64_t rho_num[EST_MAX_STAGES], rho_den[EST_MAX_STAGES];
+} est_handoff_t;
+
+/* Errors: EST_EINVAL for NULLs, service_time_us == 0, non-monotone arrivals or a configuration entry out of range. */
+int estimator_tuner_handoff(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *config,
+                            uint32_t service_time_us, est_handoff_t *out);
+
 /* Fill *out with the timing of the last successful run on this handle. */
 int estimator_last_stats(const estimator_t *h, est_stats_t *out);
 

@@ -23,6 +23,7 @@ int launch_cfg(const EstCfgArgs &a, void *stream);
 int launch_prep1(const EstPrepArgs &a, void *stream);
 int launch_prep2(const EstPrepArgs &a, void *stream);
 int launch_sim(const EstSimArgs &a, void *stream);
+int launch_envelope(const EstEnvArgs &a, void *stream);
 uint32_t max_resident_waves(uint32_t lds_bytes_per_wave);  // wavefronts of the simulation kernel the device holds at once
 
 void *event_create();

@@ -1413,4 +1413,62 @@ EST_DEV void cfg_thread(const EstCfgArgs &a, uint32_t tid, uint32_t nthreads) {
     if (bad) wv::atomic_or_u32(&a.status->bad_cfg, 1u);
 }
 
+// Traffic envelope of the trace (Section 5, "traffic envelopes"): for every window width the largest
+// number of arrivals in any half-open window [t, t + width).  The maximum is attained by a window
+// that starts at an arrival.  Thread tid (of nthreads) takes a run of consecutive queries; for the
+// first it finds, per width, the first arrival at or after arrival[j] + width (the widths ascend, so
+// each search starts where the previous one ended: gallop, then bisect); for the following queries
+// the window ends only move forward, a step at a time.
+EST_DEV void envelope_thread(const EstEnvArgs &a, uint32_t tid, uint32_t nthreads) {
+    const uint64_t chunk = (a.n + nthreads - 1) / nthreads;
+    const uint64_t j0 = (uint64_t)tid * chunk, j1 = j0 + chunk < a.n ? j0 + chunk : a.n;
+    if (j0 >= j1) return;
+    uint32_t best[EST_MAX_WINDOWS], end[EST_MAX_WINDOWS];  // arrivals [j, end[i]) lie inside window i of query j
+#pragma unroll
+    for (uint32_t i = 0; i < EST_MAX_WINDOWS; ++i) best[i] = end[i] = 0;
+    const uint32_t n = (uint32_t)a.n;
+    {
+        const uint64_t t0 = a.arrival[j0];
+        uint32_t e = (uint32_t)j0 + 1;
+#pragma unroll
+        for (uint32_t i = 0; i < EST_MAX_WINDOWS; ++i) {
+            if (i < a.n_win) {
+                const uint64_t limit = t0 + a.win_us[i];
+                // invariant: arrival[e - 1] < limit
+                uint32_t step = 1;
+                while (e + step <= n && (uint64_t)a.arrival[e + step - 1] < limit) {
+                    e += step;
+                    step <<= 1;
+                }
+                uint32_t lo = e, hi = e + step - 1 < n ? e + step - 1 : n;  // the answer is in [lo, hi]
+                while (lo < hi) {
+                    const uint32_t mid = lo + ((hi - lo) >> 1);
+                    if ((uint64_t)a.arrival[mid] < limit) lo = mid + 1; else hi = mid;
+                }
+                e = lo;
+                end[i] = e;
+                best[i] = e - (uint32_t)j0;
+            }
+        }
+    }
+    for (uint64_t j = j0 + 1; j < j1; ++j) {
+        const uint64_t t0 = a.arrival[j];
+#pragma unroll
+        for (uint32_t i = 0; i < EST_MAX_WINDOWS; ++i) {
+            if (i < a.n_win) {
+                const uint64_t limit = t0 + a.win_us[i];
+                uint32_t e = end[i];  // (> j: the window of the query before already held that query and this one's predecessor)
+                if (e <= (uint32_t)j) e = (uint32_t)j + 1;
+                while (e < n && (uint64_t)a.arrival[e] < limit) ++e;
+                end[i] = e;
+                const uint32_t cnt = e - (uint32_t)j;
+                best[i] = cnt > best[i] ? cnt : best[i];
+            }
+        }
+    }
+#pragma unroll
+    for (uint32_t i = 0; i < EST_MAX_WINDOWS; ++i)
+        if (i < a.n_win && best[i] > a.max_queries[i]) wv::atomic_max_u32(&a.max_queries[i], best[i]);
+}
+
 }  // namespace estdev

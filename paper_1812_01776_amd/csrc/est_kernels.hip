@@ -39,6 +39,10 @@ __global__ __launch_bounds__(256) void est_prep2_kernel(EstPrepArgs a) {
     estdev::prep2_thread(a, blockIdx.x * blockDim.x + threadIdx.x, gridDim.x * blockDim.x);
 }
 
+__global__ __launch_bounds__(256) void est_envelope_kernel(EstEnvArgs a) {
+    estdev::envelope_thread(a, blockIdx.x * blockDim.x + threadIdx.x, gridDim.x * blockDim.x);
+}
+
 __global__ __launch_bounds__(256) void est_cfg_kernel(EstCfgArgs a) {
     estdev::cfg_thread(a, blockIdx.x * blockDim.x + threadIdx.x, gridDim.x * blockDim.x);
 }
@@ -127,6 +131,10 @@ int launch_prep1(const EstPrepArgs &a, void *stream) {
 int launch_prep2(const EstPrepArgs &a, void *stream) {
     est_prep2_kernel<<<blocks_for(a.n, 256, 4096), 256, 0, (hipStream_t)stream>>>(a);
     return check(hipGetLastError(), "est_prep2_kernel");
+}
+int launch_envelope(const EstEnvArgs &a, void *stream) {
+    est_envelope_kernel<<<blocks_for(a.n, 256 * 16, 8192), 256, 0, (hipStream_t)stream>>>(a);  // 16 queries in a row per thread
+    return check(hipGetLastError(), "est_envelope_kernel");
 }
 int launch_sim(const EstSimArgs &a, void *stream) {
     const uint32_t blocks = (a.n_slots + EST_WAVES_PER_BLOCK - 1) / EST_WAVES_PER_BLOCK;

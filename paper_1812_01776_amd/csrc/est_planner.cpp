@@ -375,3 +375,67 @@ extern "C" int estimator_plan(estimator_t *h, const est_trace_t *trace, uint32_t
         return EST_EINTERNAL;
     }
 }
+
+// ---- hand-off to the tuner: traffic envelope (one kernel over the trace) and per-model ratios
+extern "C" int estimator_tuner_handoff(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *config,
+                                       uint32_t service_time_us, est_handoff_t *out) {
+    if (!h) return EST_EINVAL;
+    auto bad = [&](const char *msg) {
+        h->err = msg;
+        return EST_EINVAL;
+    };
+    if (!trace || !config || !out) return bad("handoff: NULL argument");
+    if (trace->n > 0 && (!trace->arrival_us || !trace->visit_mask)) return bad("handoff: trace arrays are NULL");
+    if (service_time_us == 0) return bad("handoff: service time must be positive");
+    if (trace->n >= (1ull << 31)) return bad("handoff: trace too large");
+    const uint32_t S = h->dag.S, H = h->dag.H, Bmax = h->dag.Bmax;
+    for (uint32_t s = 0; s < S; ++s)
+        if (config[s].hw >= H || config[s].batch < 1 || config[s].batch > Bmax || config[s].replicas < 1 || config[s].replicas > EST_MAX_REPLICAS)
+            return bad("handoff: configuration entry out of range");
+    for (uint64_t q = 1; q < trace->n; ++q)
+        if (trace->arrival_us[q] < trace->arrival_us[q - 1]) return bad("handoff: arrival times decrease");
+    est_handoff_t r;
+    memset(&r, 0, sizeof r);
+    for (uint64_t w = service_time_us; r.n_windows < EST_MAX_WINDOWS && (r.n_windows == 0 || w <= 60000000ull); w *= 2)
+        r.window_us[r.n_windows++] = w;
+    if (trace->n > 0) {
+        EstEnvArgs a;
+        memset(&a, 0, sizeof a);
+        void *d_arr = estbe::dmalloc(trace->n * 4), *d_q = estbe::dmalloc(EST_MAX_WINDOWS * 4);
+        int rc = EST_OK;
+        if (!d_arr || !d_q) {
+            h->err = "handoff: device allocation failed";
+            rc = EST_ENOMEM;
+        } else if (estbe::h2d(d_arr, trace->arrival_us, trace->n * 4, nullptr) || estbe::zero(d_q, EST_MAX_WINDOWS * 4, nullptr)) {
+            h->err = std::string("handoff: upload: ") + estbe::last_error();
+            rc = EST_EDEVICE;
+        } else {
+            a.arrival = (const uint32_t *)d_arr;
+            a.n = trace->n;
+            a.n_win = r.n_windows;
+            for (uint32_t i = 0; i < r.n_windows; ++i) a.win_us[i] = r.window_us[i];
+            a.max_queries = (uint32_t *)d_q;
+            if (estbe::launch_envelope(a, nullptr) || estbe::d2h(r.max_queries, d_q, r.n_windows * 4, nullptr) || estbe::sync(nullptr)) {
+                h->err = std::string("handoff: envelope kernel: ") + estbe::last_error();
+                rc = EST_EDEVICE;
+            }
+        }
+        if (d_arr) estbe::dfree(d_arr);
+        if (d_q) estbe::dfree(d_q);
+        if (rc != EST_OK) return rc;
+    }
+    const uint64_t span = trace->n > 0 ? (uint64_t)trace->arrival_us[trace->n - 1] - trace->arrival_us[0] : 0;
+    for (uint32_t s = 0; s < S; ++s) {
+        uint64_t visits = 0;
+        for (uint64_t q = 0; q < trace->n; ++q) visits += (trace->visit_mask[q] >> s) & 1u;
+        const uint64_t L = h->lat[((size_t)s * H + config[s].hw) * Bmax + (config[s].batch - 1)];
+        r.mu_num[s] = (uint64_t)config[s].batch * 1000000ull;
+        r.mu_den[s] = L;
+        // lambda s_m / (R mu_m) = (n / span) (visits / n) / (R batch / L) = visits L / (span R batch)   (times in us cancel)
+        r.rho_num[s] = visits * L;
+        r.rho_den[s] = span * config[s].replicas * config[s].batch;
+    }
+    *out = r;
+    return EST_OK;
+}
+

@@ -129,6 +129,15 @@ struct EstPrepArgs {
     EstStatus *status;
 };
 
+// Traffic envelope (Section 5): the largest number of arrivals inside any window of each width.
+struct EstEnvArgs {
+    const uint32_t *arrival;         // [n], non-decreasing
+    uint64_t n;
+    uint32_t n_win;
+    uint64_t win_us[EST_MAX_WINDOWS];
+    uint32_t *max_queries;           // [n_win], zero on entry
+};
+
 struct EstCfgArgs {
     const EstDag *dag;
     const EstStageCfg *cfg;

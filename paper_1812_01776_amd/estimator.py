@@ -19,7 +19,7 @@ CFG_DTYPE = np.dtype([("hw", "u1"), ("batch", "u1"), ("replicas", "<u2")])
 
 SYMBOLS = ["estimator_create", "estimator_run", "estimator_run_dev", "estimator_run_latencies",
            "estimator_run_latencies_dev", "estimator_workspace_bytes", "estimator_last_stats",
-           "estimator_last_error", "estimator_destroy", "estimator_plan"]
+           "estimator_last_error", "estimator_destroy", "estimator_plan", "estimator_tuner_handoff"]
 
 
 class EstimatorError(RuntimeError):
@@ -55,6 +55,12 @@ class _PlanStep(ctypes.Structure):
     _fields_ = [("action", ctypes.c_uint32), ("stage", ctypes.c_int32), ("cost_uusd_hr", ctypes.c_uint64)]
 
 
+class _Handoff(ctypes.Structure):
+    _fields_ = [("n_windows", ctypes.c_uint32), ("reserved", ctypes.c_uint32), ("window_us", ctypes.c_uint64 * 32),
+                ("max_queries", ctypes.c_uint32 * 32), ("mu_num", ctypes.c_uint64 * 32), ("mu_den", ctypes.c_uint64 * 32),
+                ("rho_num", ctypes.c_uint64 * 32), ("rho_den", ctypes.c_uint64 * 32)]
+
+
 PLAN_ACTIONS = ("init", "batch", "replica", "hw")
 
 
@@ -83,6 +89,7 @@ def load_library(path=LIB_PATH):
     lib.estimator_last_error.restype = ctypes.c_char_p
     lib.estimator_destroy.restype = None
     lib.estimator_plan.restype = ctypes.c_int
+    lib.estimator_tuner_handoff.restype = ctypes.c_int
     return lib
 
 
@@ -181,6 +188,21 @@ class Estimator:
         log = [(PLAN_ACTIONS[steps[i].action], steps[i].stage, steps[i].cost_uusd_hr) for i in range(min(res.n_steps, max_steps))]
         return {"config": cfg, "cost_uusd_hr": res.cost_uusd_hr, "p99_us": res.p99_us, "steps": log, "n_steps": res.n_steps,
                 "estimator_calls": res.estimator_calls, "candidates": res.candidates}
+
+    def tuner_handoff(self, arrival_us, visit_mask, config, service_time_us):
+        """estimator_tuner_handoff: window widths, the envelope's query counts, and per model the exact
+        integer pairs (mu_num, mu_den), (rho_num, rho_den)."""
+        arr = np.ascontiguousarray(arrival_us, dtype=np.uint32)
+        msk = np.ascontiguousarray(visit_mask, dtype=np.uint32)
+        cfg = np.ascontiguousarray(config, dtype=CFG_DTYPE).reshape(-1)
+        tr = _Trace(arr.shape[0], _ptr(arr), _ptr(msk))
+        out = _Handoff()
+        self._check(self._lib.estimator_tuner_handoff(self._h, ctypes.byref(tr), _ptr(cfg), ctypes.c_uint32(service_time_us),
+                                                      ctypes.byref(out)))
+        k = out.n_windows
+        return {"window_us": list(out.window_us[:k]), "max_queries": list(out.max_queries[:k]),
+                "mu": [(out.mu_num[s], out.mu_den[s]) for s in range(self.S)],
+                "rho": [(out.rho_num[s], out.rho_den[s]) for s in range(self.S)]}
 
     # ---- device-pointer entry points (torch tensors on the GPU supply memory and the stream)
     def run_dev(self, arrival_t, mask_t, cfg_t, n_cfg, slo_us, workspace_t=None, stream=None):

@@ -110,6 +110,10 @@ int launch_prep2(const EstPrepArgs &a, void *) {
     for (uint32_t t = 0; t < 7; ++t) estdev::prep2_thread(a, t, 7);
     return 0;
 }
+int launch_envelope(const EstEnvArgs &a, void *) {
+    for (uint32_t t = 0; t < 7; ++t) estdev::envelope_thread(a, t, 7);
+    return 0;
+}
 int launch_sim(const EstSimArgs &a, void *) {
     static uint64_t lds[(64 * 1024) / 8];
     if (a.lds_bytes > sizeof lds) abort();
