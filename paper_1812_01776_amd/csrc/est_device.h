@@ -375,6 +375,9 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             }
             break;
         }
+        // every step below works on a window of up to 64 queries and may emit as many: with less room
+        // than that in the output ring, let the reader run first rather than squeeze batches through
+        if (space < 64u) break;
         const uint32_t w = umin(staged, 64u);
         const uint64_t key = ln < w ? lkey[(lhead + ln) & (SCAN_INRING - 1)] : ~0ull;
         const uint32_t rdy = (uint32_t)(key >> 32);

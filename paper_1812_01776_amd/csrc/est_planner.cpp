@@ -25,6 +25,16 @@ namespace {
 
 typedef std::vector<est_stage_cfg_t> Cfg;  // one entry per stage
 
+struct DevMem {  // device memory freed on every path out
+    void *p;
+    explicit DevMem(size_t bytes) : p(bytes ? estbe::dmalloc(bytes) : nullptr) {}
+    ~DevMem() {
+        if (p) estbe::dfree(p);
+    }
+    DevMem(const DevMem &) = delete;
+    DevMem &operator=(const DevMem &) = delete;
+};
+
 struct Planner {
     estimator *h;
     uint32_t S, H, Bmax, rmax, slo;
@@ -50,8 +60,8 @@ struct Planner {
         const uint64_t C = cands.size();
         std::vector<est_stage_cfg_t> flat(C * S);
         for (uint64_t i = 0; i < C; ++i) memcpy(&flat[i * S], cands[i].data(), S * sizeof(est_stage_cfg_t));
-        void *d_cfg = estbe::dmalloc(C * S * sizeof(est_stage_cfg_t)), *d_p99 = estbe::dmalloc(C * 4), *d_miss = estbe::dmalloc(C * 4),
-             *d_cost = estbe::dmalloc(C * 8);
+        DevMem m_cfg(C * S * sizeof(est_stage_cfg_t)), m_p99(C * 4), m_miss(C * 4), m_cost(C * 8);
+        void *d_cfg = m_cfg.p, *d_p99 = m_p99.p, *d_miss = m_miss.p, *d_cost = m_cost.p;
         bool ok = d_cfg && d_p99 && d_miss && d_cost;
         if (!ok) {
             err = EST_ENOMEM;
@@ -81,10 +91,6 @@ struct Planner {
                 h->err = std::string("planner: download results: ") + estbe::last_error();
             }
         }
-        if (d_cfg) estbe::dfree(d_cfg);
-        if (d_p99) estbe::dfree(d_p99);
-        if (d_miss) estbe::dfree(d_miss);
-        if (d_cost) estbe::dfree(d_cost);
         ++calls;
         candidates += C;
         return ok;
@@ -215,27 +221,16 @@ extern "C" int estimator_plan(estimator_t *h, const est_trace_t *trace, uint32_t
         P.visits.assign(P.S, 0);
         for (uint64_t q = 0; q < trace->n; ++q)
             for (uint32_t s = 0; s < P.S; ++s) P.visits[s] += (trace->visit_mask[q] >> s) & 1u;
-        void *d_arr = nullptr, *d_mask = nullptr;
+        DevMem m_arr(trace->n * 4), m_mask(trace->n * 4);
         if (trace->n > 0) {
-            d_arr = estbe::dmalloc(trace->n * 4);
-            d_mask = estbe::dmalloc(trace->n * 4);
-            if (!d_arr || !d_mask || estbe::h2d(d_arr, trace->arrival_us, trace->n * 4, nullptr) ||
-                estbe::h2d(d_mask, trace->visit_mask, trace->n * 4, nullptr) || estbe::sync(nullptr)) {
-                if (d_arr) estbe::dfree(d_arr);
-                if (d_mask) estbe::dfree(d_mask);
+            if (!m_arr.p || !m_mask.p || estbe::h2d(m_arr.p, trace->arrival_us, trace->n * 4, nullptr) ||
+                estbe::h2d(m_mask.p, trace->visit_mask, trace->n * 4, nullptr) || estbe::sync(nullptr)) {
                 h->err = "planner: cannot place the trace on the device";
                 return EST_ENOMEM;
             }
         }
-        P.d_arr = (const uint32_t *)d_arr;
-        P.d_mask = (const uint32_t *)d_mask;
-        struct Free {
-            void *a, *b;
-            ~Free() {
-                if (a) estbe::dfree(a);
-                if (b) estbe::dfree(b);
-            }
-        } guard{d_arr, d_mask};
+        P.d_arr = (const uint32_t *)m_arr.p;
+        P.d_mask = (const uint32_t *)m_mask.p;
 
         uint32_t n_steps = 0;
         auto log_step = [&](uint32_t action, int32_t stage, uint64_t cost) {
@@ -401,7 +396,8 @@ extern "C" int estimator_tuner_handoff(estimator_t *h, const est_trace_t *trace,
     if (trace->n > 0) {
         EstEnvArgs a;
         memset(&a, 0, sizeof a);
-        void *d_arr = estbe::dmalloc(trace->n * 4), *d_q = estbe::dmalloc(EST_MAX_WINDOWS * 4);
+        DevMem m_arr(trace->n * 4), m_q(EST_MAX_WINDOWS * 4);
+        void *d_arr = m_arr.p, *d_q = m_q.p;
         int rc = EST_OK;
         if (!d_arr || !d_q) {
             h->err = "handoff: device allocation failed";
@@ -420,8 +416,6 @@ extern "C" int estimator_tuner_handoff(estimator_t *h, const est_trace_t *trace,
                 rc = EST_EDEVICE;
             }
         }
-        if (d_arr) estbe::dfree(d_arr);
-        if (d_q) estbe::dfree(d_q);
         if (rc != EST_OK) return rc;
     }
     const uint64_t span = trace->n > 0 ? (uint64_t)trace->arrival_us[trace->n - 1] - trace->arrival_us[0] : 0;
