@@ -82,6 +82,16 @@ EST_DEV View view_of(const Ctx &c, int32_t ring) {
     return v;
 }
 
+// The same with the scalars marked as identical in every lane (they are: one address, one value), which
+// keeps everything computed from them in scalar registers.
+EST_DEV View uniform_view_of(const Ctx &c, int32_t ring) {
+    View v = view_of(c, ring);
+    v.mask = wv::uniform(v.mask);
+    v.wr = wv::uniform(v.wr);
+    v.fin = wv::uniform(v.fin);
+    return v;
+}
+
 // Free elements of a ring: capacity minus the distance to its slowest consumer.
 EST_DEV uint32_t ring_space(const Ctx &c, int32_t ring, uint32_t wr) {
     const EstRing &R = c.P->rings[ring];
@@ -268,7 +278,9 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     const EstPlan &P = *c.P;
     const uint32_t s = op.stage;
     const EstStageCfg sc = c.cfg[s];
-    const uint32_t B = sc.batch, R = sc.replicas, bm = op.b_max;
+    // (values read from memory are the same in every lane; saying so keeps what is computed from them in
+    // scalar registers, off the vector unit)
+    const uint32_t B = wv::uniform(sc.batch), R = wv::uniform(sc.replicas), bm = wv::uniform(op.b_max);
     EST_CHECK(B >= 1 && B <= op.b_max && R >= 1 && R <= op.r_max);
     const uint32_t *Ltab = c.a->lat_us + ((uint64_t)s * c.a->dag->H + sc.hw) * c.a->dag->Bmax;
     const uint32_t Lmine = ln < B ? Ltab[ln] : 0u;  // lane l holds L(l+1)
@@ -301,14 +313,17 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     }
     wv::sync();
 
-    const View in = view_of(c, op.src_ring[0]);
-    uint32_t rraw = c.st[P.rd_off + op.src_edge[0]];  // next source position to read
+    View in = view_of(c, op.src_ring[0]);
+    in.mask = wv::uniform(in.mask);
+    in.wr = wv::uniform(in.wr);
+    in.fin = wv::uniform(in.fin);
+    uint32_t rraw = wv::uniform(c.st[P.rd_off + op.src_edge[0]]);  // next source position to read
     uint32_t lhead = 0, ltail = 0;                     // in-ring: consumed / filled
     const EstRing &OR = P.rings[op.out_ring];
     uint64_t *out = c.rings + OR.off;
-    const uint32_t omask = OR.cap_mask;
-    uint32_t wr = c.st[P.wr_off + op.out_ring];
-    uint32_t space = ring_space(c, op.out_ring, wr);
+    const uint32_t omask = wv::uniform(OR.cap_mask);
+    uint32_t wr = wv::uniform(c.st[P.wr_off + op.out_ring]);
+    uint32_t space = wv::uniform(ring_space(c, op.out_ring, wr));
     bool progress = false, finished = false;
 #ifdef EST_EMU_CHECKS
     uint32_t chk_wr = wr;  // everything written from here on is verified to be in order, step by step
@@ -693,7 +708,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                         space -= ns + extra;
                         EST_CHK_ORDER(inv ? 3 : 2);
                         // the run's batches that finish at or after tau wait in the slot of their replica
-                        const uint32_t inv_p = linv[p - 1u];                      // floor(x / p) = x * inv_p >> 16 for x < 64
+                        const uint32_t inv_p = wv::uniform(linv[p - 1u]);                      // floor(x / p) = x * inv_p >> 16 for x < 64
                         const uint32_t kmod = bid - p * ((bid * inv_p) >> 16);   // the replica (idle-table lane) of my group
                         const uint32_t myslot = wv::shfl(rslot, kmod);
                         const bool waits = ln < m && !safe;
@@ -952,8 +967,8 @@ template <bool DIAG>
 EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     const uint32_t ln = wv::lane();
     const EstPlan &P = *c.P;
-    const uint32_t K = op.n_src;
-    const bool is_lat = op.type == EST_OP_LAT;
+    const uint32_t K = wv::uniform(op.n_src);
+    const bool is_lat = wv::uniform(op.type) == EST_OP_LAT;
     const uint8_t *acc = c.a->acc + (uint64_t)op.acc_idx * c.a->acc_stride;
     uint8_t *cnt = c.cnt + op.cnt_off;
     uint64_t *skey = c.lds;
@@ -970,21 +985,21 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     uint64_t *out = nullptr;
     uint32_t omask = 0, wr, space = 0xFFFFFFFFu;
     if (is_lat) {
-        wr = c.st[P.miss_off + 1];
+        wr = wv::uniform(c.st[P.miss_off + 1]);
     } else {
         const EstRing &OR = P.rings[op.out_ring];
         out = c.rings + OR.off;
-        omask = OR.cap_mask;
-        wr = c.st[P.wr_off + op.out_ring];
-        space = ring_space(c, op.out_ring, wr);
+        omask = wv::uniform(OR.cap_mask);
+        wr = wv::uniform(c.st[P.wr_off + op.out_ring]);
+        space = wv::uniform(ring_space(c, op.out_ring, wr));
     }
     uint32_t miss = 0;
     bool progress = false, finished = false;
 
     if (K == 1 && !op.has_cnt) {
         // one source, every query fed by it alone: filter and copy, window by window
-        const View sv = view_of(c, op.src_ring[0]);
-        uint32_t rc = raw[0];
+        const View sv = uniform_view_of(c, op.src_ring[0]);
+        uint32_t rc = wv::uniform(raw[0]);
         for (;;) {
             if (!is_lat && space < 64u) break;  // wait for the consumer
             if (rc == sv.wr) {
@@ -1020,8 +1035,8 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         // ---- stage up to 64 accepted elements of every source
         uint32_t more = 0;  // bit j: elements beyond the staged ones may exist in source j
         for (uint32_t j = 0; j < K; ++j) {
-            const View sv = view_of(c, op.src_ring[j]);
-            uint32_t n = 0, rc = raw[j];
+            const View sv = uniform_view_of(c, op.src_ring[j]);
+            uint32_t n = 0, rc = wv::uniform(raw[j]);
             while (n < 64 && rc != sv.wr) {
                 const uint32_t w = umin(64u, sv.wr - rc);
                 const uint64_t key = ln < w ? sv.base[(rc + ln) & sv.mask] : 0ull;
@@ -1055,12 +1070,14 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         bool blocked = false;
         uint32_t staged_total = 0;
         for (uint32_t j = 0; j < K; ++j) {
-            staged_total += nst[j];
+            const uint32_t nj = wv::uniform(nst[j]);
+            staged_total += nj;
             if (!((more >> j) & 1u)) continue;
-            if (nst[j] == 0) {
+            if (nj == 0) {
                 blocked = true;
             } else {
-                uint64_t last = eff_key(skey[j * 64 + nst[j] - 1], j, nst[j] - 1);
+                const uint64_t lk = skey[j * 64 + nj - 1];
+                const uint64_t last = eff_key(((uint64_t)wv::uniform((uint32_t)(lk >> 32)) << 32) | wv::uniform((uint32_t)lk), j, nj - 1);
                 bound = last < bound ? last : bound;
             }
         }
@@ -1071,13 +1088,18 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         // ---- rank every staged element up to the bound among all staged elements
         uint32_t m_total = 0;
         bool clamped = false;  // some staged key sits at the horizon (a source's keys ascend: look at its last)
-        for (uint32_t j = 0; j < K; ++j) clamped = clamped || (nst[j] > 0 && (uint32_t)(skey[j * 64 + nst[j] - 1u] >> 32) == 0xFFFFFFFFu);
         for (uint32_t j = 0; j < K; ++j) {
-            const bool have = ln < nst[j];
+            const uint32_t nj = wv::uniform(nst[j]);
+            clamped = clamped || (nj > 0 && wv::uniform((uint32_t)(skey[j * 64 + nj - 1u] >> 32)) == 0xFFFFFFFFu);
+        }
+        for (uint32_t j = 0; j < K; ++j) {
+            const uint32_t nj = wv::uniform(nst[j]);
+            const bool have = ln < nj;
             const uint64_t rk = have ? skey[j * 64 + ln] : 0ull;
             const uint64_t x = eff_key(rk, j, ln);
             const bool emit = have && x <= bound;
-            m_src[j] = popc64(lanes_below(nst[j]) & wv::ballot(x <= bound));
+            const uint32_t mj = popc64(lanes_below(nj) & wv::ballot(x <= bound));
+            m_src[j] = mj;
             if (emit) {
                 uint32_t rank = ln;
                 for (uint32_t j2 = 0; j2 < K; ++j2) {
@@ -1103,7 +1125,7 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 EST_CHECK(rank < P.max_src * 64);
                 merged[rank] = rk;
             }
-            m_total += m_src[j];
+            m_total += mj;
         }
         EST_CHECK(m_total >= 1);
         if (DIAG && c.a->dbg_ticks && ln == 0) { wv::atomic_add_u64(c.a->status->dbg_cnt + 5, 1); wv::atomic_add_u64(c.a->status->dbg_cnt + 6, m_total); }
@@ -1224,7 +1246,7 @@ EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *
     for (;;) {
         bool progress = false, alldone = true;
         for (uint32_t opi = 0; opi < P.n_ops; ++opi) {
-            if (c.st[P.done_off + opi]) continue;
+            if (wv::uniform(c.st[P.done_off + opi])) continue;
             const EstOp &op = P.ops[opi];
             const uint64_t k0 = (DIAG && a.dbg_ticks) ? wv::ticks() : 0;
             bool p = op.type == EST_OP_SCAN ? scan_run<DIAG>(c, op, opi) : merge_run<DIAG>(c, op, opi);
@@ -1236,7 +1258,7 @@ EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *
                 if (op.type == EST_OP_SCAN) a.dbg_ticks[a.n_cfg + ((uint64_t)t * EST_MAX_STAGES + op.stage) * 4 + 1] += dt;  // per candidate and stage
             }
             progress = progress || p;
-            alldone = alldone && c.st[P.done_off + opi] != 0;
+            alldone = alldone && wv::uniform(c.st[P.done_off + opi]) != 0;
         }
         if (alldone) break;
         if (!progress) {
