@@ -1449,13 +1449,13 @@ EST_DEV void envelope_thread(const EstEnvArgs &a, uint32_t tid, uint32_t nthread
     const uint64_t j0 = (uint64_t)tid * chunk, j1 = j0 + chunk < a.n ? j0 + chunk : a.n;
     if (j0 >= j1) return;
     uint32_t best[EST_MAX_WINDOWS], end[EST_MAX_WINDOWS];  // arrivals [j, end[i]) lie inside window i of query j
-#pragma unroll
+EST_UNROLL
     for (uint32_t i = 0; i < EST_MAX_WINDOWS; ++i) best[i] = end[i] = 0;
     const uint32_t n = (uint32_t)a.n;
     {
         const uint64_t t0 = a.arrival[j0];
         uint32_t e = (uint32_t)j0 + 1;
-#pragma unroll
+EST_UNROLL
         for (uint32_t i = 0; i < EST_MAX_WINDOWS; ++i) {
             if (i < a.n_win) {
                 const uint64_t limit = t0 + a.win_us[i];
@@ -1478,7 +1478,7 @@ EST_DEV void envelope_thread(const EstEnvArgs &a, uint32_t tid, uint32_t nthread
     }
     for (uint64_t j = j0 + 1; j < j1; ++j) {
         const uint64_t t0 = a.arrival[j];
-#pragma unroll
+EST_UNROLL
         for (uint32_t i = 0; i < EST_MAX_WINDOWS; ++i) {
             if (i < a.n_win) {
                 const uint64_t limit = t0 + a.win_us[i];
@@ -1491,7 +1491,7 @@ EST_DEV void envelope_thread(const EstEnvArgs &a, uint32_t tid, uint32_t nthread
             }
         }
     }
-#pragma unroll
+EST_UNROLL
     for (uint32_t i = 0; i < EST_MAX_WINDOWS; ++i)
         if (i < a.n_win && best[i] > a.max_queries[i]) wv::atomic_max_u32(&a.max_queries[i], best[i]);
 }

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #define EST_DEV __device__ __forceinline__
+#define EST_UNROLL _Pragma("unroll")
 #define EST_CHECK(cond) ((void)0)
 
 namespace wv {

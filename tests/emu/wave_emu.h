@@ -11,6 +11,7 @@
 #include <stdlib.h>
 
 #define EST_DEV static inline
+#define EST_UNROLL
 #define EST_CHECK(cond)                                                                       \
     do {                                                                                      \
         if (!(cond)) {                                                                        \
