@@ -1,7 +1,7 @@
 """Plain reference of what the planner hands to the tuner (arXiv 1812.01776, Section 5,
 "Initialization"): the traffic envelope of the sample trace and the per-model ratios.
 
-TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
+TEST INFRASTRUCTURE ONLY: imported by tests/ and nothing else.
 
 Envelope: window widths dT_i = T_s * 2^i while dT_i <= 60 s (at least dT_0); q_i = the largest number
 of arrivals in any half-open window [t, t + dT_i).  Written as the definition: a window holding the
