@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 # HBM bytes per launch of est_sim_kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes summarised in
 # profiles/est_sim_kernel_W4.md, keyed by (workload, candidates per call).  Valid for the kernel those
 # passes profiled; an entry is removed when the kernel changes and put back after re-profiling.
-MEASURED_TRAFFIC_BYTES = {("W4", 65536): 1.5188e13}
+MEASURED_TRAFFIC_BYTES = {("W4", 65536): 1.5719e13}
 
 
 def main():

@@ -197,7 +197,7 @@ EST_DEV uint64_t sort_time_query(uint32_t e, uint32_t q, uint64_t VM, uint32_t b
 // ------------------------------------------------------------------------------------------ SCAN
 //
 // Per-wavefront working set of a scan, in LDS:
-//   in-ring   256 (key, source position) pairs: the next elements of the stage's input stream,
+//   in-ring   256 keys: the next elements of the stage's input stream,
 //             refilled from the source ring in chunks (and filtered on the way, when only some
 //             elements of the source visit the stage);
 //   slots     one per replica: the members of the replica's last batch, sorted by query index,
@@ -213,7 +213,7 @@ enum { SCAN_INRING = 256 };
 EST_DEV bool scan_emit(const EstOp &op, const uint32_t *lslots, uint64_t E, uint32_t rend, uint32_t &rcnt,
                        uint32_t rslot, uint64_t *out, uint32_t omask, uint32_t &wr, uint32_t &space, bool &progress) {
     const uint32_t ln = wv::lane();
-    const uint32_t bm = op.b_max;
+    const uint32_t bm = wv::uniform(op.b_max);
     while (E) {
         const uint32_t l0 = ctz64(E);
         const uint32_t mv = wv::bcast(rend, l0);
@@ -290,11 +290,10 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     uint32_t *g_end = c.rep + op.rep_off, *g_cnt = g_end + op.r_max, *g_slot = g_cnt + op.r_max;
     uint32_t *g_slots = c.slots + op.slot_off;
     uint64_t *lkey = c.lds;
-    uint32_t *lpos = (uint32_t *)(c.lds + SCAN_INRING);
-    uint32_t *ltab = lpos + SCAN_INRING;   // 10 x 64 words: staging for re-sorting the replica table, per-group values
-    uint32_t *lstart = ltab + 448;         // 65: first lane of each group of a window (+ the end)
-    uint32_t *linv = ltab + 576;           // 64: linv[d-1] = ceil(65536 / d), so that floor(x / d) = x * linv[d-1] >> 16 for x <= 64
-    uint32_t *lslots = ltab + 640;
+    uint32_t *ltab = (uint32_t *)(c.lds + SCAN_INRING);  // 4 x 64 words of per-group values (reused as staging by the rare table re-sort)
+    uint32_t *lstart = ltab + 256;         // 65 (of 72): first lane of each group of a window (+ the end)
+    uint32_t *linv = ltab + 328;           // 64: linv[d-1] = ceil(65536 / d), so that floor(x / d) = x * linv[d-1] >> 16 for x <= 64
+    uint32_t *lslots = ltab + 392;
     const uint8_t *acc = c.a->acc + (uint64_t)op.acc_idx * c.a->acc_stride;
     const uint64_t below = lanes_below(ln);
     linv[ln] = (65536u + ln) / (ln + 1u);
@@ -318,6 +317,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     in.wr = wv::uniform(in.wr);
     in.fin = wv::uniform(in.fin);
     uint32_t rraw = wv::uniform(c.st[P.rd_off + op.src_edge[0]]);  // next source position to read
+    const uint32_t rd_entry = rraw;
     uint32_t lhead = 0, ltail = 0;                     // in-ring: consumed / filled
     const EstRing &OR = P.rings[op.out_ring];
     uint64_t *out = c.rings + OR.off;
@@ -375,9 +375,9 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             ltail += popc64(A1);
             const uint32_t i2 = (ltail + wv::rank_below(A2)) & (SCAN_INRING - 1);
             ltail += popc64(A2);
-            if (a0) { lkey[i0] = k0; lpos[i0] = rraw + ln; }
-            if (a1) { lkey[i1] = k1; lpos[i1] = rraw + 64 + ln; }
-            if (a2) { lkey[i2] = k2; lpos[i2] = rraw + 128 + ln; }
+            if (a0) lkey[i0] = k0;
+            if (a1) lkey[i1] = k1;
+            if (a2) lkey[i2] = k2;
             rraw += w0 + w1 + w2;
             EST_CHECK(ltail - lhead <= SCAN_INRING);
             wv::sync();
@@ -573,7 +573,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             const uint32_t pidle = popc64(idle0);  // idle now: a prefix of the sorted table
             uint32_t m = 0;
             if (pidle > 0) {
-                uint32_t *lend = ltab + 192, *lg = ltab + 256, *luns = ltab + 320;  // per group: end, size, waits
+                uint32_t *lend = ltab, *lg = ltab + 64, *luns = ltab + 128;  // per group: end, size, waits
                 // groups: queries with the same ready time, cut into pieces of B (a piece of B queries is
                 // a full batch; the queries of a run are in query-index order, so piece j holds its
                 // members j*B .. j*B+B-1, as the queue would hand them out)
@@ -602,7 +602,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 const uint32_t g = nh - start;
                 const bool final = staged <= 64 && rraw == in.wr && in.fin;
                 const uint32_t e = sat_add(rdy, wv::shfl(Lmine, g - 1));       // (L is 0 beyond B: rejected below)
-                uint32_t *lrdy = ltab + 384;                                   // per group: ready time
+                uint32_t *lrdy = ltab + 192;                                   // per group: ready time
                 if (ln < w && ln == start) { lend[bid] = e; lg[bid] = g; lrdy[bid] = rdy; }
                 wv::sync();
                 // replicas that serve the run: the table's first p entries, each free by the time its turn
@@ -740,6 +740,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                                 const uint32_t ej = wv::bcast(cend, j);
                                 if (ej < cend || (ej == cend && j < ln)) ++trank;
                             }
+                            wv::sync();  // (the per-group values in this area have been read)
                             if (isrep) { ltab[trank] = cend; ltab[64 + trank] = ccnt; ltab[128 + trank] = cslot; }
                             wv::sync();
                             if (isrep) { rend = ltab[ln]; rcnt = ltab[64 + ln]; rslot = ltab[128 + ln]; }
@@ -942,9 +943,37 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         const uint32_t cn = wv::bcast(rcnt, l), sl = wv::bcast(rslot, l);
         if (ln < cn) g_slots[sl * bm + ln] = lslots[sl * bm + ln];
     }
+    // Staged but unconsumed queries are read again next time: the read cursor goes back to the first of
+    // them.  Without a filter that is simply their number of places back; with one, the source is walked
+    // backwards, a window at a time, until that many accepted queries have been passed.
+    uint32_t cursor = rraw;
+    {
+        uint32_t need = ltail - lhead;
+        if (!op.filtered) {
+            cursor = rraw - need;
+        } else {
+            while (need > 0) {
+                const uint32_t wb = umin(64u, cursor - rd_entry);  // (never back beyond where this call started)
+                EST_CHECK(wb > 0);
+                const uint32_t from = cursor - wb;
+                const uint64_t kb = ln < wb ? in.base[(from + ln) & in.mask] : 0ull;
+                const uint64_t Ab = lanes_below(wb) & wv::ballot((acc[(uint32_t)kb] & 1u) != 0u);
+                const uint32_t have = popc64(Ab);
+                if (have < need) {
+                    need -= have;
+                    cursor = from;
+                    continue;
+                }
+                // the need-th accepted query from the top of this window
+                uint64_t rest = Ab;
+                for (uint32_t i = have; i > need; --i) rest &= rest - 1;  // drop the accepted ones below it
+                cursor = from + ctz64(rest);
+                need = 0;
+            }
+        }
+    }
     if (ln == 0) {
-        // staged but unconsumed elements are read again next time
-        c.st[P.rd_off + op.src_edge[0]] = (ltail != lhead) ? lpos[lhead & (SCAN_INRING - 1)] : rraw;
+        c.st[P.rd_off + op.src_edge[0]] = cursor;
         c.st[P.wr_off + op.out_ring] = wr;
         if (finished) {
             c.st[P.fin_off + op.out_ring] = 1;

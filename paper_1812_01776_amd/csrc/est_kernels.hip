@@ -23,13 +23,20 @@ int check(hipError_t e, const char *what) {
 // pinned at 128 per lane (four wavefronts per SIMD): one register more would cost a quarter of the
 // resident wavefronts, which costs more than the few spills this forces.
 #define EST_WAVES_PER_BLOCK 4
-template <bool DIAG>
-__global__ __launch_bounds__(64 * EST_WAVES_PER_BLOCK) __attribute__((amdgpu_waves_per_eu(4, 4))) void est_sim_kernel(EstSimArgs a) {
+template <bool DIAG, int WAVES_PER_SIMD>
+__global__ __launch_bounds__(64 * EST_WAVES_PER_BLOCK) __attribute__((amdgpu_waves_per_eu(WAVES_PER_SIMD, WAVES_PER_SIMD)))
+void est_sim_kernel(EstSimArgs a) {
     extern __shared__ uint64_t lds[];  // EST_WAVES_PER_BLOCK x a.lds_bytes
     const uint32_t wave = threadIdx.x >> 6;
     const uint32_t slot = blockIdx.x * EST_WAVES_PER_BLOCK + wave;
     if (slot < a.n_slots) estdev::slot_loop<DIAG>(a, slot, lds + (size_t)wave * (a.lds_bytes / 8));
 }
+
+// The kernel is built for four wavefronts per SIMD (128 registers per lane) and for five (96 registers, a
+// few spills): the second is used when the LDS need of the launch lets five workgroups share a compute
+// unit, where the extra wavefront hides more latency than the spills cost.
+constexpr uint32_t LDS_PER_CU = 160u * 1024u;
+bool five_fit(uint32_t lds_bytes_per_wave) { return (uint64_t)lds_bytes_per_wave * EST_WAVES_PER_BLOCK * 5u <= LDS_PER_CU; }
 
 __global__ __launch_bounds__(256) void est_prep1_kernel(EstPrepArgs a) {
     estdev::prep1_thread(a, blockIdx.x * blockDim.x + threadIdx.x, gridDim.x * blockDim.x);
@@ -139,10 +146,14 @@ int launch_envelope(const EstEnvArgs &a, void *stream) {
 int launch_sim(const EstSimArgs &a, void *stream) {
     const uint32_t blocks = (a.n_slots + EST_WAVES_PER_BLOCK - 1) / EST_WAVES_PER_BLOCK;
     // (the variant that keeps diagnostic counters is launched only when they are asked for)
+    const size_t lds = (size_t)a.lds_bytes * EST_WAVES_PER_BLOCK;
+    const dim3 grid(blocks), block(64 * EST_WAVES_PER_BLOCK);
     if (a.dbg_ticks)
-        est_sim_kernel<true><<<blocks, 64 * EST_WAVES_PER_BLOCK, (size_t)a.lds_bytes * EST_WAVES_PER_BLOCK, (hipStream_t)stream>>>(a);
+        est_sim_kernel<true, 4><<<grid, block, lds, (hipStream_t)stream>>>(a);
+    else if (five_fit(a.lds_bytes))
+        est_sim_kernel<false, 5><<<grid, block, lds, (hipStream_t)stream>>>(a);
     else
-        est_sim_kernel<false><<<blocks, 64 * EST_WAVES_PER_BLOCK, (size_t)a.lds_bytes * EST_WAVES_PER_BLOCK, (hipStream_t)stream>>>(a);
+        est_sim_kernel<false, 4><<<grid, block, lds, (hipStream_t)stream>>>(a);
     return check(hipGetLastError(), "est_sim_kernel");
 }
 
@@ -153,10 +164,12 @@ uint32_t max_resident_waves(uint32_t lds_bytes_per_wave) {
     int dev = 0, cus = 0, blocks = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_kernel<false>, 64 * EST_WAVES_PER_BLOCK,
-                                                     (size_t)lds_bytes_per_wave * EST_WAVES_PER_BLOCK) != hipSuccess ||
-        blocks < 1)
-        blocks = 8;  // unknown: assume the most a compute unit can hold
+    const hipError_t e = five_fit(lds_bytes_per_wave)
+                             ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_kernel<false, 5>, 64 * EST_WAVES_PER_BLOCK,
+                                                                            (size_t)lds_bytes_per_wave * EST_WAVES_PER_BLOCK)
+                             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_kernel<false, 4>, 64 * EST_WAVES_PER_BLOCK,
+                                                                            (size_t)lds_bytes_per_wave * EST_WAVES_PER_BLOCK);
+    if (e != hipSuccess || blocks < 1) blocks = 8;  // unknown: assume the most a compute unit can hold
     return (uint32_t)cus * (uint32_t)blocks * EST_WAVES_PER_BLOCK;
 }
 
@@ -191,7 +204,7 @@ extern "C" int est_selftest_wave(uint32_t *host_out) {
 // given LDS size per wavefront (diagnostics).
 extern "C" int est_debug_occupancy(uint32_t lds_bytes_per_wave) {
     int blocks = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_kernel<false>, 64 * EST_WAVES_PER_BLOCK,
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_kernel<false, 4>, 64 * EST_WAVES_PER_BLOCK,
                                                      (size_t)lds_bytes_per_wave * EST_WAVES_PER_BLOCK) != hipSuccess)
         return -1;
     return blocks;

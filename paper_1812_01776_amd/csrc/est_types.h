@@ -14,7 +14,7 @@
 #define EST_SRC_TRACE (-1)
 #define EST_DUP_BUCKETS 128u                       // hash buckets for spotting one query twice in a window of a join
 #define EST_LDS_MERGE_BYTES(k) ((k) * 1280u + 128u + 4u * EST_DUP_BUCKETS)   // LDS of one wavefront for a k-source merge
-#define EST_LDS_SCAN_BYTES(rb) (5632u + 4u * (rb))      // ... for a scan whose replica slots hold rb members
+#define EST_LDS_SCAN_BYTES(rb) (3616u + 4u * (rb))      // ... for a scan whose replica slots hold rb members
 
 enum { EST_OP_SCAN = 0, EST_OP_MERGE = 1, EST_OP_LAT = 2 };
 
