@@ -6,10 +6,12 @@
 //     bottleneck sequence does not depend on the feasibility answers, so the next 32 configurations of
 //     that sequence are evaluated at once and the first feasible one is taken;
 //   * DowngradeHW re-initialises one model on the next cheaper hardware by adding replicas until
-//     feasible: all replica counts 1..max are evaluated at once and the smallest feasible one is
-//     taken; its local IncreaseBatch / RemoveReplica search advances in lock step for all models;
+//     feasible, then walks IncreaseBatch / RemoveReplica on that model alone: every configuration that
+//     search can reach differs from the current one only in that model's (batch, replicas) on the
+//     cheaper hardware, so that whole grid (batch 1, 2, 4, ... x replicas 1..max) is evaluated and the
+//     search becomes table look-ups;
 //   * one iteration of MinimizeCost evaluates IncreaseBatch and RemoveReplica of every model together
-//     with the re-initialisations above, then picks the cheapest feasible result (first in
+//     with the grids above in ONE call, then picks the cheapest feasible result (first in
 //     (model, action) order on ties).
 #include <algorithm>
 #include <cstdio>
@@ -254,10 +256,15 @@ extern "C" int estimator_plan(estimator_t *h, const est_trace_t *trace, uint32_t
         log_step(EST_PLAN_INIT, -1, P.cost(cfg));
 
         for (;;) {
-            // -- candidates of this iteration: per model IncreaseBatch, RemoveReplica, and the re-initialisation
-            //    of DowngradeHW (all replica counts on the cheaper hardware at batch 1)
+            // -- candidates of this iteration: per model IncreaseBatch and RemoveReplica, and for DowngradeHW the
+            //    whole (batch, replicas) grid of that model on the cheaper hardware.  The action's replica search
+            //    and its local search only ever visit grid points, so one batched Estimator call answers every
+            //    question the iteration can ask and the walk itself runs on the host from the table.
             std::vector<Cfg> cands;
             std::vector<int> idx_inc(P.S, -1), idx_rem(P.S, -1), idx_down(P.S, -1), hw2(P.S, -1);
+            uint32_t nb = 0;  // batch sizes 1, 2, 4, ... that fit the profile
+            while ((2u << nb) <= P.Bmax) ++nb;
+            ++nb;
             for (uint32_t s = 0; s < P.S; ++s) {
                 Cfg c;
                 if (P.increase_batch(cfg, s, c)) {
@@ -271,58 +278,42 @@ extern "C" int estimator_plan(estimator_t *h, const est_trace_t *trace, uint32_t
                 hw2[s] = P.cheaper_hw(cfg, s);
                 if (hw2[s] >= 0) {
                     idx_down[s] = (int)cands.size();
-                    for (uint32_t r = 1; r <= P.rmax; ++r) {
-                        c = cfg;
-                        c[s].hw = (uint8_t)hw2[s];
-                        c[s].batch = 1;
-                        c[s].replicas = (uint16_t)r;
-                        cands.push_back(c);
-                    }
+                    for (uint32_t k = 0; k < nb; ++k)
+                        for (uint32_t r = 1; r <= P.rmax; ++r) {
+                            c = cfg;
+                            c[s].hw = (uint8_t)hw2[s];
+                            c[s].batch = (uint8_t)(1u << k);
+                            c[s].replicas = (uint16_t)r;
+                            cands.push_back(c);
+                        }
                 }
             }
             std::vector<uint32_t> p99;
             if (!P.evaluate(cands, p99)) return P.err;
-            // -- DowngradeHW: smallest feasible replica count, then the local search, all models in lock step
+            // -- DowngradeHW: smallest feasible replica count at batch 1, then IncreaseBatch / RemoveReplica on
+            //    that model alone while one of them stays feasible (the cheaper of the two, the larger batch when
+            //    they cost the same)
             std::vector<Cfg> local(P.S);
             std::vector<char> alive(P.S, 0);
             for (uint32_t s = 0; s < P.S; ++s) {
                 if (idx_down[s] < 0) continue;
-                for (uint32_t r = 1; r <= P.rmax; ++r)
-                    if (p99[idx_down[s] + r - 1] <= P.slo) {
-                        local[s] = cands[idx_down[s] + r - 1];
-                        alive[s] = 1;
-                        break;
-                    }
-            }
-            std::vector<char> searching = alive;
-            for (;;) {
-                std::vector<Cfg> lc;
-                std::vector<int> li(P.S, -1), lr(P.S, -1);
-                for (uint32_t s = 0; s < P.S; ++s) {
-                    if (!searching[s]) continue;
-                    Cfg c;
-                    if (P.increase_batch(local[s], s, c)) {
-                        li[s] = (int)lc.size();
-                        lc.push_back(c);
-                    }
-                    if (P.remove_replica(local[s], s, c)) {
-                        lr[s] = (int)lc.size();
-                        lc.push_back(c);
-                    }
-                }
-                if (lc.empty()) break;
-                std::vector<uint32_t> lp;
-                if (!P.evaluate(lc, lp)) return P.err;
-                for (uint32_t s = 0; s < P.S; ++s) {
-                    if (!searching[s]) continue;
-                    int pick = -1;
-                    if (li[s] >= 0 && lp[li[s]] <= P.slo) pick = li[s];
-                    if (lr[s] >= 0 && lp[lr[s]] <= P.slo && (pick < 0 || P.cost(lc[lr[s]]) < P.cost(lc[pick]))) pick = lr[s];
-                    if (pick < 0)
-                        searching[s] = 0;
+                auto at = [&](uint32_t k, uint32_t r) { return (size_t)idx_down[s] + (size_t)k * P.rmax + (r - 1); };
+                uint32_t k = 0, r = 1;
+                while (r <= P.rmax && p99[at(0, r)] > P.slo) ++r;
+                if (r > P.rmax) continue;
+                const bool removal_is_cheaper = P.price(s, (uint32_t)hw2[s]) > 0;
+                for (;;) {
+                    const bool inc_ok = k + 1 < nb && p99[at(k + 1, r)] <= P.slo;
+                    const bool rem_ok = r > 1 && p99[at(k, r - 1)] <= P.slo;
+                    if (rem_ok && (!inc_ok || removal_is_cheaper))
+                        --r;
+                    else if (inc_ok)
+                        ++k;
                     else
-                        local[s] = lc[pick];
+                        break;
                 }
+                local[s] = cands[at(k, r)];
+                alive[s] = 1;
             }
             // -- the cheapest feasible result, first in (model, action) order on ties
             const uint64_t cur = P.cost(cfg);
