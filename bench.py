@@ -25,6 +25,12 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 # passes profiled; an entry is removed when the kernel changes and put back after re-profiling.
 MEASURED_TRAFFIC_BYTES = {("W4", 65536): 1.5719e13}
 
+# The kernel is bound by vector-instruction issue, not by HBM, so the line also says how full the
+# VALU issue slots are: SQ_INSTS_VALU per launch from the same profile (same validity rule), against
+# 256 CUs x 4 SIMDs x 2.4 GHz / 4 cycles per wave64 instruction on a 16-lane SIMD.
+MEASURED_VALU_INSTS = {("W4", 65536): 5.2901e12}
+VALU_PEAK_GINST_S = 256 * 4 * 2.4 / 4.0  # 614.4 G wavefront instructions / s
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -147,6 +153,13 @@ def main():
     avg_launch_s = sim_ms * 1e-3 / launches
     achieved = alg_bytes_per_launch / avg_launch_s / 1e9
 
+    valu = None
+    insts = MEASURED_VALU_INSTS.get((args.workload, min(args.chunk, w.n_configs)))
+    if insts is not None and launches == args.steps:  # one launch per step, as profiled
+        g = insts / avg_launch_s / 1e9
+        valu = {"insts_per_launch": insts, "achieved": g, "peak": VALU_PEAK_GINST_S, "unit": "G wave64 VALU instructions/s",
+                "frac": g / VALU_PEAK_GINST_S}
+
     p99 = res["p99_us"].cpu().numpy().view(np.uint32)
     feasible = int((p99 <= w.slo_us).sum())
 
@@ -177,7 +190,7 @@ def main():
                    "feasible_configs": feasible},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, min(args.chunk, w.n_configs))),
-                     "kernel": "est_sim_kernel", "avg_launch_ms": avg_launch_s * 1e3},
+                     "kernel": "est_sim_kernel", "avg_launch_ms": avg_launch_s * 1e3, "valu_issue": valu},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
