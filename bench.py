@@ -8,6 +8,7 @@ with all inputs already resident in GPU memory.  Prints one JSON line.
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload W5]
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -47,6 +48,11 @@ def main():
                     help="instead of the sweep, time the greedy planner (estimator_plan) on the workload's pipeline, trace and SLO")
     ap.add_argument("--handoff", action="store_true",
                     help="instead of the sweep, time estimator_tuner_handoff (traffic envelope + per-model ratios) on the workload's trace")
+    ap.add_argument("--shared", action="store_true",
+                    help="instead of the hot path with every candidate simulated on its own: the same candidates through "
+                         "estimator_run_shared_dev, upstream stages shared with a base configuration (W4, W5)")
+    ap.add_argument("--shared-bases-per-call", type=int, default=0, help="bases per library call (0 = 4096 on W4, 384 on W5)")
+    ap.add_argument("--shared-configs", type=int, default=0, help="only the first this many candidates (0 = all)")
     ap.add_argument("--planner-queries", type=int, default=50000, help="trace prefix the planner works on")
     ap.add_argument("--planner-max-replicas", type=int, default=32)
     args = ap.parse_args()
@@ -64,6 +70,9 @@ def main():
     w = workloads.WORKLOADS[args.workload]()
     est = estimator.Estimator(w.parents, w.lat_us, w.cost_uusd_hr)
     cfg = estimator.pack_configs(w.cfg_hw, w.cfg_batch, w.cfg_replicas)
+    digest = lambda a: hashlib.sha256(np.ascontiguousarray(a).tobytes()).hexdigest()[:16]  # which inputs this line was measured on
+    input_sha256 = {"arrival_us": digest(w.arrival_us), "visit_mask": digest(w.visit_mask), "configs": digest(cfg),
+                    "lat_us": digest(w.lat_us), "cost_uusd_hr": digest(w.cost_uusd_hr)}
     arr_t = torch.from_numpy(w.arrival_us.view(np.int32)).to(dev)
     msk_t = torch.from_numpy(w.visit_mask.view(np.int32)).to(dev)
     cfg_t = torch.from_numpy(cfg.view(np.uint8).reshape(-1)).to(dev)
@@ -115,6 +124,59 @@ def main():
         return
 
     S = w.n_stages
+    if args.shared:
+        # The same candidates with shared upstream stages.  W5's candidates are 64-member neighbourhoods, the
+        # first member being the base; a grid (W4) is cut along its most downstream swept stage: the base of a
+        # candidate is the candidate with that stage at the grid's first value.
+        words = cfg.view(np.uint32).reshape(w.n_configs, S)
+        if args.workload == "W5":
+            base_rows, base_of = words[::64].copy(), (np.arange(w.n_configs) // 64).astype(np.int64)
+        else:
+            varies = [s_ for s_ in range(S) if (words[:, s_] != words[0, s_]).any()]
+            key = words.copy()
+            if varies:
+                key[:, max(varies)] = words[0, max(varies)]
+            base_rows, base_of = np.unique(key, axis=0, return_inverse=True)
+            base_of = base_of.reshape(-1)
+        C = args.shared_configs if args.shared_configs > 0 else w.n_configs
+        per_call = args.shared_bases_per_call or (384 if args.workload == "W5" else 4096)
+        order = np.argsort(base_of[:C], kind="stable")  # candidates grouped by base, results put back in place
+        p99 = np.zeros(C, np.uint32); miss = np.zeros(C, np.uint32)
+        sim_ms = cap_ms = 0.0; frac = []; calls = 0
+        used = np.unique(base_of[:C])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for lo in range(0, len(used), per_call):
+            bsel = used[lo:lo + per_call]
+            remap = np.full(len(base_rows), -1, np.int64); remap[bsel] = np.arange(len(bsel))
+            csel = order[np.isin(base_of[:C][order], bsel)]
+            b_t = torch.from_numpy(np.ascontiguousarray(base_rows[bsel]).view(np.uint8).reshape(-1)).to(dev)
+            c_t = torch.from_numpy(np.ascontiguousarray(words[csel]).view(np.uint8).reshape(-1)).to(dev)
+            o_t = torch.from_numpy(remap[base_of[:C][csel]].astype(np.int32)).to(dev)
+            r = est.run_shared_dev(arr_t, msk_t, b_t, len(bsel), c_t, o_t, len(csel), w.slo_us)
+            st = est.stats()
+            p99[csel] = r["p99_us"].cpu().numpy().view(np.uint32); miss[csel] = r["miss_count"].cpu().numpy().view(np.uint32)
+            sim_ms += st["sim_ms"]; cap_ms += st["capture_ms"]; frac.append(st["ops_run_fraction"] * len(csel)); calls += 1
+            print("[bench] shared: bases %d..%d of %d (%d candidates) done, kernels %.1f ms of which bases %.1f ms, scratch %.1f GB"
+                  % (lo, lo + len(bsel), len(used), len(csel), st["sim_ms"], st["capture_ms"], st["workspace_bytes"] / 1e9), file=sys.stderr, flush=True)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        # a seeded sample against the oracle, which simulates each candidate on its own
+        from oracle import oracle
+        n_sample = args.cpu_sample if args.cpu_sample >= 0 else 8
+        idx = np.sort(np.random.default_rng(7).choice(C, size=min(n_sample, C), replace=False))
+        ok = None
+        if len(idx):
+            ref = oracle.run(w.parents, w.lat_us, w.cost_uusd_hr, w.arrival_us, w.visit_mask, w.cfg_hw[idx], w.cfg_batch[idx], w.cfg_replicas[idx], w.slo_us)
+            ok = bool(np.array_equal(ref["p99_us"], p99[idx].astype(np.uint64)) and np.array_equal(ref["miss_count"], miss[idx].astype(np.uint64)))
+        print(json.dumps({"metric": "config*query simulations/s with shared upstream stages on 1 MI355X", "value": C * w.n_queries / (t1 - t0),
+                          "unit": "config*query simulations/s", "n_gpus": 1, "steps": 1, "warmup": 0, "ms_per_step": (t1 - t0) * 1e3,
+                          "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+                          "config": {"workload": args.workload, "n_configs": C, "n_queries": w.n_queries, "bases": int(len(used)), "library_calls": calls,
+                                     "kernel_ms": sim_ms, "kernel_ms_bases": cap_ms, "operations_run_fraction": float(sum(frac) / C),
+                                     "feasible_configs": int((p99 <= w.slo_us).sum()), "oracle_sample": int(len(idx)), "matches_oracle": ok}}))
+        return
+
     stats = {"sim_ms": 0.0, "launches": 0}
 
     def one_pass(tag, timed):
@@ -187,7 +249,7 @@ def main():
         "dtype": "u32", "data": "synthetic",
         "config": {"workload": args.workload, "n_configs": w.n_configs, "n_queries": w.n_queries, "n_stages": w.n_stages,
                    "stage_visits_per_config": visits, "scratch_slots": st["n_slots"], "candidates_per_call": min(args.chunk, w.n_configs),
-                   "feasible_configs": feasible},
+                   "feasible_configs": feasible, "input_sha256": input_sha256},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, min(args.chunk, w.n_configs))),
                      "kernel": "est_sim_kernel", "avg_launch_ms": avg_launch_s * 1e3, "valu_issue": valu},

@@ -95,6 +95,8 @@ typedef struct {
     float prep_ms;            /* trace / configuration preprocessing kernels                          */
     uint64_t stage_visits;    /* sum over stages of queries visiting the stage (per candidate)        */
     uint64_t workspace_bytes; /* device scratch used                                                  */
+    float capture_ms;         /* estimator_run_shared_dev: the launch that simulates the bases (part of sim_ms) */
+    float ops_run_fraction;   /* estimator_run_shared_dev: operations run / (candidates x operations); else 0    */
 } est_stats_t;
 
 /*
@@ -136,6 +138,26 @@ int estimator_run_dev(estimator_t *h, const est_trace_t *trace, const est_stage_
  */
 int estimator_run_latencies(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *configs,
                             uint64_t n_cfg, uint32_t *lat_us_out);
+
+/*
+ * estimator_run_dev for candidates that share upstream stages with a base configuration, as the
+ * candidates of one step of the planner's search do (Section 4.3: each action changes one model of the
+ * current configuration).  A stage's completions depend only on the configuration of the stage and of
+ * its ancestors in the pipeline, so for candidate i every stage that is configured, together with all
+ * its ancestors, as in bases[base_of[i]] is simulated once for that base instead of once per
+ * candidate.  Results are those of estimator_run_dev on configs, bit for bit; bases are not reported.
+ * bases is [n_bases][S], configs [n_cfg][S], base_of [n_cfg] with entries < n_bases: DEVICE
+ * pointers, like the trace arrays and the arrays of out.  A candidate may differ from its base in
+ * any number of stages (sharing shrinks accordingly); n_bases == 0 behaves as estimator_run_dev.
+ * The library allocates the scratch (cached in the handle like estimator_run_dev's; the streams shared
+ * by one base stay in memory for the whole call: 8 bytes x queries per shared stream).
+ * Errors as estimator_run_dev; EST_EINVAL for a base_of entry out of range; EST_ENOMEM when the
+ * bases' streams do not fit (pass fewer bases per call); EST_EUNSUPPORTED for pipelines whose run
+ * needs more than 64 operations or streams.
+ */
+int estimator_run_shared_dev(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *bases, uint64_t n_bases,
+                             const est_stage_cfg_t *configs, const uint32_t *base_of, uint64_t n_cfg, uint32_t slo_us,
+                             est_result_t *out, void *hip_stream);
 
 /* Device-pointer variant of estimator_run_latencies; lat_us_out is a device buffer [n_cfg][n]. */
 int estimator_run_latencies_dev(estimator_t *h, const est_trace_t *trace,

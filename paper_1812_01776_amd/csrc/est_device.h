@@ -58,6 +58,9 @@ struct Ctx {
     const EstStageCfg *cfg;
     uint64_t *lds;
     uint32_t t;  // candidate index
+    // streams taken from another candidate's captured run instead of this one's scratch (bit per ring)
+    uint64_t memo_rings;
+    const uint64_t *cap_rings;
 };
 
 struct View {
@@ -65,12 +68,19 @@ struct View {
     uint32_t mask, wr, fin;
 };
 
+template <bool MEMO>
 EST_DEV View view_of(const Ctx &c, int32_t ring) {
     View v;
     if (ring == EST_SRC_TRACE) {
         v.base = c.a->trace_keys;
         v.mask = 0xFFFFFFFFu;
         v.wr = c.a->n;
+        v.fin = 1;
+    } else if (MEMO && ((c.memo_rings >> ring) & 1ull)) {  // a whole stream somebody else produced; cursors were preset
+        const EstRing &R = c.a->cap_plan->rings[ring];
+        v.base = c.cap_rings + R.off;
+        v.mask = R.cap_mask;
+        v.wr = c.st[c.P->wr_off + ring];
         v.fin = 1;
     } else {
         const EstRing &R = c.P->rings[ring];
@@ -84,8 +94,9 @@ EST_DEV View view_of(const Ctx &c, int32_t ring) {
 
 // The same with the scalars marked as identical in every lane (they are: one address, one value), which
 // keeps everything computed from them in scalar registers.
+template <bool MEMO>
 EST_DEV View uniform_view_of(const Ctx &c, int32_t ring) {
-    View v = view_of(c, ring);
+    View v = view_of<MEMO>(c, ring);
     v.mask = wv::uniform(v.mask);
     v.wr = wv::uniform(v.wr);
     v.fin = wv::uniform(v.fin);
@@ -272,7 +283,7 @@ EST_DEV bool scan_emit(const EstOp &op, const uint32_t *lslots, uint64_t E, uint
     return true;
 }
 
-template <bool DIAG>
+template <bool DIAG, bool MEMO>
 EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     const uint32_t ln = wv::lane();
     const EstPlan &P = *c.P;
@@ -312,7 +323,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     }
     wv::sync();
 
-    View in = view_of(c, op.src_ring[0]);
+    View in = view_of<MEMO>(c, op.src_ring[0]);
     in.mask = wv::uniform(in.mask);
     in.wr = wv::uniform(in.wr);
     in.fin = wv::uniform(in.fin);
@@ -992,7 +1003,7 @@ EST_DEV uint64_t eff_key(uint64_t key, uint32_t j, uint32_t l) {
     return (uint32_t)(key >> 32) == 0xFFFFFFFFu ? (0xFFFFFFFF00000000ull | (uint64_t)(j << 8) | l) : key;
 }
 
-template <bool DIAG>
+template <bool DIAG, bool MEMO>
 EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     const uint32_t ln = wv::lane();
     const EstPlan &P = *c.P;
@@ -1027,7 +1038,7 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
 
     if (K == 1 && !op.has_cnt) {
         // one source, every query fed by it alone: filter and copy, window by window
-        const View sv = uniform_view_of(c, op.src_ring[0]);
+        const View sv = uniform_view_of<MEMO>(c, op.src_ring[0]);
         uint32_t rc = wv::uniform(raw[0]);
         for (;;) {
             if (!is_lat && space < 64u) break;  // wait for the consumer
@@ -1064,7 +1075,7 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         // ---- stage up to 64 accepted elements of every source
         uint32_t more = 0;  // bit j: elements beyond the staged ones may exist in source j
         for (uint32_t j = 0; j < K; ++j) {
-            const View sv = uniform_view_of(c, op.src_ring[j]);
+            const View sv = uniform_view_of<MEMO>(c, op.src_ring[j]);
             uint32_t n = 0, rc = wv::uniform(raw[j]);
             while (n < 64 && rc != sv.wr) {
                 const uint32_t w = umin(64u, sv.wr - rc);
@@ -1242,7 +1253,7 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
 // One wavefront = one candidate.  Every loop ends: an operation that consumes or emits nothing
 // reports no progress, and a full pass over the operations without progress stops the candidate with
 // an error flag.
-template <bool DIAG>
+template <bool DIAG, bool MEMO>
 EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *lds) {
     const uint32_t ln = wv::lane();
     const EstPlan &P = *a.plan;
@@ -1271,6 +1282,33 @@ EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *
         for (uint64_t i = ln; i < a.cnt_stride / 4; i += 64) cw[i] = 0;
     }
     wv::sync();
+    c.memo_rings = 0;
+    c.cap_rings = nullptr;
+    if (MEMO) {
+        // Operations this candidate does not run count as done.  In a replay the streams they would have
+        // produced are complete already in the captured run of the candidate's base: point the readers
+        // there and preset the write cursors to the captured lengths.
+        const uint64_t skip = a.skip_ops[t];
+        const bool replay = a.cap_rings != nullptr;
+        const uint32_t b = replay ? a.base_of[t] : 0u;
+        const uint32_t *cs = replay ? a.cap_state + (uint64_t)b * a.cap_state_stride : nullptr;
+        if (replay) c.cap_rings = a.cap_rings + (uint64_t)b * a.cap_ring_stride;
+        uint64_t mr = 0;
+        for (uint32_t opi = 0; opi < P.n_ops; ++opi) {
+            if (!((skip >> opi) & 1ull)) continue;
+            const int32_t r = P.ops[opi].out_ring;
+            if (ln == 0) c.st[P.done_off + opi] = 1;
+            if (replay && r >= 0) {
+                mr |= 1ull << r;
+                if (ln == 0) {
+                    c.st[P.wr_off + r] = cs[P.wr_off + r];
+                    c.st[P.fin_off + r] = 1;
+                }
+            }
+        }
+        c.memo_rings = mr;
+        wv::sync();
+    }
 
     for (;;) {
         bool progress = false, alldone = true;
@@ -1278,7 +1316,7 @@ EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *
             if (wv::uniform(c.st[P.done_off + opi])) continue;
             const EstOp &op = P.ops[opi];
             const uint64_t k0 = (DIAG && a.dbg_ticks) ? wv::ticks() : 0;
-            bool p = op.type == EST_OP_SCAN ? scan_run<DIAG>(c, op, opi) : merge_run<DIAG>(c, op, opi);
+            bool p = op.type == EST_OP_SCAN ? scan_run<DIAG, MEMO>(c, op, opi) : merge_run<DIAG, MEMO>(c, op, opi);
             if (DIAG && a.dbg_ticks && ln == 0) {
                 const uint32_t at = op.type == EST_OP_SCAN ? 8 + 3 * EST_MAX_STAGES + op.stage
                                                            : 8 + 4 * EST_MAX_STAGES + (op.type == EST_OP_LAT ? 1 : 0);
@@ -1356,15 +1394,17 @@ EST_DEV void select_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_
 // A wavefront takes candidates from the launch's work counter until none is left, simulating each
 // in its own scratch slot and, unless per-query latencies were asked for, selecting the P99 right
 // away from the slot's latency array.
-template <bool DIAG>
-EST_DEV void slot_loop(const EstSimArgs &a, uint32_t slot, uint64_t *lds) {
+template <bool DIAG, bool MEMO>
+EST_DEV void slot_loop(const EstSimArgs &a, uint32_t wave_slot, uint64_t *lds) {
     for (;;) {
         uint32_t t = 0;
         if (wv::lane() == 0) t = wv::fetch_add_u32(&a.status->next_cfg, 1u);
         t = wv::bcast(t, 0);
         if (t >= a.n_cfg) break;
+        if (MEMO && a.order) t = a.order[t];
+        const uint32_t slot = (MEMO && a.slot_by_cfg) ? t : wave_slot;
         const uint64_t t0 = (DIAG && a.dbg_ticks) ? wv::ticks() : 0;
-        if (a.n > 0) sim_wave<DIAG>(a, t, slot, lds);
+        if (a.n > 0) sim_wave<DIAG, MEMO>(a, t, slot, lds);
         wv::sync();
         const uint64_t k1 = (DIAG && a.dbg_ticks) ? wv::ticks() : 0;
         if (!a.lat_by_qid) select_wave(a, t, slot, lds);

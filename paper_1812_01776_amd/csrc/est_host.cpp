@@ -444,6 +444,287 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     return EST_OK;
 }
 
+// Candidates that share upstream stages with a base configuration (Section 4.3: the candidates of a
+// planner step differ from the current configuration in one model).  A stage's output depends only on
+// the configurations of the stage and of its ancestors, so for every candidate the operations whose
+// stage and ancestors are configured as in the candidate's base are not run: their output streams are
+// read from one captured run of the base.  Two launches: the bases, leaving the streams some candidate
+// will read in full-length buffers (and running only what those streams need); then the candidates.
+int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t *d_mask, const est_stage_cfg_t *d_bases,
+                    uint64_t n_bases, const est_stage_cfg_t *d_cfg, const uint32_t *d_base_of, uint64_t n_cfg, uint32_t slo_us,
+                    uint32_t *d_p99, uint32_t *d_miss, uint64_t *d_cost, void *stream) {
+    if (n >= (1ull << 31)) return fail(h, EST_EINVAL, "trace too long (%llu queries)", (unsigned long long)n);
+    if (n_cfg >= (1ull << 31) || n_bases >= (1ull << 31)) return fail(h, EST_EINVAL, "too many configurations");
+    if (n_cfg == 0) return EST_OK;
+    if (n == 0 || n_bases == 0)  // nothing to share
+        return run_core(h, n, d_arrival, d_mask, d_cfg, n_cfg, slo_us, MODE_P99, d_p99, d_miss, d_cost, nullptr, nullptr, 0, stream);
+    const uint32_t S = h->dag.S;
+    EventSet evs;
+    void *ev_p0 = evs.make(), *ev_p1 = evs.make(), *ev_p2 = evs.make(), *ev_p3 = evs.make();
+    void *e0 = evs.make(), *e1 = evs.make(), *e2 = evs.make();
+    if (!ev_p0 || !ev_p1 || !ev_p2 || !ev_p3 || !e0 || !e1 || !e2) return dev_fail(h, "event create");
+
+    // ---- scan the configurations (bases and candidates) and the trace
+    if (estbe::zero(h->d_status, sizeof(EstStatus), stream)) return dev_fail(h, "clear status");
+    estbe::event_record(ev_p0, stream);
+    EstCfgArgs ca;
+    ca.dag = h->d_dag;
+    ca.status = h->d_status;
+    ca.cfg = (const EstStageCfg *)d_bases;
+    ca.n_cfg = n_bases;
+    if (estbe::launch_cfg(ca, stream)) return dev_fail(h, "configuration scan");
+    ca.cfg = (const EstStageCfg *)d_cfg;
+    ca.n_cfg = n_cfg;
+    if (estbe::launch_cfg(ca, stream)) return dev_fail(h, "configuration scan");
+    EstPrepArgs pa;
+    memset(&pa, 0, sizeof pa);
+    pa.dag = h->d_dag;
+    pa.arrival = d_arrival;
+    pa.mask = d_mask;
+    pa.n = (uint32_t)n;
+    pa.status = h->d_status;
+    if (estbe::launch_prep1(pa, stream)) return dev_fail(h, "trace scan");
+    estbe::event_record(ev_p1, stream);
+    EstStatus st;
+    std::vector<est_stage_cfg_t> cfg(n_cfg * S), bases(n_bases * S);
+    std::vector<uint32_t> base_of(n_cfg);
+    if (estbe::d2h(&st, h->d_status, sizeof st, stream) || estbe::d2h(cfg.data(), d_cfg, cfg.size() * sizeof(est_stage_cfg_t), stream) ||
+        estbe::d2h(bases.data(), d_bases, bases.size() * sizeof(est_stage_cfg_t), stream) ||
+        estbe::d2h(base_of.data(), d_base_of, n_cfg * 4, stream) || estbe::sync(stream))
+        return dev_fail(h, "read status and configurations");
+    if (st.bad_cfg) return fail(h, EST_EINVAL, "a configuration entry is out of range (hw < %u, 1 <= batch <= %u, 1 <= replicas <= %d)",
+                                h->dag.H, h->dag.Bmax, EST_MAX_REPLICAS);
+    if (st.bad_trace) return fail(h, EST_EINVAL, "arrival times decrease");
+    if ((uint64_t)st.last_arrival + h->sum_max_lat + slo_us >= EST_HORIZON_US)
+        return fail(h, EST_EINVAL, "trace too close to the horizon: last arrival %u + worst service %llu + slo %u >= 2^32-1",
+                    st.last_arrival, (unsigned long long)h->sum_max_lat, slo_us);
+    for (uint64_t t = 0; t < n_cfg; ++t)
+        if (base_of[t] >= n_bases) return fail(h, EST_EINVAL, "base_of[%llu] = %u is not a base (%llu bases)", (unsigned long long)t, base_of[t], (unsigned long long)n_bases);
+    st.n_visit[S] = (uint32_t)n;
+
+    PlanOut po;
+    po.sz = Sizes();
+    po.n_acc = 0;
+    int rc = build_plan(h, st, n, po);
+    if (rc != EST_OK) return rc;
+    const EstPlan &P = po.plan;
+    if (P.n_ops > 64 || P.n_rings > 64) return fail(h, EST_EUNSUPPORTED, "shared runs handle at most 64 operations and 64 streams");
+
+    // ---- which operations each candidate skips, which streams must be captured, what the capture has to run
+    std::vector<int32_t> producer(P.n_rings, -1);
+    for (uint32_t i = 0; i < P.n_ops; ++i)
+        if (P.ops[i].out_ring >= 0) producer[P.ops[i].out_ring] = (int32_t)i;
+    std::vector<uint64_t> skip(n_cfg);
+    uint64_t captured_rings = 0;
+    for (uint64_t t = 0; t < n_cfg; ++t) {
+        const est_stage_cfg_t *c = &cfg[t * S], *b = &bases[(uint64_t)base_of[t] * S];
+        uint64_t same = 0;  // operations whose output equals the base's
+        for (uint32_t i = 0; i < P.n_ops; ++i) {
+            const EstOp &op = P.ops[i];
+            if (op.type == EST_OP_LAT) continue;
+            bool eq = true;
+            for (uint32_t j = 0; j < op.n_src; ++j)
+                if (op.src_ring[j] >= 0 && !((same >> producer[op.src_ring[j]]) & 1ull)) eq = false;
+            if (op.type == EST_OP_SCAN && memcmp(&c[op.stage], &b[op.stage], sizeof(est_stage_cfg_t)) != 0) eq = false;
+            if (eq) same |= 1ull << i;
+        }
+        skip[t] = same;
+        for (uint32_t i = 0; i < P.n_ops; ++i) {  // streams a skipped operation hands to one that runs
+            if ((same >> i) & 1ull) continue;
+            const EstOp &op = P.ops[i];
+            for (uint32_t j = 0; j < op.n_src; ++j)
+                if (op.src_ring[j] >= 0 && ((same >> producer[op.src_ring[j]]) & 1ull)) captured_rings |= 1ull << op.src_ring[j];
+        }
+    }
+    uint64_t needed = 0;  // the producers of the captured streams and everything upstream of them
+    for (int32_t i = (int32_t)P.n_ops - 1; i >= 0; --i) {
+        const EstOp &op = P.ops[i];
+        if (op.out_ring >= 0 && ((captured_rings >> op.out_ring) & 1ull)) needed |= 1ull << i;
+        if ((needed >> i) & 1ull)
+            for (uint32_t j = 0; j < op.n_src; ++j)
+                if (op.src_ring[j] >= 0) needed |= 1ull << producer[op.src_ring[j]];
+    }
+    const uint64_t all_ops = P.n_ops == 64 ? ~0ull : ((1ull << P.n_ops) - 1ull);
+    const std::vector<uint64_t> skip_cap(n_bases, all_ops & ~needed);
+
+    // candidates that run the most operations are handed out first, so that the launch ends on short ones
+    std::vector<uint32_t> order(n_cfg);
+    for (uint64_t t = 0; t < n_cfg; ++t) order[t] = (uint32_t)t;
+    std::stable_sort(order.begin(), order.end(),
+                     [&](uint32_t x, uint32_t y) { return __builtin_popcountll(skip[x]) < __builtin_popcountll(skip[y]); });
+
+    // the capture's layout: the same operations and streams; captured streams, and streams one of whose
+    // readers the capture does not run, with room for every element
+    // (nobody consumes during the capture, and a producer only writes while it sees the free room a
+    // bounded ring offers when its reader has caught up: so that much room on top of the stream itself)
+    EstPlan PC = P;
+    uint64_t cap_elems = 0, room = ~0ull;
+    for (uint32_t r = 0; r < P.n_rings; ++r) room = std::min<uint64_t>(room, (uint64_t)P.rings[r].cap_mask + 1);
+    for (uint32_t r = 0; r < P.n_rings; ++r) {
+        uint64_t cap = (uint64_t)P.rings[r].cap_mask + 1;
+        bool idle_reader = false;  // a reader the capture does not run never frees anything
+        for (uint32_t i = 0; i < P.n_ops; ++i)
+            for (uint32_t j = 0; j < P.ops[i].n_src; ++j)
+                if (P.ops[i].src_ring[j] == (int32_t)r && !((needed >> i) & 1ull)) idle_reader = true;
+        if (((captured_rings >> r) & 1ull) || (idle_reader && ((needed >> producer[r]) & 1ull)))
+            cap = std::max<uint64_t>(cap, pow2ceil(st.n_visit[P.ops[producer[r]].stage] + room));
+        PC.rings[r].off = cap_elems;
+        PC.rings[r].cap_mask = (uint32_t)(cap - 1);
+        cap_elems += cap;
+    }
+
+    // ---- lay out the scratch (in the handle's cached workspace, grown when it is too small)
+    const uint64_t n_pad = align_up(std::max<uint64_t>(n, 1), 256);
+    uint64_t at = 0;
+    auto take = [&](uint64_t bytes) {
+        uint64_t a0 = at;
+        at = align_up(at + bytes, 256);
+        return a0;
+    };
+    const uint64_t o_keys = take(n_pad * 8);
+    const uint64_t o_acc = take((uint64_t)std::max<uint32_t>(po.n_acc, 1) * n_pad);
+    const uint64_t o_p99 = take(n_cfg * 4), o_miss = take(n_cfg * 4), o_cost = take(n_cfg * 8);
+    const uint64_t o_skip = take(n_cfg * 8), o_skip_cap = take(n_bases * 8), o_order = take(n_cfg * 4);
+    const uint64_t o_res_cap = take(n_bases * 8);  // results of the capture launch (only its cost is written; unused)
+    const uint64_t o_plan_cap = take(sizeof(EstPlan));
+    const uint64_t o_cstate = take(n_bases * po.sz.state_words * 4);
+    const uint64_t o_crings = take(n_bases * cap_elems * 8);
+    const uint64_t o_crep = take(n_bases * po.sz.rep_words * 4);
+    const uint64_t o_cslots = take(n_bases * po.sz.slot_words * 4);
+    const uint64_t o_ccnt = take(n_bases * po.sz.cnt_bytes);
+    const uint64_t fixed = at;
+    const uint64_t per_cfg = po.sz.per_cfg_bytes(n, true) + 64;
+    const uint32_t resident = std::max<uint32_t>(estbe::max_resident_waves(po.lds_bytes), 1);
+    const uint64_t avail = ((uint64_t)estbe::mem_free() + h->ws_bytes) / 100 * 85;
+    if (fixed + per_cfg * std::min<uint64_t>(n_cfg, 256) + 8 * 256 > avail)
+        return fail(h, EST_ENOMEM, "%llu bases need %llu bytes of captured streams and %llu are free: pass fewer bases per call",
+                    (unsigned long long)n_bases, (unsigned long long)fixed, (unsigned long long)avail);
+    uint64_t n_slots = std::min<uint64_t>({n_cfg, (uint64_t)resident, (avail - fixed - 8 * 256) / per_cfg});
+    auto area = [&](uint64_t bytes_per_cfg) {
+        uint64_t a0 = at;
+        at = align_up(at + bytes_per_cfg * n_slots, 256);
+        return a0;
+    };
+    const uint64_t o_state = area(po.sz.state_words * 4);
+    const uint64_t o_rings = area(po.sz.ring_elems * 8);
+    const uint64_t o_rep = area(po.sz.rep_words * 4);
+    const uint64_t o_slots = area(po.sz.slot_words * 4);
+    const uint64_t o_cnt = area(po.sz.cnt_bytes);
+    const uint64_t o_lat = area(n * 4);
+    if (h->ws_bytes < at) {
+        if (h->ws) estbe::dfree(h->ws);
+        h->ws = nullptr;
+        h->ws_bytes = 0;
+        h->ws = estbe::dmalloc(at);
+        if (!h->ws) return fail(h, EST_ENOMEM, "cannot allocate %llu bytes of device scratch", (unsigned long long)at);
+        h->ws_bytes = at;
+    }
+    uint8_t *ws = (uint8_t *)h->ws;
+
+    // ---- per-query tables, plans, masks
+    estbe::event_record(ev_p2, stream);
+    if (estbe::h2d(h->d_plan, &po.plan, sizeof(EstPlan), stream) || estbe::h2d(ws + o_plan_cap, &PC, sizeof(EstPlan), stream) ||
+        estbe::h2d(ws + o_skip, skip.data(), n_cfg * 8, stream) || estbe::h2d(ws + o_order, order.data(), n_cfg * 4, stream) || estbe::h2d(ws + o_skip_cap, skip_cap.data(), n_bases * 8, stream))
+        return dev_fail(h, "upload plan");
+    pa.trace_keys = (uint64_t *)(ws + o_keys);
+    pa.acc = ws + o_acc;
+    pa.acc_stride = n_pad;
+    pa.n_acc = po.n_acc;
+    memcpy(pa.acc_stage, po.acc_stage, sizeof(uint32_t) * po.n_acc);
+    memcpy(pa.acc_slot_of_src, po.acc_slot_of_src, sizeof pa.acc_slot_of_src);
+    if (estbe::launch_prep2(pa, stream)) return dev_fail(h, "trace tables");
+    estbe::event_record(ev_p3, stream);
+
+    EstSimArgs sa;
+    memset(&sa, 0, sizeof sa);
+    sa.dag = h->d_dag;
+    sa.lat_us = h->d_lat;
+    sa.cost_uusd_hr = h->d_cost;
+    sa.arrival = d_arrival;
+    sa.trace_keys = (const uint64_t *)(ws + o_keys);
+    sa.acc = ws + o_acc;
+    sa.acc_stride = n_pad;
+    sa.n = (uint32_t)n;
+    sa.slo_us = slo_us;
+    sa.max_src = po.plan.max_src;
+    sa.lds_bytes = po.lds_bytes;
+    sa.status = h->d_status;
+
+    // ---- launch 1: the bases, candidate t in slot t, streams left in place
+    estbe::event_record(e0, stream);
+    const bool capture = needed != 0;
+    if (capture) {
+        EstSimArgs ca2 = sa;
+        ca2.plan = (const EstPlan *)(ws + o_plan_cap);
+        ca2.cfg = (const EstStageCfg *)d_bases;
+        ca2.n_cfg = (uint32_t)n_bases;
+        ca2.n_slots = (uint32_t)std::min<uint64_t>(n_bases, resident);
+        ca2.have_lat = 0;
+        ca2.state = (uint32_t *)(ws + o_cstate);  ca2.state_stride = po.sz.state_words;
+        ca2.rings = (uint64_t *)(ws + o_crings);  ca2.ring_stride = cap_elems;
+        ca2.rep = (uint32_t *)(ws + o_crep);      ca2.rep_stride = po.sz.rep_words;
+        ca2.slots = (uint32_t *)(ws + o_cslots);  ca2.slot_stride = po.sz.slot_words;
+        ca2.counters = ws + o_ccnt;               ca2.cnt_stride = po.sz.cnt_bytes;
+        ca2.lat = nullptr;
+        ca2.p99 = (uint32_t *)(ws + o_res_cap); ca2.miss = (uint32_t *)(ws + o_res_cap); ca2.cost = (uint64_t *)(ws + o_res_cap);
+        ca2.skip_ops = (const uint64_t *)(ws + o_skip_cap);
+        ca2.slot_by_cfg = 1;
+        if (estbe::launch_sim(ca2, stream)) return dev_fail(h, "simulation kernel (bases)");
+        if (estbe::zero(&h->d_status->next_cfg, 4, stream)) return dev_fail(h, "reset the work counter");
+    }
+    estbe::event_record(e1, stream);
+
+    // ---- launch 2: the candidates
+    {
+        EstSimArgs cb = sa;
+        cb.plan = h->d_plan;
+        cb.cfg = (const EstStageCfg *)d_cfg;
+        cb.n_cfg = (uint32_t)n_cfg;
+        cb.n_slots = (uint32_t)n_slots;
+        cb.have_lat = 1;
+        cb.state = (uint32_t *)(ws + o_state);  cb.state_stride = po.sz.state_words;
+        cb.rings = (uint64_t *)(ws + o_rings);  cb.ring_stride = po.sz.ring_elems;
+        cb.rep = (uint32_t *)(ws + o_rep);      cb.rep_stride = po.sz.rep_words;
+        cb.slots = (uint32_t *)(ws + o_slots);  cb.slot_stride = po.sz.slot_words;
+        cb.counters = ws + o_cnt;               cb.cnt_stride = po.sz.cnt_bytes;
+        cb.lat = (uint32_t *)(ws + o_lat);      cb.lat_stride = n;
+        cb.p99 = (uint32_t *)(ws + o_p99); cb.miss = (uint32_t *)(ws + o_miss); cb.cost = (uint64_t *)(ws + o_cost);
+        cb.skip_ops = (const uint64_t *)(ws + o_skip);
+        cb.base_of = d_base_of;
+        cb.order = (const uint32_t *)(ws + o_order);
+        cb.cap_plan = (const EstPlan *)(ws + o_plan_cap);
+        if (capture) {
+            cb.cap_rings = (const uint64_t *)(ws + o_crings);  cb.cap_ring_stride = cap_elems;
+            cb.cap_state = (const uint32_t *)(ws + o_cstate);  cb.cap_state_stride = po.sz.state_words;
+        }
+        if (estbe::launch_sim(cb, stream)) return dev_fail(h, "simulation kernel");
+    }
+    estbe::event_record(e2, stream);
+    EstStatus st2;
+    if (estbe::d2h(&st2, h->d_status, sizeof st2, stream) || estbe::sync(stream)) return dev_fail(h, "run");
+    if (st2.sim_error) return fail(h, EST_EINTERNAL, "the simulation kernel stopped without finishing a candidate");
+    if (estbe::d2d(d_p99, ws + o_p99, n_cfg * 4, stream) || estbe::d2d(d_miss, ws + o_miss, n_cfg * 4, stream) ||
+        estbe::d2d(d_cost, ws + o_cost, n_cfg * 8, stream) || estbe::sync(stream))
+        return dev_fail(h, "copy results");
+    est_stats_t &ss = h->stats;
+    memset(&ss, 0, sizeof ss);
+    ss.n_launches = capture ? 2 : 1;
+    ss.n_slots = (uint32_t)n_slots;
+    ss.capture_ms = estbe::event_ms(e0, e1);
+    ss.sim_ms = estbe::event_ms(e0, e2);
+    ss.prep_ms = estbe::event_ms(ev_p0, ev_p1) + estbe::event_ms(ev_p2, ev_p3);
+    for (uint32_t s = 0; s < S; ++s) ss.stage_visits += st.n_visit[s];
+    ss.workspace_bytes = at;
+    // operations actually run, in units of one candidate's whole operation list (1.0 = nothing shared)
+    {
+        double ran = (double)n_bases * __builtin_popcountll(needed);
+        for (uint64_t t = 0; t < n_cfg; ++t) ran += P.n_ops - __builtin_popcountll(skip[t]);
+        ss.ops_run_fraction = (float)(ran / ((double)n_cfg * P.n_ops));
+    }
+    h->have_stats = true;
+    return EST_OK;
+}
+
 int check_run_args(estimator *h, const est_trace_t *trace, const est_stage_cfg_t *configs, uint64_t n_cfg) {
     if (!h) return EST_EINVAL;
     h->err.clear();
@@ -539,6 +820,23 @@ int estimator_run_dev(estimator_t *h, const est_trace_t *trace, const est_stage_
     try {
         return run_core(h, trace->n, trace->arrival_us, trace->visit_mask, configs, n_cfg, slo_us, MODE_P99, out ? out->p99_us : nullptr,
                         out ? out->miss_count : nullptr, out ? out->cost_uusd_hr : nullptr, nullptr, workspace, workspace_bytes, hip_stream);
+    } catch (const std::bad_alloc &) {
+        return fail(h, EST_ENOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(h, EST_EINTERNAL, "unexpected exception");
+    }
+}
+
+int estimator_run_shared_dev(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *bases, uint64_t n_bases,
+                             const est_stage_cfg_t *configs, const uint32_t *base_of, uint64_t n_cfg, uint32_t slo_us,
+                             est_result_t *out, void *hip_stream) {
+    int rc = check_run_args(h, trace, configs, n_cfg);
+    if (rc != EST_OK) return rc;
+    if (n_cfg > 0 && (!out || !out->p99_us || !out->miss_count || !out->cost_uusd_hr)) return fail(h, EST_EINVAL, "result arrays are NULL");
+    if (n_cfg > 0 && n_bases > 0 && (!bases || !base_of)) return fail(h, EST_EINVAL, "bases or base_of is NULL");
+    try {
+        return run_shared_core(h, trace->n, trace->arrival_us, trace->visit_mask, bases, n_bases, configs, base_of, n_cfg, slo_us,
+                               out ? out->p99_us : nullptr, out ? out->miss_count : nullptr, out ? out->cost_uusd_hr : nullptr, hip_stream);
     } catch (const std::bad_alloc &) {
         return fail(h, EST_ENOMEM, "host allocation failed");
     } catch (...) {

@@ -23,13 +23,13 @@ int check(hipError_t e, const char *what) {
 // pinned at 128 per lane (four wavefronts per SIMD): one register more would cost a quarter of the
 // resident wavefronts, which costs more than the few spills this forces.
 #define EST_WAVES_PER_BLOCK 4
-template <bool DIAG, int WAVES_PER_SIMD>
+template <bool DIAG, int WAVES_PER_SIMD, bool MEMO = false>
 __global__ __launch_bounds__(64 * EST_WAVES_PER_BLOCK) __attribute__((amdgpu_waves_per_eu(WAVES_PER_SIMD, WAVES_PER_SIMD)))
 void est_sim_kernel(EstSimArgs a) {
     extern __shared__ uint64_t lds[];  // EST_WAVES_PER_BLOCK x a.lds_bytes
     const uint32_t wave = threadIdx.x >> 6;
     const uint32_t slot = blockIdx.x * EST_WAVES_PER_BLOCK + wave;
-    if (slot < a.n_slots) estdev::slot_loop<DIAG>(a, slot, lds + (size_t)wave * (a.lds_bytes / 8));
+    if (slot < a.n_slots) estdev::slot_loop<DIAG, MEMO>(a, slot, lds + (size_t)wave * (a.lds_bytes / 8));
 }
 
 // The kernel is built for four wavefronts per SIMD (128 registers per lane) and for five (96 registers, a
@@ -148,7 +148,12 @@ int launch_sim(const EstSimArgs &a, void *stream) {
     // (the variant that keeps diagnostic counters is launched only when they are asked for)
     const size_t lds = (size_t)a.lds_bytes * EST_WAVES_PER_BLOCK;
     const dim3 grid(blocks), block(64 * EST_WAVES_PER_BLOCK);
-    if (a.dbg_ticks)
+    if (a.skip_ops) {  // candidates that skip operations (shared upstream stages): the variant that reads the extra arguments
+        if (five_fit(a.lds_bytes))
+            est_sim_kernel<false, 5, true><<<grid, block, lds, (hipStream_t)stream>>>(a);
+        else
+            est_sim_kernel<false, 4, true><<<grid, block, lds, (hipStream_t)stream>>>(a);
+    } else if (a.dbg_ticks)
         est_sim_kernel<true, 4><<<grid, block, lds, (hipStream_t)stream>>>(a);
     else if (five_fit(a.lds_bytes))
         est_sim_kernel<false, 5><<<grid, block, lds, (hipStream_t)stream>>>(a);

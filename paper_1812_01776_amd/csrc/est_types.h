@@ -113,6 +113,17 @@ struct EstSimArgs {
     EstStatus *status;
     uint64_t *dbg_ticks;           // optional [n_cfg]: 100 MHz ticks each candidate took (diagnostics)
     uint32_t *p99; uint32_t *miss; uint64_t *cost;   // [n_cfg] results
+    // Shared upstream stages (Section 4.3: the candidates of one planner step differ from a common base
+    // in one model, so everything upstream of the change is simulated once).  Only read by the kernel
+    // variant launched when skip_ops is set.
+    const uint64_t *skip_ops;      // [n_cfg]: bit i = operation i is not run for this candidate
+    const uint32_t *base_of;       // [n_cfg]: whose captured streams stand in for the skipped producers (replay only)
+    const EstPlan *cap_plan;       // layout of one captured candidate's streams
+    const uint64_t *cap_rings;  uint64_t cap_ring_stride;    // elements; null = nothing is replayed (a capture launch)
+    const uint32_t *cap_state;  uint64_t cap_state_stride;   // words
+    uint32_t slot_by_cfg;          // 1: candidate t works in scratch slot t and its streams stay there (capture)
+    uint32_t pad3;
+    const uint32_t *order;         // optional [n_cfg]: the k-th candidate handed out is order[k] (longest first)
 };
 
 struct EstPrepArgs {

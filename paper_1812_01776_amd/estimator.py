@@ -19,7 +19,8 @@ CFG_DTYPE = np.dtype([("hw", "u1"), ("batch", "u1"), ("replicas", "<u2")])
 
 SYMBOLS = ["estimator_create", "estimator_run", "estimator_run_dev", "estimator_run_latencies",
            "estimator_run_latencies_dev", "estimator_workspace_bytes", "estimator_last_stats",
-           "estimator_last_error", "estimator_destroy", "estimator_plan", "estimator_tuner_handoff"]
+           "estimator_last_error", "estimator_destroy", "estimator_plan", "estimator_tuner_handoff",
+           "estimator_run_shared_dev"]
 
 
 class EstimatorError(RuntimeError):
@@ -66,7 +67,8 @@ PLAN_ACTIONS = ("init", "batch", "replica", "hw")
 
 class Stats(ctypes.Structure):
     _fields_ = [("n_launches", ctypes.c_uint32), ("n_slots", ctypes.c_uint32), ("sim_ms", ctypes.c_float),
-                ("prep_ms", ctypes.c_float), ("stage_visits", ctypes.c_uint64), ("workspace_bytes", ctypes.c_uint64)]
+                ("prep_ms", ctypes.c_float), ("stage_visits", ctypes.c_uint64), ("workspace_bytes", ctypes.c_uint64),
+                ("capture_ms", ctypes.c_float), ("ops_run_fraction", ctypes.c_float)]
 
 
 def load_library(path=LIB_PATH):
@@ -90,6 +92,7 @@ def load_library(path=LIB_PATH):
     lib.estimator_destroy.restype = None
     lib.estimator_plan.restype = ctypes.c_int
     lib.estimator_tuner_handoff.restype = ctypes.c_int
+    lib.estimator_run_shared_dev.restype = ctypes.c_int
     return lib
 
 
@@ -223,6 +226,24 @@ class Estimator:
         self._check(self._lib.estimator_run_dev(self._h, ctypes.byref(tr), ctypes.c_void_p(cfg_t.data_ptr()),
                                                 ctypes.c_uint64(n_cfg), ctypes.c_uint32(slo_us), ctypes.byref(res), ws_ptr,
                                                 ctypes.c_uint64(ws_len), ctypes.c_void_p(st.cuda_stream)))
+        return {"p99_us": p99[:n_cfg], "miss_count": miss[:n_cfg], "cost_uusd_hr": cost[:n_cfg]}
+
+    def run_shared_dev(self, arrival_t, mask_t, bases_t, n_bases, cfg_t, base_of_t, n_cfg, slo_us, stream=None):
+        """run_dev for candidates that share upstream stages with bases: bases_t like cfg_t
+        (n_bases*S*4 bytes), base_of_t an int32 CUDA tensor [n_cfg] of base indices.  Same results."""
+        import torch
+        dev = arrival_t.device
+        n = arrival_t.numel()
+        p99 = torch.empty(max(n_cfg, 1), dtype=torch.int32, device=dev)
+        miss = torch.empty(max(n_cfg, 1), dtype=torch.int32, device=dev)
+        cost = torch.empty(max(n_cfg, 1), dtype=torch.int64, device=dev)
+        tr = _Trace(n, ctypes.c_void_p(arrival_t.data_ptr()), ctypes.c_void_p(mask_t.data_ptr()))
+        res = _Result(ctypes.c_void_p(p99.data_ptr()), ctypes.c_void_p(miss.data_ptr()), ctypes.c_void_p(cost.data_ptr()))
+        st = stream if stream is not None else torch.cuda.current_stream(dev)
+        self._check(self._lib.estimator_run_shared_dev(
+            self._h, ctypes.byref(tr), ctypes.c_void_p(bases_t.data_ptr()), ctypes.c_uint64(n_bases),
+            ctypes.c_void_p(cfg_t.data_ptr()), ctypes.c_void_p(base_of_t.data_ptr()), ctypes.c_uint64(n_cfg),
+            ctypes.c_uint32(slo_us), ctypes.byref(res), ctypes.c_void_p(st.cuda_stream)))
         return {"p99_us": p99[:n_cfg], "miss_count": miss[:n_cfg], "cost_uusd_hr": cost[:n_cfg]}
 
     def run_latencies_dev(self, arrival_t, mask_t, cfg_t, n_cfg, workspace_t=None, stream=None):

@@ -322,6 +322,31 @@ def random_case(seed, S=None, n=None, C=None, max_b=8, max_r=4, H=2, small_times
     return Workload("rand%d" % seed, parents, lat, cost, arr, mask, hw, bt, rp, slo)
 
 
+def neighbourhood_case(seed, n=None, n_bases=None, per_base=None, **kw):
+    """random_case whose candidates are neighbours of a few base configurations (the call pattern of
+    the planner's search, Section 4.3): each candidate copies its base and re-draws 0, 1 or 2 stages.
+    Returns the workload plus (base hw, batch, replicas arrays [n_bases][S], base_of [C])."""
+    rng = np.random.default_rng(10_000 + seed)
+    nb = int(rng.integers(1, 4)) if n_bases is None else n_bases
+    pb = int(rng.integers(2, 9)) if per_base is None else per_base
+    w = random_case(seed, n=n, C=nb, **kw)
+    S, H, Bmax = w.lat_us.shape
+    max_r = kw.get("max_r", 4)
+    b_hw, b_bt, b_rp = w.cfg_hw.copy(), w.cfg_batch.copy(), w.cfg_replicas.copy()
+    hw, bt, rp, base_of = [], [], [], []
+    for b in range(nb):
+        for _ in range(pb):
+            h, t, r = b_hw[b].copy(), b_bt[b].copy(), b_rp[b].copy()
+            for s in rng.choice(S, size=min(S, int(rng.integers(0, 3))), replace=False):
+                h[s] = rng.integers(0, H); t[s] = rng.integers(1, Bmax + 1); r[s] = rng.integers(1, max_r + 1)
+            hw.append(h); bt.append(t); rp.append(r); base_of.append(b)
+    order = rng.permutation(len(base_of))  # candidates of one base need not be adjacent
+    w.cfg_hw = np.array(hw, np.uint8)[order]
+    w.cfg_batch = np.array(bt, np.uint8)[order]
+    w.cfg_replicas = np.array(rp, np.uint16)[order]
+    return w, (b_hw, b_bt, b_rp), np.array(base_of, np.uint32)[order]
+
+
 def backlog_case(seed):
     """A small overloaded pipeline: service times far above the arrival gaps, so queues stay long,
     batches run full and replicas rotate.  Every fourth seed quantises all times (replicas fall

@@ -126,7 +126,14 @@ int launch_sim(const EstSimArgs &a, void *) {
             st->next_cfg = t;
             b.n_cfg = t + 1;  // this slot stops after candidate t
             memset(lds, 0x5A, sizeof lds);
-            emu::run_wave([&] { if (b.dbg_ticks) estdev::slot_loop<true>(b, slot, lds); else estdev::slot_loop<false>(b, slot, lds); });
+            emu::run_wave([&] {
+                if (b.skip_ops)
+                    estdev::slot_loop<false, true>(b, slot, lds);
+                else if (b.dbg_ticks)
+                    estdev::slot_loop<true, false>(b, slot, lds);
+                else
+                    estdev::slot_loop<false, false>(b, slot, lds);
+            });
         }
     }
     return 0;

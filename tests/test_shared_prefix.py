@@ -1,0 +1,95 @@
+"""Candidates that share upstream stages with a base (estimator_run_shared_dev): the results must be
+those of simulating every candidate on its own, so the reference is the CPU oracle run on the
+candidates alone -- it never sees bases or sharing.  Host logic (which operations a candidate skips,
+which streams are kept) runs here through the wavefront emulation; the GPU tests run the kernels.
+"""
+import types
+
+import numpy as np
+import pytest
+
+import emu_lib
+from oracle import oracle
+from paper_1812_01776_amd import estimator as binding
+from paper_1812_01776_amd import workloads
+
+
+def _oracle(w):
+    return oracle.run(w.parents, w.lat_us, w.cost_uusd_hr, w.arrival_us, w.visit_mask, w.cfg_hw, w.cfg_batch, w.cfg_replicas, w.slo_us)
+
+
+def _run_shared(est, w, bases, base_of, device):
+    import torch
+    cfg = binding.pack_configs(w.cfg_hw, w.cfg_batch, w.cfg_replicas)
+    bcfg = binding.pack_configs(*bases)
+    t = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a).view(dt).reshape(-1).copy()).to(device)
+    stream = None if device != "cpu" else types.SimpleNamespace(cuda_stream=0)  # the emulation's "device" memory is host memory
+    res = est.run_shared_dev(t(w.arrival_us, np.int32), t(w.visit_mask, np.int32), t(bcfg, np.uint8), bcfg.shape[0], t(cfg, np.uint8),
+                             t(base_of, np.int32), cfg.shape[0], w.slo_us, stream=stream)
+    return {k: v.cpu().numpy() for k, v in res.items()}, est.stats()
+
+
+def _check(est, w, bases, base_of, device):
+    got, stats = _run_shared(est, w, bases, base_of, device)
+    ref = _oracle(w)
+    assert np.array_equal(got["p99_us"].view(np.uint32).astype(np.uint64), ref["p99_us"])
+    assert np.array_equal(got["miss_count"].view(np.uint32).astype(np.uint64), ref["miss_count"])
+    assert np.array_equal(got["cost_uusd_hr"].view(np.uint64), ref["cost_uusd_hr"])
+    return stats
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_shared_run_equals_independent_simulation_emulated(seed):
+    kw = [dict(), dict(dag="linear"), dict(small_times=True), dict(tie_heavy=True)][seed % 4]
+    w, bases, base_of = workloads.neighbourhood_case(seed, **kw)
+    _check(emu_lib.make(w), w, bases, base_of, "cpu")
+
+
+def test_sharing_skips_work_and_identical_candidates_skip_everything_but_the_sink():
+    w, bases, base_of = workloads.neighbourhood_case(3, n=120, n_bases=2, per_base=6, S=5, dag="linear")
+    # every candidate equal to its base: only the latency sink runs per candidate
+    w.cfg_hw = bases[0][base_of]; w.cfg_batch = bases[1][base_of]; w.cfg_replicas = bases[2][base_of]
+    stats = _check(emu_lib.make(w), w, bases, base_of, "cpu")
+    assert stats["n_launches"] == 2 and 0 < stats["ops_run_fraction"] < 0.5
+    # every candidate differs from its base in the first stage: nothing can be shared, one launch
+    w.cfg_replicas = w.cfg_replicas.copy(); w.cfg_replicas[:, 0] = bases[2][base_of][:, 0] % 4 + 1
+    stats = _check(emu_lib.make(w), w, bases, base_of, "cpu")
+    assert stats["n_launches"] == 1 and stats["ops_run_fraction"] == 1.0
+
+
+def test_shared_run_rejects_bad_base_index():
+    w, bases, base_of = workloads.neighbourhood_case(5, n=40)
+    bad = base_of.copy(); bad[0] = 99
+    with pytest.raises(binding.EstimatorError) as ei:
+        _run_shared(emu_lib.make(w), w, bases, bad, "cpu")
+    assert ei.value.code == binding.EST_EINVAL
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("seed", range(40))
+def test_shared_run_equals_independent_simulation(seed):
+    kw = [dict(), dict(dag="linear"), dict(small_times=True), dict(tie_heavy=True)][seed % 4]
+    w, bases, base_of = workloads.neighbourhood_case(seed, n=int(np.random.default_rng(seed).integers(200, 4000)), n_bases=3,
+                                                     per_base=12, max_b=16, max_r=6, **kw)
+    _check(binding.Estimator(w.parents, w.lat_us, w.cost_uusd_hr), w, bases, base_of, "cuda:0")
+
+
+@pytest.mark.gpu
+def test_shared_run_on_the_ten_stage_pipeline():
+    # the 10-stage pipeline of the large workloads, neighbourhoods as in W5, 20,000 queries
+    w = workloads.w5(n=20_000, n_base=24)
+    base_of = (np.arange(w.n_configs) // 64).astype(np.uint32)
+    bases = (w.cfg_hw[::64].copy(), w.cfg_batch[::64].copy(), w.cfg_replicas[::64].copy())
+    est = binding.Estimator(w.parents, w.lat_us, w.cost_uusd_hr)
+    got, stats = _run_shared(est, w, bases, base_of, "cuda:0")
+    import torch
+    cfg = binding.pack_configs(w.cfg_hw, w.cfg_batch, w.cfg_replicas)
+    t = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a).view(dt).reshape(-1).copy()).to("cuda:0")
+    plain = est.run_dev(t(w.arrival_us, np.int32), t(w.visit_mask, np.int32), t(cfg, np.uint8), cfg.shape[0], w.slo_us)
+    for k in ("p99_us", "miss_count", "cost_uusd_hr"):
+        assert np.array_equal(got[k], plain[k].cpu().numpy())
+    idx = np.arange(0, w.n_configs, 37)  # and a sample against the oracle
+    ref = oracle.run(w.parents, w.lat_us, w.cost_uusd_hr, w.arrival_us, w.visit_mask, w.cfg_hw[idx], w.cfg_batch[idx], w.cfg_replicas[idx], w.slo_us)
+    assert np.array_equal(got["p99_us"].view(np.uint32)[idx].astype(np.uint64), ref["p99_us"])
+    assert np.array_equal(got["miss_count"].view(np.uint32)[idx].astype(np.uint64), ref["miss_count"])
+    assert stats["ops_run_fraction"] < 0.8
