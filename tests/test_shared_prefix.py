@@ -57,6 +57,24 @@ def test_sharing_skips_work_and_identical_candidates_skip_everything_but_the_sin
     assert stats["n_launches"] == 1 and stats["ops_run_fraction"] == 1.0
 
 
+def test_no_bases_or_no_queries_fall_back_to_the_plain_run():
+    import torch
+    w, bases, base_of = workloads.neighbourhood_case(7, n=60)
+    est = emu_lib.make(w)
+    cfg = binding.pack_configs(w.cfg_hw, w.cfg_batch, w.cfg_replicas)
+    t = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a).view(dt).reshape(-1).copy())
+    stream = types.SimpleNamespace(cuda_stream=0)
+    res = est.run_shared_dev(t(w.arrival_us, np.int32), t(w.visit_mask, np.int32), t(cfg, np.uint8)[:0], 0, t(cfg, np.uint8),
+                             t(base_of, np.int32), cfg.shape[0], w.slo_us, stream=stream)
+    ref = _oracle(w)
+    assert np.array_equal(res["p99_us"].numpy().view(np.uint32).astype(np.uint64), ref["p99_us"])
+    empty = torch.zeros(0, dtype=torch.int32)
+    res = est.run_shared_dev(empty, empty, t(binding.pack_configs(*bases), np.uint8), len(bases[0]), t(cfg, np.uint8),
+                             t(base_of, np.int32), cfg.shape[0], w.slo_us, stream=stream)
+    assert not res["p99_us"].numpy().any() and not res["miss_count"].numpy().any()
+    assert np.array_equal(res["cost_uusd_hr"].numpy().view(np.uint64), ref["cost_uusd_hr"])
+
+
 def test_shared_run_rejects_bad_base_index():
     w, bases, base_of = workloads.neighbourhood_case(5, n=40)
     bad = base_of.copy(); bad[0] = 99
