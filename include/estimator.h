@@ -149,10 +149,12 @@ int estimator_run_latencies(estimator_t *h, const est_trace_t *trace, const est_
  * bases is [n_bases][S], configs [n_cfg][S], base_of [n_cfg] with entries < n_bases: DEVICE
  * pointers, like the trace arrays and the arrays of out.  A candidate may differ from its base in
  * any number of stages (sharing shrinks accordingly); n_bases == 0 behaves as estimator_run_dev.
- * The library allocates the scratch (cached in the handle like estimator_run_dev's; the streams shared
- * by one base stay in memory for the whole call: 8 bytes x queries per shared stream).
- * Errors as estimator_run_dev; EST_EINVAL for a base_of entry out of range; EST_ENOMEM when the
- * bases' streams do not fit (pass fewer bases per call); EST_EUNSUPPORTED for pipelines whose run
+ * The library allocates the scratch (cached in the handle like estimator_run_dev's).  The streams shared
+ * by one base take 8 bytes x queries per shared stream; when those of all bases do not fit, the bases
+ * are taken in rounds, the next round's bases running on a second stream of the library's own (default
+ * priority) beside the current round's candidates.  All work has completed when the call returns.
+ * Errors as estimator_run_dev; EST_EINVAL for a base_of entry out of range; EST_ENOMEM when not even
+ * one base's streams fit beside one candidate's scratch; EST_EUNSUPPORTED for pipelines whose run
  * needs more than 64 operations or streams.
  */
 int estimator_run_shared_dev(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *bases, uint64_t n_bases,

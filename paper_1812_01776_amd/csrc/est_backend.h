@@ -26,6 +26,10 @@ int launch_sim(const EstSimArgs &a, void *stream);
 int launch_envelope(const EstEnvArgs &a, void *stream);
 uint32_t max_resident_waves(uint32_t lds_bytes_per_wave);  // wavefronts of the simulation kernel the device holds at once
 
+void *stream_create();            // a second stream at the default priority; nullptr on failure
+void stream_destroy(void *stream);
+int stream_wait_event(void *stream, void *ev);  // later work on stream starts after ev has completed
+
 void *event_create();
 void event_destroy(void *ev);
 int event_record(void *ev, void *stream);

@@ -461,8 +461,8 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
     const uint32_t S = h->dag.S;
     EventSet evs;
     void *ev_p0 = evs.make(), *ev_p1 = evs.make(), *ev_p2 = evs.make(), *ev_p3 = evs.make();
-    void *e0 = evs.make(), *e1 = evs.make(), *e2 = evs.make();
-    if (!ev_p0 || !ev_p1 || !ev_p2 || !ev_p3 || !e0 || !e1 || !e2) return dev_fail(h, "event create");
+    void *e0 = evs.make(), *e2 = evs.make();
+    if (!ev_p0 || !ev_p1 || !ev_p2 || !ev_p3 || !e0 || !e2) return dev_fail(h, "event create");
 
     // ---- scan the configurations (bases and candidates) and the trace
     if (estbe::zero(h->d_status, sizeof(EstStatus), stream)) return dev_fail(h, "clear status");
@@ -545,13 +545,6 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
                 if (op.src_ring[j] >= 0) needed |= 1ull << producer[op.src_ring[j]];
     }
     const uint64_t all_ops = P.n_ops == 64 ? ~0ull : ((1ull << P.n_ops) - 1ull);
-    const std::vector<uint64_t> skip_cap(n_bases, all_ops & ~needed);
-
-    // candidates that run the most operations are handed out first, so that the launch ends on short ones
-    std::vector<uint32_t> order(n_cfg);
-    for (uint64_t t = 0; t < n_cfg; ++t) order[t] = (uint32_t)t;
-    std::stable_sort(order.begin(), order.end(),
-                     [&](uint32_t x, uint32_t y) { return __builtin_popcountll(skip[x]) < __builtin_popcountll(skip[y]); });
 
     // the capture's layout: the same operations and streams; captured streams, and streams one of whose
     // readers the capture does not run, with room for every element
@@ -573,8 +566,60 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
         cap_elems += cap;
     }
 
-    // ---- lay out the scratch (in the handle's cached workspace, grown when it is too small)
+    // ---- rounds: when the captured streams of all bases do not fit beside the candidates' scratch, the bases
+    //      are taken a group at a time, with two capture areas: while the candidates of one group run on the
+    //      caller's stream, the next group's bases run on a second stream and fill the wavefront slots the
+    //      candidates leave (a launch of a few hundred bases alone would leave most of the device idle for as
+    //      long as one simulation takes)
     const uint64_t n_pad = align_up(std::max<uint64_t>(n, 1), 256);
+    const uint64_t cap_bytes = po.sz.state_words * 4 + cap_elems * 8 + po.sz.rep_words * 4 + po.sz.slot_words * 4 + po.sz.cnt_bytes + 8 + 8;
+    const uint64_t per_cfg = po.sz.per_cfg_bytes(n, true) + 64;
+    const uint32_t resident = std::max<uint32_t>(estbe::max_resident_waves(po.lds_bytes), 1);
+    const uint64_t avail = ((uint64_t)estbe::mem_free() + h->ws_bytes) / 100 * 85;
+    const uint64_t fixed_est = n_pad * 8 + (uint64_t)std::max<uint32_t>(po.n_acc, 1) * n_pad + n_cfg * 32 + sizeof(EstPlan) + 2 * sizeof(EstStatus) + 64 * 256;
+    uint64_t n_slots = std::min<uint64_t>(n_cfg, resident);
+    uint64_t nb = n_bases;  // bases per round
+    uint32_t n_areas = 1;
+    if (fixed_est + n_bases * cap_bytes + per_cfg * n_slots > avail) {
+        n_areas = 2;
+        for (;;) {
+            const uint64_t rest = avail > fixed_est + per_cfg * n_slots ? avail - fixed_est - per_cfg * n_slots : 0;
+            nb = rest / (2 * cap_bytes);
+            if (nb >= 1 || n_slots <= 64) break;
+            n_slots = std::max<uint64_t>(64, n_slots / 2);  // fewer candidates in flight to make room for one base per area
+        }
+        if (nb < 1)
+            return fail(h, EST_ENOMEM, "one base's captured streams (%llu bytes) and one candidate's scratch (%llu) do not fit in %llu free bytes",
+                        (unsigned long long)cap_bytes, (unsigned long long)per_cfg, (unsigned long long)avail);
+        nb = std::min<uint64_t>(nb, n_bases);
+    }
+    if (const char *e = getenv("EST_SHARED_BASES_PER_ROUND")) {  // for tests: force small rounds
+        const long v = atol(e);
+        if (v >= 1 && (uint64_t)v < nb) {
+            nb = (uint64_t)v;
+            n_areas = 2;
+        }
+    }
+    const uint64_t n_rounds = (n_bases + nb - 1) / nb;
+    if (n_rounds == 1) n_areas = 1;
+
+    // candidates grouped by round; inside a round those that run the most operations are handed out first,
+    // so that a launch ends on short ones
+    std::vector<uint32_t> order(n_cfg), base_local(n_cfg);
+    for (uint64_t t = 0; t < n_cfg; ++t) {
+        order[t] = (uint32_t)t;
+        base_local[t] = (uint32_t)(base_of[t] % nb);
+    }
+    std::stable_sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) {
+        const uint64_t rx = base_of[x] / nb, ry = base_of[y] / nb;
+        if (rx != ry) return rx < ry;
+        return __builtin_popcountll(skip[x]) < __builtin_popcountll(skip[y]);
+    });
+    std::vector<uint64_t> round_lo(n_rounds + 1, n_cfg);
+    for (uint64_t i = n_cfg; i-- > 0;) round_lo[base_of[order[i]] / nb] = i;
+    for (uint64_t k = n_rounds; k-- > 0;) round_lo[k] = std::min(round_lo[k], round_lo[k + 1]);  // rounds without candidates
+
+    // ---- lay out the scratch (in the handle's cached workspace, grown when it is too small)
     uint64_t at = 0;
     auto take = [&](uint64_t bytes) {
         uint64_t a0 = at;
@@ -584,22 +629,18 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
     const uint64_t o_keys = take(n_pad * 8);
     const uint64_t o_acc = take((uint64_t)std::max<uint32_t>(po.n_acc, 1) * n_pad);
     const uint64_t o_p99 = take(n_cfg * 4), o_miss = take(n_cfg * 4), o_cost = take(n_cfg * 8);
-    const uint64_t o_skip = take(n_cfg * 8), o_skip_cap = take(n_bases * 8), o_order = take(n_cfg * 4);
-    const uint64_t o_res_cap = take(n_bases * 8);  // results of the capture launch (only its cost is written; unused)
+    const uint64_t o_skip = take(n_cfg * 8), o_skip_cap = take(nb * 8), o_order = take(n_cfg * 4), o_base_local = take(n_cfg * 4);
+    const uint64_t o_res_cap = take(nb * 8);  // results of the bases' launches (only the cost is written; unused)
     const uint64_t o_plan_cap = take(sizeof(EstPlan));
-    const uint64_t o_cstate = take(n_bases * po.sz.state_words * 4);
-    const uint64_t o_crings = take(n_bases * cap_elems * 8);
-    const uint64_t o_crep = take(n_bases * po.sz.rep_words * 4);
-    const uint64_t o_cslots = take(n_bases * po.sz.slot_words * 4);
-    const uint64_t o_ccnt = take(n_bases * po.sz.cnt_bytes);
-    const uint64_t fixed = at;
-    const uint64_t per_cfg = po.sz.per_cfg_bytes(n, true) + 64;
-    const uint32_t resident = std::max<uint32_t>(estbe::max_resident_waves(po.lds_bytes), 1);
-    const uint64_t avail = ((uint64_t)estbe::mem_free() + h->ws_bytes) / 100 * 85;
-    if (fixed + per_cfg * std::min<uint64_t>(n_cfg, 256) + 8 * 256 > avail)
-        return fail(h, EST_ENOMEM, "%llu bases need %llu bytes of captured streams and %llu are free: pass fewer bases per call",
-                    (unsigned long long)n_bases, (unsigned long long)fixed, (unsigned long long)avail);
-    uint64_t n_slots = std::min<uint64_t>({n_cfg, (uint64_t)resident, (avail - fixed - 8 * 256) / per_cfg});
+    const uint64_t o_status = take(2 * sizeof(EstStatus));  // work counters of the two kinds of launch
+    uint64_t o_cstate[2], o_crings[2], o_crep[2], o_cslots[2], o_ccnt[2];
+    for (uint32_t i = 0; i < n_areas; ++i) {
+        o_cstate[i] = take(nb * po.sz.state_words * 4);
+        o_crings[i] = take(nb * cap_elems * 8);
+        o_crep[i] = take(nb * po.sz.rep_words * 4);
+        o_cslots[i] = take(nb * po.sz.slot_words * 4);
+        o_ccnt[i] = take(nb * po.sz.cnt_bytes);
+    }
     auto area = [&](uint64_t bytes_per_cfg) {
         uint64_t a0 = at;
         at = align_up(at + bytes_per_cfg * n_slots, 256);
@@ -620,11 +661,15 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
         h->ws_bytes = at;
     }
     uint8_t *ws = (uint8_t *)h->ws;
+    EstStatus *st_cap = (EstStatus *)(ws + o_status), *st_rep = st_cap + 1;
 
     // ---- per-query tables, plans, masks
+    const std::vector<uint64_t> skip_cap(nb, all_ops & ~needed);
     estbe::event_record(ev_p2, stream);
     if (estbe::h2d(h->d_plan, &po.plan, sizeof(EstPlan), stream) || estbe::h2d(ws + o_plan_cap, &PC, sizeof(EstPlan), stream) ||
-        estbe::h2d(ws + o_skip, skip.data(), n_cfg * 8, stream) || estbe::h2d(ws + o_order, order.data(), n_cfg * 4, stream) || estbe::h2d(ws + o_skip_cap, skip_cap.data(), n_bases * 8, stream))
+        estbe::h2d(ws + o_skip, skip.data(), n_cfg * 8, stream) || estbe::h2d(ws + o_order, order.data(), n_cfg * 4, stream) ||
+        estbe::h2d(ws + o_base_local, base_local.data(), n_cfg * 4, stream) || estbe::h2d(ws + o_skip_cap, skip_cap.data(), nb * 8, stream) ||
+        estbe::zero(ws + o_status, 2 * sizeof(EstStatus), stream))
         return dev_fail(h, "upload plan");
     pa.trace_keys = (uint64_t *)(ws + o_keys);
     pa.acc = ws + o_acc;
@@ -648,69 +693,118 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
     sa.slo_us = slo_us;
     sa.max_src = po.plan.max_src;
     sa.lds_bytes = po.lds_bytes;
-    sa.status = h->d_status;
 
-    // ---- launch 1: the bases, candidate t in slot t, streams left in place
-    estbe::event_record(e0, stream);
     const bool capture = needed != 0;
-    if (capture) {
-        EstSimArgs ca2 = sa;
-        ca2.plan = (const EstPlan *)(ws + o_plan_cap);
-        ca2.cfg = (const EstStageCfg *)d_bases;
-        ca2.n_cfg = (uint32_t)n_bases;
-        ca2.n_slots = (uint32_t)std::min<uint64_t>(n_bases, resident);
-        ca2.have_lat = 0;
-        ca2.state = (uint32_t *)(ws + o_cstate);  ca2.state_stride = po.sz.state_words;
-        ca2.rings = (uint64_t *)(ws + o_crings);  ca2.ring_stride = cap_elems;
-        ca2.rep = (uint32_t *)(ws + o_crep);      ca2.rep_stride = po.sz.rep_words;
-        ca2.slots = (uint32_t *)(ws + o_cslots);  ca2.slot_stride = po.sz.slot_words;
-        ca2.counters = ws + o_ccnt;               ca2.cnt_stride = po.sz.cnt_bytes;
-        ca2.lat = nullptr;
-        ca2.p99 = (uint32_t *)(ws + o_res_cap); ca2.miss = (uint32_t *)(ws + o_res_cap); ca2.cost = (uint64_t *)(ws + o_res_cap);
-        ca2.skip_ops = (const uint64_t *)(ws + o_skip_cap);
-        ca2.slot_by_cfg = 1;
-        if (estbe::launch_sim(ca2, stream)) return dev_fail(h, "simulation kernel (bases)");
-        if (estbe::zero(&h->d_status->next_cfg, 4, stream)) return dev_fail(h, "reset the work counter");
-    }
-    estbe::event_record(e1, stream);
-
-    // ---- launch 2: the candidates
-    {
-        EstSimArgs cb = sa;
-        cb.plan = h->d_plan;
-        cb.cfg = (const EstStageCfg *)d_cfg;
-        cb.n_cfg = (uint32_t)n_cfg;
-        cb.n_slots = (uint32_t)n_slots;
-        cb.have_lat = 1;
-        cb.state = (uint32_t *)(ws + o_state);  cb.state_stride = po.sz.state_words;
-        cb.rings = (uint64_t *)(ws + o_rings);  cb.ring_stride = po.sz.ring_elems;
-        cb.rep = (uint32_t *)(ws + o_rep);      cb.rep_stride = po.sz.rep_words;
-        cb.slots = (uint32_t *)(ws + o_slots);  cb.slot_stride = po.sz.slot_words;
-        cb.counters = ws + o_cnt;               cb.cnt_stride = po.sz.cnt_bytes;
-        cb.lat = (uint32_t *)(ws + o_lat);      cb.lat_stride = n;
-        cb.p99 = (uint32_t *)(ws + o_p99); cb.miss = (uint32_t *)(ws + o_miss); cb.cost = (uint64_t *)(ws + o_cost);
-        cb.skip_ops = (const uint64_t *)(ws + o_skip);
-        cb.base_of = d_base_of;
-        cb.order = (const uint32_t *)(ws + o_order);
-        cb.cap_plan = (const EstPlan *)(ws + o_plan_cap);
-        if (capture) {
-            cb.cap_rings = (const uint64_t *)(ws + o_crings);  cb.cap_ring_stride = cap_elems;
-            cb.cap_state = (const uint32_t *)(ws + o_cstate);  cb.cap_state_stride = po.sz.state_words;
+    struct SideStream {  // the second stream, drained and destroyed on every path out
+        void *s = nullptr;
+        ~SideStream() {
+            if (s) {
+                estbe::sync(s);
+                estbe::stream_destroy(s);
+            }
         }
-        if (estbe::launch_sim(cb, stream)) return dev_fail(h, "simulation kernel");
+    } side;
+    void *cap_stream = stream;
+    if (capture && n_rounds > 1) {
+        side.s = estbe::stream_create();
+        if (!side.s) return dev_fail(h, "stream create");
+        cap_stream = side.s;
+        if (estbe::stream_wait_event(cap_stream, ev_p3)) return dev_fail(h, "stream wait");  // tables and plans are in place
+    }
+    std::vector<void *> cap_begin(n_rounds, nullptr), cap_done(n_rounds, nullptr), rep_done(n_rounds, nullptr);
+    for (uint64_t k = 0; k < n_rounds; ++k) {
+        cap_begin[k] = evs.make(); cap_done[k] = evs.make(); rep_done[k] = evs.make();
+        if (!cap_begin[k] || !cap_done[k] || !rep_done[k]) return dev_fail(h, "event create");
+    }
+    // the bases of round k, candidate t in slot t of capture area k mod 2, streams left in place
+    auto launch_bases = [&](uint64_t k) -> int {
+        const uint64_t b0 = k * nb, nbk = std::min<uint64_t>(nb, n_bases - b0);
+        const uint32_t ar = (uint32_t)(k % n_areas);
+        EstSimArgs c2 = sa;
+        c2.status = st_cap;
+        c2.plan = (const EstPlan *)(ws + o_plan_cap);
+        c2.cfg = (const EstStageCfg *)d_bases + b0 * S;
+        c2.n_cfg = (uint32_t)nbk;
+        c2.n_slots = (uint32_t)std::min<uint64_t>(nbk, resident);
+        c2.have_lat = 0;
+        c2.state = (uint32_t *)(ws + o_cstate[ar]);  c2.state_stride = po.sz.state_words;
+        c2.rings = (uint64_t *)(ws + o_crings[ar]);  c2.ring_stride = cap_elems;
+        c2.rep = (uint32_t *)(ws + o_crep[ar]);      c2.rep_stride = po.sz.rep_words;
+        c2.slots = (uint32_t *)(ws + o_cslots[ar]);  c2.slot_stride = po.sz.slot_words;
+        c2.counters = ws + o_ccnt[ar];               c2.cnt_stride = po.sz.cnt_bytes;
+        c2.lat = nullptr;
+        c2.p99 = (uint32_t *)(ws + o_res_cap); c2.miss = (uint32_t *)(ws + o_res_cap); c2.cost = (uint64_t *)(ws + o_res_cap);
+        c2.skip_ops = (const uint64_t *)(ws + o_skip_cap);
+        c2.slot_by_cfg = 1;
+        if (nbk == 0 || nbk > nb || ar >= n_areas) return 1;  // a launch must stay inside the scratch laid out above
+        if (k >= 2 && estbe::stream_wait_event(cap_stream, rep_done[k - 2])) return 1;  // the area's previous readers are done
+        estbe::event_record(cap_begin[k], cap_stream);
+        if (estbe::zero(&st_cap->next_cfg, 4, cap_stream) || estbe::launch_sim(c2, cap_stream)) return 1;
+        estbe::event_record(cap_done[k], cap_stream);
+        return 0;
+    };
+    auto launch_candidates = [&](uint64_t k) -> int {
+        const uint64_t lo = round_lo[k], hi = round_lo[k + 1];
+        const uint32_t ar = (uint32_t)(k % n_areas);
+        if (capture && cap_stream != stream && estbe::stream_wait_event(stream, cap_done[k])) return 1;
+        if (hi > lo) {
+            EstSimArgs cb = sa;
+            cb.status = st_rep;
+            cb.plan = h->d_plan;
+            cb.cfg = (const EstStageCfg *)d_cfg;
+            cb.n_cfg = (uint32_t)(hi - lo);
+            // the next round's bases become runnable when this launch starts: leave them their wavefront slots,
+            // or they would wait for this launch's wavefronts to finish
+            uint64_t mine = n_slots;
+            if (capture && k + 1 < n_rounds) {
+                const uint64_t next = std::min<uint64_t>(nb, n_bases - (k + 1) * nb);
+                mine = std::max<uint64_t>(n_slots > next ? n_slots - next : 0, std::min<uint64_t>(n_slots, 64));  // never more than exist
+            }
+            cb.n_slots = (uint32_t)std::min<uint64_t>(mine, hi - lo);
+            cb.have_lat = 1;
+            cb.state = (uint32_t *)(ws + o_state);  cb.state_stride = po.sz.state_words;
+            cb.rings = (uint64_t *)(ws + o_rings);  cb.ring_stride = po.sz.ring_elems;
+            cb.rep = (uint32_t *)(ws + o_rep);      cb.rep_stride = po.sz.rep_words;
+            cb.slots = (uint32_t *)(ws + o_slots);  cb.slot_stride = po.sz.slot_words;
+            cb.counters = ws + o_cnt;               cb.cnt_stride = po.sz.cnt_bytes;
+            cb.lat = (uint32_t *)(ws + o_lat);      cb.lat_stride = n;
+            cb.p99 = (uint32_t *)(ws + o_p99); cb.miss = (uint32_t *)(ws + o_miss); cb.cost = (uint64_t *)(ws + o_cost);
+            cb.skip_ops = (const uint64_t *)(ws + o_skip);
+            cb.base_of = (const uint32_t *)(ws + o_base_local);
+            cb.order = (const uint32_t *)(ws + o_order) + lo;
+            cb.cap_plan = (const EstPlan *)(ws + o_plan_cap);
+            if (capture) {
+                cb.cap_rings = (const uint64_t *)(ws + o_crings[ar]);  cb.cap_ring_stride = cap_elems;
+                cb.cap_state = (const uint32_t *)(ws + o_cstate[ar]);  cb.cap_state_stride = po.sz.state_words;
+            }
+            if (cb.n_slots > n_slots || cb.n_slots == 0) return 1;  // a launch must stay inside the scratch laid out above
+            if (estbe::zero(&st_rep->next_cfg, 4, stream) || estbe::launch_sim(cb, stream)) return 1;
+        }
+        estbe::event_record(rep_done[k], stream);
+        return 0;
+    };
+    estbe::event_record(e0, stream);
+    if (capture && launch_bases(0)) return dev_fail(h, "simulation kernel (bases)");
+    for (uint64_t k = 0; k < n_rounds; ++k) {
+        if (capture && k + 1 < n_rounds && launch_bases(k + 1)) return dev_fail(h, "simulation kernel (bases)");
+        if (launch_candidates(k)) return dev_fail(h, "simulation kernel");
     }
     estbe::event_record(e2, stream);
-    EstStatus st2;
-    if (estbe::d2h(&st2, h->d_status, sizeof st2, stream) || estbe::sync(stream)) return dev_fail(h, "run");
-    if (st2.sim_error) return fail(h, EST_EINTERNAL, "the simulation kernel stopped without finishing a candidate");
+    EstStatus st2, st3;
+    if (estbe::d2h(&st2, st_cap, sizeof st2, stream) || estbe::d2h(&st3, st_rep, sizeof st3, stream) || estbe::sync(stream))
+        return dev_fail(h, "run");
+    if (st2.sim_error || st3.sim_error) return fail(h, EST_EINTERNAL, "the simulation kernel stopped without finishing a candidate");
     if (estbe::d2d(d_p99, ws + o_p99, n_cfg * 4, stream) || estbe::d2d(d_miss, ws + o_miss, n_cfg * 4, stream) ||
         estbe::d2d(d_cost, ws + o_cost, n_cfg * 8, stream) || estbe::sync(stream))
         return dev_fail(h, "copy results");
+    float capture_ms = 0.f;
+    if (capture)
+        for (uint64_t k = 0; k < n_rounds; ++k) capture_ms += estbe::event_ms(cap_begin[k], cap_done[k]);
     est_stats_t &ss = h->stats;
     memset(&ss, 0, sizeof ss);
-    ss.n_launches = capture ? 2 : 1;
+    ss.n_launches = (uint32_t)((capture ? 2 : 1) * n_rounds);
     ss.n_slots = (uint32_t)n_slots;
-    ss.capture_ms = estbe::event_ms(e0, e1);
+    ss.capture_ms = capture_ms;
     ss.sim_ms = estbe::event_ms(e0, e2);
     ss.prep_ms = estbe::event_ms(ev_p0, ev_p1) + estbe::event_ms(ev_p2, ev_p3);
     for (uint32_t s = 0; s < S; ++s) ss.stage_visits += st.n_visit[s];

@@ -178,6 +178,14 @@ uint32_t max_resident_waves(uint32_t lds_bytes_per_wave) {
     return (uint32_t)cus * (uint32_t)blocks * EST_WAVES_PER_BLOCK;
 }
 
+void *stream_create() {
+    hipStream_t st = nullptr;
+    if (check(hipStreamCreateWithFlags(&st, hipStreamNonBlocking), "hipStreamCreate")) return nullptr;
+    return (void *)st;
+}
+void stream_destroy(void *stream) { (void)hipStreamDestroy((hipStream_t)stream); }
+int stream_wait_event(void *stream, void *ev) { return check(hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)ev, 0), "hipStreamWaitEvent"); }
+
 void *event_create() {
     hipEvent_t e = nullptr;
     if (check(hipEventCreate(&e), "hipEventCreate")) return nullptr;

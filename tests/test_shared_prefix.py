@@ -57,6 +57,16 @@ def test_sharing_skips_work_and_identical_candidates_skip_everything_but_the_sin
     assert stats["n_launches"] == 1 and stats["ops_run_fraction"] == 1.0
 
 
+@pytest.mark.parametrize("per_round", [1, 2])
+def test_bases_taken_a_group_at_a_time_emulated(per_round, monkeypatch):
+    # more bases than one round holds (forced here): two capture areas used in turn
+    monkeypatch.setenv("EST_SHARED_BASES_PER_ROUND", str(per_round))
+    for seed in (2, 9):
+        w, bases, base_of = workloads.neighbourhood_case(seed, n=150, n_bases=5, per_base=4)
+        stats = _check(emu_lib.make(w), w, bases, base_of, "cpu")
+        assert stats["n_launches"] in (-(-5 // per_round), 2 * -(-5 // per_round))
+
+
 def test_no_bases_or_no_queries_fall_back_to_the_plain_run():
     import torch
     w, bases, base_of = workloads.neighbourhood_case(7, n=60)
@@ -90,6 +100,17 @@ def test_shared_run_equals_independent_simulation(seed):
     w, bases, base_of = workloads.neighbourhood_case(seed, n=int(np.random.default_rng(seed).integers(200, 4000)), n_bases=3,
                                                      per_base=12, max_b=16, max_r=6, **kw)
     _check(binding.Estimator(w.parents, w.lat_us, w.cost_uusd_hr), w, bases, base_of, "cuda:0")
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("per_round", [1, 3])
+def test_bases_taken_a_group_at_a_time(per_round, monkeypatch):
+    # forced small rounds: the next round's bases run on a second stream beside this round's candidates
+    monkeypatch.setenv("EST_SHARED_BASES_PER_ROUND", str(per_round))
+    for seed in (1, 4, 10):
+        w, bases, base_of = workloads.neighbourhood_case(seed, n=3000, n_bases=7, per_base=10, max_b=16, max_r=6)
+        stats = _check(binding.Estimator(w.parents, w.lat_us, w.cost_uusd_hr), w, bases, base_of, "cuda:0")
+        assert stats["n_launches"] >= -(-7 // per_round)
 
 
 @pytest.mark.gpu
