@@ -51,7 +51,7 @@ def main():
     ap.add_argument("--shared", action="store_true",
                     help="instead of the hot path with every candidate simulated on its own: the same candidates through "
                          "estimator_run_shared_dev, upstream stages shared with a base configuration (W4, W5)")
-    ap.add_argument("--shared-bases-per-call", type=int, default=0, help="bases per library call (0 = 4096 on W4, 1024 on W5; the library takes them in rounds that fit the memory)")
+    ap.add_argument("--shared-bases-per-call", type=int, default=0, help="bases per library call (0 = 4096 on W4, 2048 on W5; the library takes them in rounds that fit the memory)")
     ap.add_argument("--shared-configs", type=int, default=0, help="only the first this many candidates (0 = all)")
     ap.add_argument("--planner-queries", type=int, default=50000, help="trace prefix the planner works on")
     ap.add_argument("--planner-max-replicas", type=int, default=32)
@@ -139,7 +139,7 @@ def main():
             base_rows, base_of = np.unique(key, axis=0, return_inverse=True)
             base_of = base_of.reshape(-1)
         C = args.shared_configs if args.shared_configs > 0 else w.n_configs
-        per_call = args.shared_bases_per_call or (1024 if args.workload == "W5" else 4096)
+        per_call = args.shared_bases_per_call or (2048 if args.workload == "W5" else 4096)
         order = np.argsort(base_of[:C], kind="stable")  # candidates grouped by base, results put back in place
         p99 = np.zeros(C, np.uint32); miss = np.zeros(C, np.uint32)
         sim_ms = cap_ms = 0.0; frac = []; calls = 0

@@ -610,10 +610,14 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
         order[t] = (uint32_t)t;
         base_local[t] = (uint32_t)(base_of[t] % nb);
     }
+    std::vector<uint64_t> work(n_cfg, 0);  // elements the candidate's operations will move: what its run time goes with
+    for (uint64_t t = 0; t < n_cfg; ++t)
+        for (uint32_t i = 0; i < P.n_ops; ++i)
+            if (!((skip[t] >> i) & 1ull)) work[t] += st.n_visit[P.ops[i].stage];
     std::stable_sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) {
         const uint64_t rx = base_of[x] / nb, ry = base_of[y] / nb;
         if (rx != ry) return rx < ry;
-        return __builtin_popcountll(skip[x]) < __builtin_popcountll(skip[y]);
+        return work[x] > work[y];
     });
     std::vector<uint64_t> round_lo(n_rounds + 1, n_cfg);
     for (uint64_t i = n_cfg; i-- > 0;) round_lo[base_of[order[i]] / nb] = i;
