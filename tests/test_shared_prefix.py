@@ -132,3 +132,32 @@ def test_shared_run_on_the_ten_stage_pipeline():
     assert np.array_equal(got["p99_us"].view(np.uint32)[idx].astype(np.uint64), ref["p99_us"])
     assert np.array_equal(got["miss_count"].view(np.uint32)[idx].astype(np.uint64), ref["miss_count"])
     assert stats["ops_run_fraction"] < 0.8
+
+
+@pytest.mark.gpu
+def test_shared_run_at_full_trace_length_sampled():
+    # W4's trace at its full 1,000,000 queries; 2,048 candidates of the grid, cut along its most downstream
+    # swept stage (1,024 bases, two candidates each, streams of full length); two sampled candidates against the oracle
+    import torch
+    w = workloads.w4()
+    g = np.arange(16)  # grid index of the four swept stages: candidate = g0 + 16 g1 + 256 g2 + 4096 g3
+    sel = (g[:, None, None, None] + 16 * g[None, :, None, None] + 256 * g[None, None, :4, None] +
+           4096 * np.array([0, 5])[None, None, None, :]).reshape(-1)
+    sel = np.sort(sel)
+    w = w.subset(cfg_index=sel, n_queries=w.n_queries)
+    S = w.n_stages
+    cfg = binding.pack_configs(w.cfg_hw, w.cfg_batch, w.cfg_replicas)
+    words = cfg.view(np.uint32).reshape(-1, S)
+    varies = [s for s in range(S) if (words[:, s] != words[0, s]).any()]
+    key = words.copy(); key[:, max(varies)] = words[0, max(varies)]
+    base_rows, base_of = np.unique(key, axis=0, return_inverse=True)
+    t = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a).view(dt).reshape(-1).copy()).to("cuda:0")
+    est = binding.Estimator(w.parents, w.lat_us, w.cost_uusd_hr)
+    res = est.run_shared_dev(t(w.arrival_us, np.int32), t(w.visit_mask, np.int32), t(base_rows, np.uint8), len(base_rows), t(cfg, np.uint8),
+                             t(base_of.reshape(-1).astype(np.int32), np.int32), len(words), w.slo_us)
+    assert est.stats()["ops_run_fraction"] < 1.0
+    idx = np.array([3, len(words) - 5])
+    ref = oracle.run(w.parents, w.lat_us, w.cost_uusd_hr, w.arrival_us, w.visit_mask, w.cfg_hw[idx], w.cfg_batch[idx], w.cfg_replicas[idx], w.slo_us)
+    assert np.array_equal(res["p99_us"].cpu().numpy().view(np.uint32)[idx].astype(np.uint64), ref["p99_us"])
+    assert np.array_equal(res["miss_count"].cpu().numpy().view(np.uint32)[idx].astype(np.uint64), ref["miss_count"])
+    assert np.array_equal(res["cost_uusd_hr"].cpu().numpy().view(np.uint64)[idx], ref["cost_uusd_hr"])
