@@ -42,9 +42,8 @@ EST_DEV uint32_t sat_add(uint32_t t, uint32_t d) {
     return e < t ? 0xFFFFFFFFu : e;
 }
 
-// LDS of one wavefront while it merges, for a plan whose widest merge has k sources:
-// staged keys uint64 [k][64] | merged run uint64 [k*64] | staged positions uint32 [k][64] |
-// per-source cursors | duplicate-spotting counters.  Size: EST_LDS_MERGE_BYTES(k).
+// LDS of one wavefront while it merges, for a plan whose widest merge has k sources: see merge_run.
+// Size: EST_LDS_MERGE_BYTES(k).
 
 struct Ctx {
     const EstSimArgs *a;
@@ -53,7 +52,7 @@ struct Ctx {
     uint64_t *rings;
     uint32_t *rep;
     uint32_t *slots;
-    uint8_t *cnt;
+    uint8_t *tab;  // time tables of the merges that join several streams
     uint32_t *lat;
     const EstStageCfg *cfg;
     uint64_t *lds;
@@ -62,6 +61,14 @@ struct Ctx {
     uint64_t memo_rings;
     const uint64_t *cap_rings;
 };
+
+// Diagnostics record of candidate t and stage s: 8 words (general steps, ticks in the stage's scan, shortcut
+// steps, queries in shortcut steps, of which: lean light-load, light-load, one-per-batch, block of batches).
+// The record of stage EST_MAX_STAGES-1 holds what belongs to no stage: ticks in merges, in the sink, in the
+// selection, merge rounds, merge output elements, merge calls, scan calls, queries in general steps.
+EST_DEV uint64_t *est_dbg_rec(const EstSimArgs *a, uint32_t t, uint32_t s) {
+    return a->dbg_ticks + a->n_cfg + ((uint64_t)t * EST_MAX_STAGES + s) * 8;
+}
 
 struct View {
     const uint64_t *base;
@@ -321,7 +328,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         const uint32_t cn = wv::bcast(rcnt, l), sl = wv::bcast(rslot, l);
         if (ln < cn) lslots[sl * bm + ln] = g_slots[sl * bm + ln];
     }
-    wv::sync();
+    wv::sync_lds();
 
     View in = view_of<MEMO>(c, op.src_ring[0]);
     in.mask = wv::uniform(in.mask);
@@ -360,7 +367,9 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     uint32_t sat_skip = 0;  // the same for the backlog shortcut
     uint32_t single_skip = 0;  // and for the one-query-per-batch shortcut
     uint32_t blk_skip = 0;     // and for the block of batches
-    uint32_t d_gen = 0, d_gene = 0, d_fp = 0, d_fpe = 0, d_b1 = 0, d_b1e = 0, d_sat = 0, d_sate = 0, d_hz = 0, d_blk = 0, d_blke = 0;  // diagnostics
+    uint32_t lean_skip = 0;    // and for the light-load step on large groups
+    uint32_t cf_skip = 0;      // and for the closed forms of one query per batch
+    uint32_t d_gen = 0, d_gene = 0, d_fp = 0, d_fpe = 0, d_b1 = 0, d_b1e = 0, d_sat = 0, d_sate = 0, d_hz = 0, d_blk = 0, d_blke = 0, d_lean = 0, d_leane = 0;  // diagnostics
 
     for (;;) {
         uint32_t staged = ltail - lhead;
@@ -391,7 +400,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             if (a2) lkey[i2] = k2;
             rraw += w0 + w1 + w2;
             EST_CHECK(ltail - lhead <= SCAN_INRING);
-            wv::sync();
+            wv::sync_lds();
             continue;
         }
         if (staged == 0) {
@@ -483,7 +492,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                                     rend = ne; rcnt = ne > Tlast ? B : 0u; rslot = ns;
                                 }
                             }
-                            wv::sync();
+                            wv::sync_lds();
                             lhead += na;
                             ++d_sat; d_sate += na;
                             progress = true;
@@ -493,6 +502,49 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 }
                 if (nacc < 2) sat_skip = 4;
             }
+        }
+        if (cf_skip == 0 && L1 > 0 && (B == 1 || mono) && w >= 32 && R <= 31 && wv::ballot(rcnt > 0) == 0) {
+            // Closed forms for a whole window of queries that are each a batch of their own, checked with one
+            // vote and left to the steps below when they do not hold.  Query i runs on the replica that served
+            // query i-R (the table's entry i for the first R).
+            //   Nobody waits: every query finds that replica free again by the time it is ready, ready[i] >=
+            //   ready[i-R] + L(1) (for B > 1 no two queries may become ready together): end[i] = ready[i] + L(1).
+            //   Everybody waits (B = 1): ready[i] <= end[i-R], so end[i] = free[i mod R] + (i div R + 1) L(1), as
+            //   long as these ascend strictly (they do while the free times lie within one L(1) of each other;
+            //   equal completion times would have to be put in query order).
+            const bool final = staged <= 64 && rraw == in.wr && in.fin;
+            const uint64_t WM = lanes_below(w);
+            const uint32_t back = ln >= R && ln < w ? (uint32_t)(lkey[(lhead + ln - R) & (SCAN_INRING - 1)] >> 32) : 0u;
+            const uint32_t prev1 = ln < R ? rend : sat_add(back, L1);
+            uint64_t ok1 = WM & wv::ballot(prev1 <= rdy);
+            if (B > 1) ok1 &= wv::ballot(rdy != wv::shl1(rdy)) | ~lanes_below(w - 1u);
+            uint32_t m = 0, x = 0;
+            if (ok1 == WM) {
+                m = (B > 1 && !final) ? w - 1u : w;  // (for B > 1 the last query may yet be joined by the next)
+                x = sat_add(rdy, L1);
+            } else if (B == 1) {
+                const uint32_t kd = (ln * inv_r) >> 16, km = ln - kd * R;
+                const uint64_t st = (uint64_t)wv::shfl(rend, km) + (uint64_t)kd * L1;  // when my replica is free for me
+                const uint64_t en = st + L1;
+                x = en >= 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)en;
+                const uint32_t xp = wv::shr1(x);
+                if ((WM & ~(wv::ballot((uint64_t)rdy <= st) & wv::ballot(x != 0xFFFFFFFFu) & (wv::ballot(x > xp) | 1ull))) == 0) m = w;
+            }
+            if (m >= R && wv::bcast(x, m - 1u) != 0xFFFFFFFFu) {
+                if (ln < m) out[(wr + ln) & omask] = ((uint64_t)x << 32) | q;
+                wr += m;
+                space -= m;
+                EST_CHK_ORDER(9);
+                const uint32_t tnew = wv::shfl(x, ln + m - R);  // the table becomes the last R completion times
+                if (isrep) rend = tnew;
+                lhead += m;
+                ++d_b1; d_b1e += m;
+                progress = true;
+                continue;
+            }
+            cf_skip = 6;
+        } else if (cf_skip) {
+            --cf_skip;
         }
         const bool b1 = B == 1 && L1 > 0;
         // With larger batch sizes the same evaluation holds as long as no query waits and no two become
@@ -565,6 +617,78 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             }
         }
         if (single_skip) --single_skip;
+        if (mono && L1 > 0 && lean_skip == 0 && w >= 16) {
+            // Light load, large groups: the queries of a run (same ready time, at most B of them) are one batch,
+            // started at that time on a replica that is idle when the window's first query becomes ready.  When
+            // the new completion times ascend from run to run and all lie after every completion time already in
+            // the table, the table stays sorted by appending them, and the output order is settled by the table
+            // alone: the members of the new batches wait in their replicas' slots, and what leaves now are the older
+            // batches that finish before tau = (ready time of the first query after the accepted runs) + L(1),
+            // before which nothing dispatched later can finish.  Work per run, not per query, apart from moving
+            // the query indices.
+            const uint32_t r0 = wv::uniform(rdy);
+            const uint64_t WM = lanes_below(w);
+            const uint32_t rprev = wv::shr1(rdy);
+            const uint64_t heads = WM & (wv::ballot(rdy != rprev) | 1ull);
+            const bool final = staged <= 64 && rraw == in.wr && in.fin;
+            const uint32_t p = popc64(REP & wv::ballot(rend <= r0));  // idle now: a prefix of the sorted table
+            const uint32_t gid = wv::rank_below(heads >> 1);           // my run (lane 0 starts run 0)
+            uint32_t m = final ? w : 63u - (uint32_t)__builtin_clzll(heads);  // the last run may go on beyond the window
+            {
+                const uint64_t fits = WM & wv::ballot(gid < p);               // one idle replica per run
+                m = umin(m, fits == ~0ull ? 64u : ctz64(~fits));
+            }
+            const uint64_t AM = lanes_below(m);
+            const uint64_t hA = heads & AM;
+            const uint32_t G = popc64(hA);
+            bool done = false;
+            if (m >= 16 && 4u * G <= m) {
+                // my run: lanes [start, nh)
+                const uint64_t upto = below | (1ull << ln);
+                const uint32_t start = 63u - (uint32_t)__builtin_clzll((hA & upto) | 1ull);
+                const uint64_t later = ln == 63 ? 0ull : (hA >> (ln + 1));
+                const uint32_t nh = later ? ln + 1u + ctz64(later) : m;
+                const uint32_t g = nh - start;
+                const uint32_t e = sat_add(rdy, wv::shfl(Lmine, (g - 1u) & 63u));  // (L is 0 beyond B: rejected below)
+                const uint32_t eprev = wv::shr1(e);
+                const uint64_t bad = AM & (wv::ballot(g > B) | wv::ballot(e == 0xFFFFFFFFu) | (hA & ~1ull & wv::ballot(eprev >= e)));
+                const uint32_t e0 = wv::uniform(e), last_old = wv::bcast(rend, R - 1u);
+                if (bad == 0 && (G == R || e0 > last_old)) {
+                    const bool tau_inf = final && m >= w;
+                    const uint32_t tau = tau_inf ? 0xFFFFFFFFu : sat_add(wv::bcast(rdy, umin(m, w - 1u)), L1);
+                    const uint64_t E = wv::ballot(rcnt > 0) & (tau_inf ? ~0ull : wv::ballot(rend < tau));
+                    if (E && !scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress)) break;  // wait for the consumer
+                    EST_CHK_ORDER(8);
+                    wv::sync_lds();  // the slots of batches just written out may be taken again
+                    const uint32_t myslot = wv::shfl(rslot, gid);
+                    if (ln < m) lslots[myslot * bm + (ln - start)] = q;
+                    if (ln < m && ln == start) { ltab[gid] = e; ltab[64 + gid] = g; }
+                    wv::sync_lds();
+                    // new table: the entries not taken move down, the new batches follow in run order
+                    const uint32_t keep = R - G;
+                    const uint32_t oe = wv::shfl(rend, ln + G), oc = wv::shfl(rcnt, ln + G), os = wv::shfl(rslot, ln + G);
+                    const uint32_t k = ln >= keep && ln < R ? ln - keep : 0u;
+                    const uint32_t ns = wv::shfl(rslot, k);
+                    const uint32_t ne = ltab[k], nc = ltab[64 + k];
+                    if (isrep) {
+                        if (ln < keep) {
+                            rend = oe; rcnt = oc; rslot = os;
+                        } else {
+                            rend = ne; rcnt = nc; rslot = ns;
+                        }
+                    }
+                    wv::sync_lds();
+                    lhead += m;
+                    ++d_lean; d_leane += m;
+                    progress = true;
+                    done = true;
+                }
+            }
+            if (done) continue;
+            lean_skip = 4;
+        } else if (lean_skip) {
+            --lean_skip;
+        }
         if (mono && fp_skip == 0) {
             // Light load: as long as every group of queries that become ready at the same instant
             // finds an idle replica at that instant and fits one batch, each group is one batch started
@@ -596,7 +720,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 const uint32_t rid = wv::rank_below(runs >> 1);  // my run (lane 0 always starts one)
                 if (ln < w && (ln == 0 || rdy != rprev)) lstart[rid] = ln;
                 if (ln == 0) lstart[nruns] = w;
-                wv::sync();
+                wv::sync_lds();
                 uint64_t heads = runs;
                 uint32_t bid = rid, start = lstart[rid], nh = lstart[rid + 1u];
                 const uint32_t rlen = ln < nruns ? lstart[ln + 1u] - lstart[ln] : 0u;
@@ -615,7 +739,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 const uint32_t e = sat_add(rdy, wv::shfl(Lmine, g - 1));       // (L is 0 beyond B: rejected below)
                 uint32_t *lrdy = ltab + 192;                                   // per group: ready time
                 if (ln < w && ln == start) { lend[bid] = e; lg[bid] = g; lrdy[bid] = rdy; }
-                wv::sync();
+                wv::sync_lds();
                 // replicas that serve the run: the table's first p entries, each free by the time its turn
                 // comes (group l takes entry l); later groups take the replica of the group p before them
                 const uint32_t ngroups = popc64(heads);
@@ -725,7 +849,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                         const bool waits = ln < m && !safe;
                         if (waits) lslots[myslot * bm + (ln - start)] = q;
                         if (ln < m && ln == start) luns[bid] = waits ? 1u : 0u;
-                        wv::sync();
+                        wv::sync_lds();
                         // new table: every idle replica that served a group holds its last group's completion
                         // time (and its members, if they wait); then everything is put back in order of time
                         const uint32_t nb = popc64(heads & lanes_below(m));      // groups accepted
@@ -751,11 +875,11 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                                 const uint32_t ej = wv::bcast(cend, j);
                                 if (ej < cend || (ej == cend && j < ln)) ++trank;
                             }
-                            wv::sync();  // (the per-group values in this area have been read)
+                            wv::sync_lds();  // (the per-group values in this area have been read)
                             if (isrep) { ltab[trank] = cend; ltab[64 + trank] = ccnt; ltab[128 + trank] = cslot; }
-                            wv::sync();
+                            wv::sync_lds();
                             if (isrep) { rend = ltab[ln]; rcnt = ltab[64 + ln]; rslot = ltab[128 + ln]; }
-                            wv::sync();
+                            wv::sync_lds();
                         }
                         lhead += m;
                         progress = true;
@@ -861,7 +985,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                     wr += nsafe + extra;
                     space -= nsafe + extra;
                     EST_CHK_ORDER(7);
-                    wv::sync();  // the slots of woven batches have been read: they may be written again
+                    wv::sync_lds();  // the slots of woven batches have been read: they may be written again
                     // members of batches that wait go to their replica's slot, sorted by query index
                     const uint64_t waitm = AM & ~safem;
                     uint32_t qs = q;
@@ -878,7 +1002,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                         rslot = tinfo & 0xFFu;
                         rcnt = tk == 0xFFu ? ((late || trend >= ecap) ? tinfo >> 16 : 0u) : (late ? bsz : 0u);
                     }
-                    wv::sync();
+                    wv::sync_lds();
                     lhead += a;
                     ++d_blk; d_blke += a;
                     progress = true;
@@ -932,16 +1056,11 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     }
 
     if (DIAG && c.a->dbg_ticks && ln == 0) {
-        uint64_t *dc = c.a->status->dbg_cnt;
-        wv::atomic_add_u64(dc + 0, d_gen); wv::atomic_add_u64(dc + 1, d_fp); wv::atomic_add_u64(dc + 2, d_fpe);
-        wv::atomic_add_u64(dc + 3, d_b1); wv::atomic_add_u64(dc + 4, d_b1e); wv::atomic_add_u64(dc + 7, 1);
-        wv::atomic_add_u64(dc + 8 + s, d_gen); wv::atomic_add_u64(dc + 8 + EST_MAX_STAGES + s, d_gene);
-        wv::atomic_add_u64(dc + 8 + 2 * EST_MAX_STAGES + s, d_fpe + d_b1e + d_sate + d_hz + d_blke);
-        wv::atomic_add_u64(dc + 8 + 4 * EST_MAX_STAGES + 3, d_sat); wv::atomic_add_u64(dc + 8 + 4 * EST_MAX_STAGES + 4, d_sate);
-        wv::atomic_add_u64(dc + 8 + 4 * EST_MAX_STAGES + 5, d_hz);
-        wv::atomic_add_u64(dc + 8 + 4 * EST_MAX_STAGES + 6, d_blk); wv::atomic_add_u64(dc + 8 + 4 * EST_MAX_STAGES + 7, d_blke);
-        uint64_t *pc = c.a->dbg_ticks + c.a->n_cfg + ((uint64_t)c.t * EST_MAX_STAGES + s) * 4;  // per candidate and stage
-        pc[0] += d_gen; pc[2] += d_fp + d_b1 + d_sat + d_blk; pc[3] += d_fpe + d_b1e + d_sate + d_hz + d_blke;
+        uint64_t *pc = est_dbg_rec(c.a, c.t, s);  // per candidate and stage (one writer: no atomics)
+        pc[0] += d_gen; pc[2] += d_fp + d_b1 + d_sat + d_blk + d_lean; pc[3] += d_fpe + d_b1e + d_sate + d_hz + d_blke + d_leane;
+        pc[4] += d_leane; pc[5] += d_fpe; pc[6] += d_b1e; pc[7] += d_blke;
+        uint64_t *po = est_dbg_rec(c.a, c.t, EST_MAX_STAGES - 1);
+        po[6] += 1; po[7] += d_gene;
     }
     // back to memory: the table, the members still waiting, the cursors
     if (isrep) {
@@ -1003,6 +1122,8 @@ EST_DEV uint64_t eff_key(uint64_t key, uint32_t j, uint32_t l) {
     return (uint32_t)(key >> 32) == 0xFFFFFFFFu ? (0xFFFFFFFF00000000ull | (uint64_t)(j << 8) | l) : key;
 }
 
+enum { MERGE_RING = 128, MERGE_GROUP = 4 };  // staged elements per source of a merge (LDS ring); sources whose loads are issued together
+
 template <bool DIAG, bool MEMO>
 EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     const uint32_t ln = wv::lane();
@@ -1010,18 +1131,6 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     const uint32_t K = wv::uniform(op.n_src);
     const bool is_lat = wv::uniform(op.type) == EST_OP_LAT;
     const uint8_t *acc = c.a->acc + (uint64_t)op.acc_idx * c.a->acc_stride;
-    uint8_t *cnt = c.cnt + op.cnt_off;
-    uint64_t *skey = c.lds;
-    uint64_t *merged = c.lds + P.max_src * 64;
-    uint32_t *spos = (uint32_t *)(c.lds + 2 * P.max_src * 64);
-    const uint64_t below = lanes_below(ln);
-
-    // small per-source tables (the same values in every lane) kept in LDS rather than in private memory
-    uint32_t *raw = spos + P.max_src * 64, *nst = raw + EST_KMAX, *cur = nst + EST_KMAX, *m_src = cur + EST_KMAX;
-    uint32_t *dupc = m_src + EST_KMAX;  // EST_DUP_BUCKETS counters: queries of a window per hash bucket (zero between windows)
-    if (op.has_cnt)
-        for (uint32_t i = ln; i < EST_DUP_BUCKETS; i += 64) dupc[i] = 0;
-    for (uint32_t j = 0; j < K; ++j) raw[j] = c.st[P.rd_off + op.src_edge[j]];
     uint64_t *out = nullptr;
     uint32_t omask = 0, wr, space = 0xFFFFFFFFu;
     if (is_lat) {
@@ -1034,205 +1143,277 @@ EST_DEV bool merge_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         space = wv::uniform(ring_space(c, op.out_ring, wr));
     }
     uint32_t miss = 0;
+    uint32_t d_rounds = 0, d_elems = 0;  // diagnostics
     bool progress = false, finished = false;
 
     if (K == 1 && !op.has_cnt) {
-        // one source, every query fed by it alone: filter and copy, window by window
+        // one source, every query fed by it alone: filter and copy, four windows of 64 at a time (their
+        // loads are issued together)
         const View sv = uniform_view_of<MEMO>(c, op.src_ring[0]);
-        uint32_t rc = wv::uniform(raw[0]);
+        uint32_t rc = wv::uniform(c.st[P.rd_off + op.src_edge[0]]);
+        const uint32_t slo = wv::uniform(c.a->slo_us);
         for (;;) {
-            if (!is_lat && space < 64u) break;  // wait for the consumer
+            if (!is_lat && space < 256u) break;  // wait for the consumer
             if (rc == sv.wr) {
                 finished = sv.fin != 0;
                 break;
             }
-            const uint32_t w = umin(64u, sv.wr - rc);
-            const uint64_t key = ln < w ? sv.base[(rc + ln) & sv.mask] : 0ull;
-            const uint32_t q = (uint32_t)key;
-            const bool fa = (acc[q] & 1u) != 0u;  // (idle lanes look at query 0)
-            const uint64_t A = lanes_below(w) & wv::ballot(fa);
-            const bool a = ln < w && fa;
-            const uint32_t pos = wr + wv::rank_below(A);
-            if (a) {
-                if (is_lat) {
-                    const uint32_t l = (uint32_t)(key >> 32) - c.a->arrival[q];
-                    c.lat[c.a->lat_by_qid ? q : pos] = l;
-                    miss += l > c.a->slo_us;
-                } else {
-                    out[pos & omask] = key;
-                }
+            const uint32_t left = sv.wr - rc;
+            uint64_t key[4];
+            uint32_t av[4], arr[4];
+EST_UNROLL
+            for (uint32_t u = 0; u < 4; ++u) key[u] = u * 64u + ln < left ? sv.base[(rc + u * 64u + ln) & sv.mask] : 0ull;
+EST_UNROLL
+            for (uint32_t u = 0; u < 4; ++u) av[u] = acc[(uint32_t)key[u]];  // (idle lanes look at query 0)
+            if (is_lat) {
+EST_UNROLL
+                for (uint32_t u = 0; u < 4; ++u) arr[u] = c.a->arrival[(uint32_t)key[u]];
             }
-            const uint32_t na = popc64(A);
-            wr += na;
-            if (!is_lat) space -= na;
-            rc += w;
-            progress = true;
-        }
-        raw[0] = rc;
-    } else
-    for (;;) {
-        if (!is_lat && space < 64u * K) break;  // wait for the consumer
-        // ---- stage up to 64 accepted elements of every source
-        uint32_t more = 0;  // bit j: elements beyond the staged ones may exist in source j
-        for (uint32_t j = 0; j < K; ++j) {
-            const View sv = uniform_view_of<MEMO>(c, op.src_ring[j]);
-            uint32_t n = 0, rc = wv::uniform(raw[j]);
-            while (n < 64 && rc != sv.wr) {
-                const uint32_t w = umin(64u, sv.wr - rc);
-                const uint64_t key = ln < w ? sv.base[(rc + ln) & sv.mask] : 0ull;
-                const bool a = ln < w && ((acc[(uint32_t)key] >> j) & 1u);
+EST_UNROLL
+            for (uint32_t u = 0; u < 4; ++u) {
+                const bool a = u * 64u + ln < left && (av[u] & 1u) != 0u;
                 const uint64_t A = wv::ballot(a);
-                const uint32_t room = 64 - n;
-                const uint32_t myrank = wv::rank_below(A);
-                if (a && myrank < room) {
-                    skey[j * 64 + n + myrank] = key;
-                    spos[j * 64 + n + myrank] = rc + ln;
+                const uint32_t pos = wr + wv::rank_below(A);
+                if (a) {
+                    if (is_lat) {
+                        const uint32_t l = (uint32_t)(key[u] >> 32) - arr[u];
+                        c.lat[c.a->lat_by_qid ? (uint32_t)key[u] : pos] = l;
+                        miss += l > slo;
+                    } else {
+                        out[pos & omask] = key[u];
+                    }
                 }
                 const uint32_t na = popc64(A);
-                if (na <= room) {
-                    n += na;
-                    rc += w;
-                } else {
-                    // the first accepted element that did not fit is read again next time
-                    uint64_t rest = A;
-                    for (uint32_t i = 0; i < room; ++i) rest &= rest - 1;
-                    rc += ctz64(rest);
-                    n = 64;
+                wr += na;
+                if (!is_lat) space -= na;
+            }
+            rc += umin(left, 256u);
+            progress = true;
+        }
+        if (ln == 0) c.st[P.rd_off + op.src_edge[0]] = rc;
+    } else {
+        // Several sources.  A query fed by several of them is ready at the largest of its times: of its
+        // elements only the one with the largest key (time, query; equal times: the higher source) is passed
+        // on.  Every accepted element leaves its time in its source's table when it is staged; an entry
+        // still unset reads as the horizon.  Sources are consumed in key order, so when an element is
+        // consumed every element of the same query with a smaller key has been staged already, and an
+        // element whose partner is unset or larger is not the last.  No counting, no read-modify-write.
+        //
+        // LDS: per source a ring of MERGE_RING staged keys (uint64) | per source 64 passed-on keys (uint64) |
+        // per source MERGE_RING accept masks (uint8) | per-source scalars (uint32 [12][EST_KMAX]).
+        const uint32_t KS = P.max_src;
+        uint64_t *rkey = c.lds;
+        uint64_t *lst = c.lds + KS * MERGE_RING;
+        uint8_t *racc = (uint8_t *)(lst + KS * 64);
+        uint32_t *sc = (uint32_t *)(racc + KS * MERGE_RING);
+        uint32_t *s_rd = sc, *s_wr = sc + EST_KMAX, *s_fin = sc + 2 * EST_KMAX, *s_head = sc + 3 * EST_KMAX, *s_tail = sc + 4 * EST_KMAX,
+                 *s_mask = sc + 5 * EST_KMAX, *s_blo = sc + 6 * EST_KMAX, *s_bhi = sc + 7 * EST_KMAX, *nst = sc + 8 * EST_KMAX,
+                 *nfin = sc + 9 * EST_KMAX, *m_src = sc + 10 * EST_KMAX;
+        const uint32_t tab_mask = wv::uniform(op.tab_mask), tab_len = wv::uniform(op.tab_len);
+        uint32_t *tab0 = (uint32_t *)(c.tab + op.tab_off);
+        for (uint32_t j = 0; j < K; ++j) {
+            const View sv = view_of<MEMO>(c, op.src_ring[j]);
+            if (ln == 0) {
+                s_rd[j] = c.st[P.rd_off + op.src_edge[j]];
+                s_wr[j] = sv.wr; s_fin[j] = sv.fin; s_mask[j] = sv.mask;
+                s_blo[j] = (uint32_t)(uintptr_t)sv.base; s_bhi[j] = (uint32_t)((uint64_t)(uintptr_t)sv.base >> 32);
+                s_head[j] = 0; s_tail[j] = 0; nst[j] = 0;
+            }
+        }
+        wv::sync_lds();
+        for (;;) {
+            if (!is_lat && space < 64u * K) break;  // wait for the consumer
+            // ---- refill: every source with no more than a window staged takes up to 64 further elements; the
+            //      loads of all sources are issued before any is used
+            bool any = false;
+            for (uint32_t j0 = 0; j0 < K; j0 += MERGE_GROUP) {
+                uint64_t kx[MERGE_GROUP];
+                uint32_t wx[MERGE_GROUP], ax[MERGE_GROUP];
+                bool some = false;
+EST_UNROLL
+                for (uint32_t u = 0; u < MERGE_GROUP; ++u) {
+                    const uint32_t j = j0 + u;
+                    wx[u] = 0;
+                    kx[u] = 0;
+                    if (j < K) {
+                        const uint32_t staged = wv::uniform(s_tail[j]) - wv::uniform(s_head[j]);
+                        const uint32_t rd = wv::uniform(s_rd[j]), left = wv::uniform(s_wr[j]) - rd;
+                        if (staged <= 64u && left > 0u) {
+                            const uint64_t *base = (const uint64_t *)(uintptr_t)(((uint64_t)wv::uniform(s_bhi[j]) << 32) | wv::uniform(s_blo[j]));
+                            const uint32_t smask = wv::uniform(s_mask[j]);
+                            wx[u] = umin(64u, left);
+                            if (ln < wx[u]) kx[u] = base[(rd + ln) & smask];
+                            some = true;
+                        }
+                    }
+                }
+                if (!some) continue;
+                any = true;
+EST_UNROLL
+                for (uint32_t u = 0; u < MERGE_GROUP; ++u) ax[u] = (wx[u] && ln < wx[u]) ? acc[(uint32_t)kx[u]] : 0u;
+EST_UNROLL
+                for (uint32_t u = 0; u < MERGE_GROUP; ++u) {
+                    const uint32_t j = j0 + u;
+                    if (!wx[u]) continue;
+                    uint32_t am = ax[u];
+                    if (!((am >> j) & 1u)) am = 0;  // not for this stage, or superseded by a nearer ancestor
+                    if (((tab_mask >> j) & 1u) && (am & (am - 1u)))
+                        tab0[(uint64_t)__builtin_popcount(tab_mask & ((1u << j) - 1u)) * tab_len + (uint32_t)kx[u]] = (uint32_t)(kx[u] >> 32);
+                    const uint32_t at = j * MERGE_RING + ((wv::uniform(s_tail[j]) + ln) & (MERGE_RING - 1u));
+                    if (ln < wx[u]) {
+                        rkey[at] = kx[u];
+                        racc[at] = (uint8_t)am;
+                    }
+                    if (ln == 0) { nst[j] = wx[u]; }  // (added to the cursors below, once the ring positions have been read)
                 }
             }
-            nst[j] = n;
-            cur[j] = rc;
-            if (!(rc == sv.wr && sv.fin)) more |= 1u << j;
-        }
-        wv::sync();
-        // ---- everything up to the smallest "last staged key" of a source that may have more is final
-        uint64_t bound = ~0ull;
-        bool blocked = false;
-        uint32_t staged_total = 0;
-        for (uint32_t j = 0; j < K; ++j) {
-            const uint32_t nj = wv::uniform(nst[j]);
-            staged_total += nj;
-            if (!((more >> j) & 1u)) continue;
-            if (nj == 0) {
-                blocked = true;
-            } else {
-                const uint64_t lk = skey[j * 64 + nj - 1];
-                const uint64_t last = eff_key(((uint64_t)wv::uniform((uint32_t)(lk >> 32)) << 32) | wv::uniform((uint32_t)lk), j, nj - 1);
-                bound = last < bound ? last : bound;
+            if (any) {
+                wv::sync();  // (tables and staged elements: written above, read below by other lanes)
+                if (ln == 0)
+                    for (uint32_t j = 0; j < K; ++j) { s_tail[j] += nst[j]; s_rd[j] += nst[j]; nst[j] = 0; }
+                wv::sync_lds();
             }
-        }
-        if (blocked || staged_total == 0) {
-            if (!blocked) finished = more == 0;
-            break;
-        }
-        // ---- rank every staged element up to the bound among all staged elements
-        uint32_t m_total = 0;
-        bool clamped = false;  // some staged key sits at the horizon (a source's keys ascend: look at its last)
-        for (uint32_t j = 0; j < K; ++j) {
-            const uint32_t nj = wv::uniform(nst[j]);
-            clamped = clamped || (nj > 0 && wv::uniform((uint32_t)(skey[j * 64 + nj - 1u] >> 32)) == 0xFFFFFFFFu);
-        }
-        for (uint32_t j = 0; j < K; ++j) {
-            const uint32_t nj = wv::uniform(nst[j]);
-            const bool have = ln < nj;
-            const uint64_t rk = have ? skey[j * 64 + ln] : 0ull;
-            const uint64_t x = eff_key(rk, j, ln);
-            const bool emit = have && x <= bound;
-            const uint32_t mj = popc64(lanes_below(nj) & wv::ballot(x <= bound));
-            m_src[j] = mj;
-            if (emit) {
+            // ---- the window of every source: its first 64 staged elements
+            uint32_t more = 0, total = 0;  // more, bit j: source j may hold elements beyond its window
+            bool blocked = false, clamped = false;
+            uint64_t bound = ~0ull;  // everything up to the smallest last key of a source that may hold more is final
+            for (uint32_t j = 0; j < K; ++j) {
+                const uint32_t h = wv::uniform(s_head[j]), staged = wv::uniform(s_tail[j]) - h;
+                const uint32_t w = umin(64u, staged);
+                const bool has_more = staged > 64u || wv::uniform(s_rd[j]) != wv::uniform(s_wr[j]) || !wv::uniform(s_fin[j]);
+                if (has_more) more |= 1u << j;
+                total += w;
+                if (w == 0) {
+                    blocked = blocked || has_more;
+                } else {
+                    const uint64_t lk = rkey[j * MERGE_RING + ((h + w - 1u) & (MERGE_RING - 1u))];
+                    const uint32_t tl = wv::uniform((uint32_t)(lk >> 32)), ql = wv::uniform((uint32_t)lk);
+                    clamped = clamped || tl == 0xFFFFFFFFu;
+                    if (has_more) {
+                        const uint64_t last = eff_key(((uint64_t)tl << 32) | ql, j, w - 1u);
+                        bound = last < bound ? last : bound;
+                    }
+                }
+            }
+            if (blocked || total == 0) {
+                if (!blocked) finished = more == 0;
+                break;
+            }
+            // ---- which of the consumed elements are passed on (the table look-ups of all sources are issued together)
+            uint32_t n_out = 0;
+            for (uint32_t j0 = 0; j0 < K; j0 += MERGE_GROUP) {
+                uint64_t kx[MERGE_GROUP];
+                uint32_t amx[MERGE_GROUP], t2x[MERGE_GROUP];
+                bool px[MERGE_GROUP];
+                uint32_t hard = 0;  // bit u: some element of the source has more than one partner
+EST_UNROLL
+                for (uint32_t u = 0; u < MERGE_GROUP; ++u) {
+                    const uint32_t j = j0 + u;
+                    kx[u] = 0; amx[u] = 0; t2x[u] = 0; px[u] = false;
+                    if (j < K) {
+                        const uint32_t w = umin(64u, wv::uniform(s_tail[j]) - wv::uniform(s_head[j]));
+                        const uint32_t at = j * MERGE_RING + ((wv::uniform(s_head[j]) + ln) & (MERGE_RING - 1u));
+                        if (ln < w) { kx[u] = rkey[at]; amx[u] = racc[at]; }
+                        const uint64_t x = clamped ? eff_key(kx[u], j, ln) : kx[u];
+                        const bool consumed = ln < w && x <= bound;  // a prefix of the window: a source's keys ascend
+                        const uint32_t mj = popc64(wv::ballot(consumed));
+                        if (ln == 0) m_src[j] = mj;
+                        px[u] = consumed && amx[u] != 0u;
+                        const uint32_t others = amx[u] & ~(1u << j);
+                        if (px[u] && others != 0u) {
+                            const uint32_t j2 = (uint32_t)__builtin_ctz(others);
+                            t2x[u] = tab0[(uint64_t)__builtin_popcount(tab_mask & ((1u << j2) - 1u)) * tab_len + (uint32_t)kx[u]];
+                        }
+                        if (wv::ballot(px[u] && (others & (others - 1u)) != 0u)) hard |= 1u << u;
+                    }
+                }
+EST_UNROLL
+                for (uint32_t u = 0; u < MERGE_GROUP; ++u) {
+                    const uint32_t j = j0 + u;
+                    if (j < K) {
+                        const uint32_t t = (uint32_t)(kx[u] >> 32);
+                        const uint32_t others = amx[u] & ~(1u << j);
+                        bool pass = px[u];
+                        if (pass && others != 0u) {
+                            const uint32_t j2 = (uint32_t)__builtin_ctz(others);
+                            if (!(t2x[u] < t || (t2x[u] == t && j2 < j))) pass = false;
+                        }
+                        if ((hard >> u) & 1u) {  // more than two parents: the remaining partners one by one
+                            for (uint32_t j2 = 0; j2 < K; ++j2) {
+                                const bool need = pass && j2 != j && ((others >> j2) & 1u);
+                                if (!wv::ballot(need)) continue;
+                                const uint32_t t2 = need ? tab0[(uint64_t)__builtin_popcount(tab_mask & ((1u << j2) - 1u)) * tab_len + (uint32_t)kx[u]] : 0u;
+                                if (need && !(t2 < t || (t2 == t && j2 < j))) pass = false;
+                            }
+                        }
+                        const uint64_t F = wv::ballot(pass);
+                        const uint32_t fr = wv::rank_below(F);
+                        if (pass) lst[j * 64 + fr] = kx[u];
+                        if (ln == 0) nfin[j] = popc64(F);
+                        n_out += popc64(F);
+                    }
+                }
+            }
+            ++d_rounds; d_elems += n_out;
+            wv::sync_lds();
+            // ---- place every passed-on element: its rank in its own list plus the smaller elements of the others
+            for (uint32_t j = 0; j < K; ++j) {
+                const uint32_t nf = wv::uniform(nfin[j]);
+                if (nf == 0) continue;
+                const bool have = ln < nf;
+                const uint64_t rk = have ? lst[j * 64 + ln] : 0ull;
                 uint32_t rank = ln;
                 for (uint32_t j2 = 0; j2 < K; ++j2) {
-                    if (j2 == j) continue;
-                    uint32_t lo = 0, hi = nst[j2];
+                    const uint32_t n2 = wv::uniform(nfin[j2]);
+                    if (j2 == j || n2 == 0) continue;
+                    const uint64_t *l2 = lst + j2 * 64;
+                    uint32_t lo = 0;  // elements of list j2 below rk (no two lists hold the same key: one element per query is passed on)
                     if (!clamped) {
-                        // (keys of different sources never coincide: a query appears once per source, and
-                        // equal keys mean the same query)  -- ties are still broken by source for safety
-                        while (lo < hi) {
-                            const uint32_t mid = (lo + hi) >> 1;
-                            const uint64_t y = skey[j2 * 64 + mid];
-                            if (y < rk || (y == rk && j2 < j)) lo = mid + 1; else hi = mid;
+EST_UNROLL
+                        for (uint32_t step = 64; step >= 1; step >>= 1) {
+                            const uint32_t i = lo + step;
+                            const bool in = i <= n2;
+                            const uint64_t y = l2[in ? i - 1u : 0u];
+                            if (in && y < rk) lo = i;
                         }
                     } else {
-                        while (lo < hi) {
-                            const uint32_t mid = (lo + hi) >> 1;
-                            const uint64_t y = eff_key(skey[j2 * 64 + mid], j2, mid);
-                            if (y < x || (y == x && j2 < j)) lo = mid + 1; else hi = mid;
+                        const uint64_t x = eff_key(rk, j, ln);
+                        for (uint32_t step = 64; step >= 1; step >>= 1) {
+                            const uint32_t i = lo + step;
+                            const bool in = i <= n2;
+                            const uint64_t y = eff_key(l2[in ? i - 1u : 0u], j2, in ? i - 1u : 0u);
+                            if (in && y < x) lo = i;
                         }
                     }
                     rank += lo;
                 }
-                EST_CHECK(rank < P.max_src * 64);
-                merged[rank] = rk;
-            }
-            m_total += mj;
-        }
-        EST_CHECK(m_total >= 1);
-        if (DIAG && c.a->dbg_ticks && ln == 0) { wv::atomic_add_u64(c.a->status->dbg_cnt + 5, 1); wv::atomic_add_u64(c.a->status->dbg_cnt + 6, m_total); }
-        wv::sync();
-        // ---- walk the merged run; a query fed by several sources is passed on at its last appearance
-        for (uint32_t base = 0; base < m_total; base += 64) {
-            const bool valid = base + ln < m_total;
-            const uint64_t key = valid ? merged[base + ln] : 0ull;
-            const uint32_t q = (uint32_t)key;
-            bool emitf = valid;
-            if (op.has_cnt) {
-                const uint32_t e = valid ? (uint32_t)__builtin_popcount(acc[q]) : 0u;
-                const bool multi = e > 1;
-                const uint64_t MM = wv::ballot(multi);
-                if (MM) {
-                    const uint32_t c0 = multi ? cnt[q] : 0u;
-                    uint32_t duprank = 0, duptotal = 1;
-                    // Only a query that appears twice in this window needs its appearances counted
-                    // together.  Candidates: lanes that share a hash bucket with another lane.
-                    const uint32_t hb = q & (EST_DUP_BUCKETS - 1u);
-                    if (multi) wv::lds_add(&dupc[hb], 1u);
-                    wv::sync();
-                    const uint32_t shared = multi ? dupc[hb] : 0u;
-                    wv::sync();
-                    if (multi) dupc[hb] = 0;
-                    for (uint64_t todo = wv::ballot(shared > 1u); todo;) {
-                        const uint32_t l = ctz64(todo);
-                        const uint32_t sq = wv::bcast(q, l);
-                        const uint64_t same = MM & wv::ballot(q == sq);
-                        if (multi && q == sq) {
-                            duprank = popc64(same & below);
-                            duptotal = popc64(same);
-                        }
-                        todo &= ~same;
+                if (have) {
+                    const uint32_t pos = wr + rank;
+                    if (is_lat) {
+                        const uint32_t q = (uint32_t)rk;
+                        const uint32_t l = (uint32_t)(rk >> 32) - c.a->arrival[q];
+                        c.lat[c.a->lat_by_qid ? q : pos] = l;
+                        miss += l > c.a->slo_us;
+                    } else {
+                        out[pos & omask] = rk;
                     }
-                    const uint32_t newc = c0 + duprank + 1;
-                    if (multi) {
-                        EST_CHECK(newc <= e);
-                        emitf = newc == e;
-                        if (duprank == duptotal - 1) cnt[q] = (uint8_t)newc;
-                    }
-                    wv::sync();
                 }
             }
-            const uint64_t Em = wv::ballot(emitf);
-            const uint32_t pos = wr + wv::rank_below(Em);
-            if (emitf) {
-                if (is_lat) {
-                    const uint32_t l = (uint32_t)(key >> 32) - c.a->arrival[q];
-                    c.lat[c.a->lat_by_qid ? q : pos] = l;
-                    miss += l > c.a->slo_us;
-                } else {
-                    out[pos & omask] = key;
-                }
-            }
-            wr += popc64(Em);
+            wr += n_out;
+            if (!is_lat) space -= n_out;  // (nobody consumes while this operation runs)
+            if (ln == 0)
+                for (uint32_t j = 0; j < K; ++j) s_head[j] += m_src[j];
+            progress = true;
+            wv::sync_lds();
         }
-        if (!is_lat) space = ring_space(c, op.out_ring, wr);
-        // ---- consumed: everything emitted; what was staged but not emitted is read again
-        for (uint32_t j = 0; j < K; ++j) raw[j] = m_src[j] < nst[j] ? spos[j * 64 + m_src[j]] : cur[j];
-        progress = true;
-        wv::sync();
+        // staged but not consumed: read again next time
+        if (ln == 0)
+            for (uint32_t j = 0; j < K; ++j) c.st[P.rd_off + op.src_edge[j]] = s_rd[j] - (s_tail[j] - s_head[j]);
     }
 
+    if (DIAG && c.a->dbg_ticks && ln == 0) { uint64_t *po = est_dbg_rec(c.a, c.t, EST_MAX_STAGES - 1); po[3] += d_rounds; po[4] += d_elems; po[5] += 1; }
     const uint32_t miss_all = is_lat ? wv::sum_u32(miss) : 0u;
     if (ln == 0) {
-        for (uint32_t j = 0; j < K; ++j) c.st[P.rd_off + op.src_edge[j]] = raw[j];
         if (is_lat) {
             c.st[P.miss_off + 1] = wr;
             c.st[P.miss_off] += miss_all;
@@ -1264,7 +1445,7 @@ EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *
     c.rings = a.rings + (uint64_t)slot * a.ring_stride;
     c.rep = a.rep + (uint64_t)slot * a.rep_stride;
     c.slots = a.slots + (uint64_t)slot * a.slot_stride;
-    c.cnt = a.counters + (uint64_t)slot * a.cnt_stride;
+    c.tab = a.tabs + (uint64_t)slot * a.tab_stride;
     c.lat = a.lat + (uint64_t)(a.lat_by_qid ? t : slot) * a.lat_stride;
     c.cfg = a.cfg + (uint64_t)t * a.dag->S;
     c.lds = lds;
@@ -1278,8 +1459,8 @@ EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *
         if (op.type == EST_OP_SCAN && ln < op.r_max) c.rep[op.rep_off + 2 * op.r_max + ln] = ln;
     }
     {
-        uint32_t *cw = (uint32_t *)c.cnt;
-        for (uint64_t i = ln; i < a.cnt_stride / 4; i += 64) cw[i] = 0;
+        uint32_t *tw = (uint32_t *)c.tab;  // no element of any joined stream has been looked at yet
+        for (uint64_t i = ln; i < a.tab_stride / 4; i += 64) tw[i] = 0xFFFFFFFFu;
     }
     wv::sync();
     c.memo_rings = 0;
@@ -1318,11 +1499,9 @@ EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *
             const uint64_t k0 = (DIAG && a.dbg_ticks) ? wv::ticks() : 0;
             bool p = op.type == EST_OP_SCAN ? scan_run<DIAG, MEMO>(c, op, opi) : merge_run<DIAG, MEMO>(c, op, opi);
             if (DIAG && a.dbg_ticks && ln == 0) {
-                const uint32_t at = op.type == EST_OP_SCAN ? 8 + 3 * EST_MAX_STAGES + op.stage
-                                                           : 8 + 4 * EST_MAX_STAGES + (op.type == EST_OP_LAT ? 1 : 0);
                 const uint64_t dt = wv::ticks() - k0;
-                wv::atomic_add_u64(a.status->dbg_cnt + at, dt);
-                if (op.type == EST_OP_SCAN) a.dbg_ticks[a.n_cfg + ((uint64_t)t * EST_MAX_STAGES + op.stage) * 4 + 1] += dt;  // per candidate and stage
+                if (op.type == EST_OP_SCAN) est_dbg_rec(&a, t, op.stage)[1] += dt;
+                else est_dbg_rec(&a, t, EST_MAX_STAGES - 1)[op.type == EST_OP_LAT ? 1 : 0] += dt;
             }
             progress = progress || p;
             alldone = alldone && wv::uniform(c.st[P.done_off + opi]) != 0;
@@ -1358,13 +1537,21 @@ EST_DEV void select_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_
     for (int pass = 3; pass >= 0; --pass) {
         const uint32_t shift = (uint32_t)pass * 8;
         for (uint32_t i = ln; i < 256; i += 64) hist[i] = 0;
-        wv::sync();
-        for (uint32_t i = ln; i < n; i += 64) {
-            const uint32_t v = lat[i];
-            const bool match = pass == 3 || (v >> (shift + 8)) == (prefix >> (shift + 8));
-            if (match) wv::lds_add(&hist[(v >> shift) & 255u], 1u);
+        wv::sync_lds();
+        for (uint32_t i0 = 0; i0 < n; i0 += 512) {  // eight loads in flight per lane
+            uint32_t v[8];
+EST_UNROLL
+            for (uint32_t u = 0; u < 8; ++u) {
+                const uint32_t i = i0 + u * 64u + ln;
+                v[u] = i < n ? lat[i] : 0u;
+            }
+EST_UNROLL
+            for (uint32_t u = 0; u < 8; ++u) {
+                const bool match = i0 + u * 64u + ln < n && (pass == 3 || (v[u] >> (shift + 8)) == (prefix >> (shift + 8)));
+                if (match) wv::lds_add(&hist[(v[u] >> shift) & 255u], 1u);
+            }
         }
-        wv::sync();
+        wv::sync_lds();
         // lane l owns bins 4l .. 4l+3
         const uint32_t h0 = hist[4 * ln], h1 = hist[4 * ln + 1], h2 = hist[4 * ln + 2], h3 = hist[4 * ln + 3];
         const uint32_t mine = h0 + h1 + h2 + h3;
@@ -1383,7 +1570,7 @@ EST_DEV void select_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_
         digit = wv::bcast(digit, hl);
         k = wv::bcast(kk, hl);
         prefix |= digit << shift;
-        wv::sync();
+        wv::sync_lds();
     }
     if (ln == 0) {
         a.p99[t] = prefix;
@@ -1409,7 +1596,7 @@ EST_DEV void slot_loop(const EstSimArgs &a, uint32_t wave_slot, uint64_t *lds) {
         const uint64_t k1 = (DIAG && a.dbg_ticks) ? wv::ticks() : 0;
         if (!a.lat_by_qid) select_wave(a, t, slot, lds);
         wv::sync();
-        if (DIAG && a.dbg_ticks && wv::lane() == 0) wv::atomic_add_u64(a.status->dbg_cnt + 8 + 4 * EST_MAX_STAGES + 2, wv::ticks() - k1);
+        if (DIAG && a.dbg_ticks && wv::lane() == 0) est_dbg_rec(&a, t, EST_MAX_STAGES - 1)[2] += wv::ticks() - k1;
         if (DIAG && a.dbg_ticks && wv::lane() == 0) a.dbg_ticks[t] = wv::ticks() - t0;
     }
 }
@@ -1435,11 +1622,11 @@ EST_DEV void nearest_sets(const EstDag &d, uint32_t mask, uint64_t *nv) {
 // visit counts.
 EST_DEV void prep1_thread(const EstPrepArgs &a, uint32_t tid, uint32_t nthreads) {
     const EstDag &d = *a.dag;
-    uint64_t uni[EST_MAX_STAGES + 1];
+    uint64_t uni[EST_MAX_STAGES + 1], muni[EST_MAX_STAGES + 1];
     uint32_t cntv[EST_MAX_STAGES + 1];
     uint64_t multi = 0;  // bit c: some visiting query of stage c has more than one nearest visited ancestor
     bool bad = false;
-    for (uint32_t c = 0; c <= d.S; ++c) { uni[c] = 0; cntv[c] = 0; }
+    for (uint32_t c = 0; c <= d.S; ++c) { uni[c] = 0; muni[c] = 0; cntv[c] = 0; }
     for (uint64_t q = tid; q < a.n; q += nthreads) {
         const uint32_t m = a.mask[q];
         if (q > 0 && a.arrival[q] < a.arrival[q - 1]) bad = true;
@@ -1449,14 +1636,20 @@ EST_DEV void prep1_thread(const EstPrepArgs &a, uint32_t tid, uint32_t nthreads)
             if (c < d.S && !((m >> c) & 1u)) continue;
             uni[c] |= nv[c];
             cntv[c]++;
-            if (__builtin_popcountll(nv[c]) > 1) multi |= 1ull << c;
+            if (__builtin_popcountll(nv[c]) > 1) {
+                multi |= 1ull << c;
+                muni[c] |= nv[c];
+            }
         }
     }
     for (uint32_t c = 0; c <= d.S; ++c) {
         if (cntv[c]) {
             wv::atomic_or_u64(&a.status->src_union[c], uni[c]);
             wv::atomic_add_u32(&a.status->n_visit[c], cntv[c]);
-            if ((multi >> c) & 1ull) wv::atomic_or_u32(&a.status->multi[c], 1u);
+            if ((multi >> c) & 1ull) {
+                wv::atomic_or_u32(&a.status->multi[c], 1u);
+                wv::atomic_or_u64(&a.status->multi_union[c], muni[c]);
+            }
         }
     }
     if (bad) wv::atomic_or_u32(&a.status->bad_trace, 1u);

@@ -44,9 +44,9 @@ uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
 // Sizes of one candidate's scratch, in units of each area.
 struct Sizes {
-    uint64_t state_words = 0, ring_elems = 0, rep_words = 0, slot_words = 0, cnt_bytes = 0;
+    uint64_t state_words = 0, ring_elems = 0, rep_words = 0, slot_words = 0, tab_bytes = 0;
     uint64_t per_cfg_bytes(uint64_t n, bool with_lat) const {
-        return state_words * 4 + ring_elems * 8 + rep_words * 4 + slot_words * 4 + cnt_bytes + (with_lat ? n * 4 : 0);
+        return state_words * 4 + ring_elems * 8 + rep_words * 4 + slot_words * 4 + tab_bytes + (with_lat ? n * 4 : 0);
     }
 };
 
@@ -142,8 +142,12 @@ int build_plan(estimator *h, const EstStatus &st, uint64_t n, PlanOut &po) {
             po.acc_stage[po.n_acc++] = c;
             op.has_cnt = st.multi[c] ? 1 : 0;
             if (op.has_cnt) {
-                op.cnt_off = po.sz.cnt_bytes;
-                po.sz.cnt_bytes += align_up(n, 16);
+                // every stream that feeds some query together with another stream gets a table of times by query
+                op.tab_off = po.sz.tab_bytes;
+                op.tab_len = (uint32_t)align_up(n, 64);
+                for (uint32_t j = 0; j < srcs[c].n; ++j)
+                    if ((st.multi_union[c] >> srcs[c].ring_src[j]) & 1ull) op.tab_mask |= 1u << j;
+                po.sz.tab_bytes += (uint64_t)__builtin_popcount(op.tab_mask) * op.tab_len * 4;
             }
         }
         if (c < S) {
@@ -341,7 +345,7 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     const uint64_t o_rings = area(po.sz.ring_elems * 8);
     const uint64_t o_rep = area(po.sz.rep_words * 4);
     const uint64_t o_slots = area(po.sz.slot_words * 4);
-    const uint64_t o_cnt = area(po.sz.cnt_bytes);
+    const uint64_t o_tab = area(po.sz.tab_bytes);
     const uint64_t o_lat = area(with_lat ? n * 4 : 0);
     if (at > ws_bytes) return fail(h, EST_EINTERNAL, "scratch layout overflow");
 
@@ -370,7 +374,7 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     const char *dbg_path = getenv("EST_DEBUG_TICKS");
     DevBuf dbg_buf;
     uint64_t *dbg_ticks = nullptr;
-    const uint64_t dbg_words = n_cfg * (1 + 4 * EST_MAX_STAGES);  // per candidate: ticks, then 4 counters per stage
+    const uint64_t dbg_words = n_cfg * (1 + 8 * EST_MAX_STAGES);  // per candidate: ticks, then 8 counters per stage
     if (dbg_path && n > 0 && dbg_buf.alloc(dbg_words * 8) && !estbe::zero(dbg_buf.p, dbg_words * 8, stream)) dbg_ticks = (uint64_t *)dbg_buf.p;
     void *e0 = evs.make(), *e1 = evs.make();
     if (!e0 || !e1) return dev_fail(h, "event create");
@@ -399,7 +403,7 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
         sa.rings = (uint64_t *)(ws + o_rings);  sa.ring_stride = po.sz.ring_elems;
         sa.rep = (uint32_t *)(ws + o_rep);      sa.rep_stride = po.sz.rep_words;
         sa.slots = (uint32_t *)(ws + o_slots);  sa.slot_stride = po.sz.slot_words;
-        sa.counters = ws + o_cnt;               sa.cnt_stride = po.sz.cnt_bytes;
+        sa.tabs = ws + o_tab;               sa.tab_stride = po.sz.tab_bytes;
         if (mode == MODE_LAT) {
             sa.lat = d_lat_out;
             sa.lat_stride = n;
@@ -422,7 +426,6 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
         if (!estbe::d2h(ticks.data(), dbg_ticks, dbg_words * 8, stream) && !estbe::sync(stream)) {
             if (FILE *f = fopen(dbg_path, "wb")) {
                 fwrite(ticks.data(), 8, dbg_words, f);
-                fwrite(st2.dbg_cnt, 8, sizeof st2.dbg_cnt / 8, f);  // then the diagnostic counters
                 fclose(f);
             }
         }
@@ -572,7 +575,7 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
     //      candidates leave (a launch of a few hundred bases alone would leave most of the device idle for as
     //      long as one simulation takes)
     const uint64_t n_pad = align_up(std::max<uint64_t>(n, 1), 256);
-    const uint64_t cap_bytes = po.sz.state_words * 4 + cap_elems * 8 + po.sz.rep_words * 4 + po.sz.slot_words * 4 + po.sz.cnt_bytes + 8 + 8;
+    const uint64_t cap_bytes = po.sz.state_words * 4 + cap_elems * 8 + po.sz.rep_words * 4 + po.sz.slot_words * 4 + po.sz.tab_bytes + 8 + 8;
     const uint64_t per_cfg = po.sz.per_cfg_bytes(n, true) + 64;
     const uint32_t resident = std::max<uint32_t>(estbe::max_resident_waves(po.lds_bytes), 1);
     const uint64_t avail = ((uint64_t)estbe::mem_free() + h->ws_bytes) / 100 * 85;
@@ -637,13 +640,13 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
     const uint64_t o_res_cap = take(nb * 8);  // results of the bases' launches (only the cost is written; unused)
     const uint64_t o_plan_cap = take(sizeof(EstPlan));
     const uint64_t o_status = take(2 * sizeof(EstStatus));  // work counters of the two kinds of launch
-    uint64_t o_cstate[2], o_crings[2], o_crep[2], o_cslots[2], o_ccnt[2];
+    uint64_t o_cstate[2], o_crings[2], o_crep[2], o_cslots[2], o_ctab[2];
     for (uint32_t i = 0; i < n_areas; ++i) {
         o_cstate[i] = take(nb * po.sz.state_words * 4);
         o_crings[i] = take(nb * cap_elems * 8);
         o_crep[i] = take(nb * po.sz.rep_words * 4);
         o_cslots[i] = take(nb * po.sz.slot_words * 4);
-        o_ccnt[i] = take(nb * po.sz.cnt_bytes);
+        o_ctab[i] = take(nb * po.sz.tab_bytes);
     }
     auto area = [&](uint64_t bytes_per_cfg) {
         uint64_t a0 = at;
@@ -654,7 +657,7 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
     const uint64_t o_rings = area(po.sz.ring_elems * 8);
     const uint64_t o_rep = area(po.sz.rep_words * 4);
     const uint64_t o_slots = area(po.sz.slot_words * 4);
-    const uint64_t o_cnt = area(po.sz.cnt_bytes);
+    const uint64_t o_tab = area(po.sz.tab_bytes);
     const uint64_t o_lat = area(n * 4);
     if (h->ws_bytes < at) {
         if (h->ws) estbe::dfree(h->ws);
@@ -735,7 +738,7 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
         c2.rings = (uint64_t *)(ws + o_crings[ar]);  c2.ring_stride = cap_elems;
         c2.rep = (uint32_t *)(ws + o_crep[ar]);      c2.rep_stride = po.sz.rep_words;
         c2.slots = (uint32_t *)(ws + o_cslots[ar]);  c2.slot_stride = po.sz.slot_words;
-        c2.counters = ws + o_ccnt[ar];               c2.cnt_stride = po.sz.cnt_bytes;
+        c2.tabs = ws + o_ctab[ar];               c2.tab_stride = po.sz.tab_bytes;
         c2.lat = nullptr;
         c2.p99 = (uint32_t *)(ws + o_res_cap); c2.miss = (uint32_t *)(ws + o_res_cap); c2.cost = (uint64_t *)(ws + o_res_cap);
         c2.skip_ops = (const uint64_t *)(ws + o_skip_cap);
@@ -770,7 +773,7 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
             cb.rings = (uint64_t *)(ws + o_rings);  cb.ring_stride = po.sz.ring_elems;
             cb.rep = (uint32_t *)(ws + o_rep);      cb.rep_stride = po.sz.rep_words;
             cb.slots = (uint32_t *)(ws + o_slots);  cb.slot_stride = po.sz.slot_words;
-            cb.counters = ws + o_cnt;               cb.cnt_stride = po.sz.cnt_bytes;
+            cb.tabs = ws + o_tab;               cb.tab_stride = po.sz.tab_bytes;
             cb.lat = (uint32_t *)(ws + o_lat);      cb.lat_stride = n;
             cb.p99 = (uint32_t *)(ws + o_p99); cb.miss = (uint32_t *)(ws + o_miss); cb.cost = (uint64_t *)(ws + o_cost);
             cb.skip_ops = (const uint64_t *)(ws + o_skip);

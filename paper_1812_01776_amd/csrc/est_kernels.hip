@@ -2,6 +2,8 @@
 // calls the host planner needs.  gfx950 only.
 #include <hip/hip_runtime.h>
 
+#include <stdlib.h>
+
 #include <string>
 
 #include "est_backend.h"
@@ -36,7 +38,10 @@ void est_sim_kernel(EstSimArgs a) {
 // few spills): the second is used when the LDS need of the launch lets five workgroups share a compute
 // unit, where the extra wavefront hides more latency than the spills cost.
 constexpr uint32_t LDS_PER_CU = 160u * 1024u;
-bool five_fit(uint32_t lds_bytes_per_wave) { return (uint64_t)lds_bytes_per_wave * EST_WAVES_PER_BLOCK * 5u <= LDS_PER_CU; }
+bool five_fit(uint32_t lds_bytes_per_wave) {
+    static const bool four = getenv("EST_FOUR_WAVES_PER_SIMD") != nullptr;  // tuning aid: always the 128-register build
+    return !four && (uint64_t)lds_bytes_per_wave * EST_WAVES_PER_BLOCK * 5u <= LDS_PER_CU;
+}
 
 __global__ __launch_bounds__(256) void est_prep1_kernel(EstPrepArgs a) {
     estdev::prep1_thread(a, blockIdx.x * blockDim.x + threadIdx.x, gridDim.x * blockDim.x);

@@ -12,8 +12,7 @@
 #define EST_MAX_CONS 36         // consumers of one ring
 #define EST_TRACE_BIT 32        // bit of the "arrival trace" pseudo-source in a source set
 #define EST_SRC_TRACE (-1)
-#define EST_DUP_BUCKETS 128u                       // hash buckets for spotting one query twice in a window of a join
-#define EST_LDS_MERGE_BYTES(k) ((k) * 1280u + 128u + 4u * EST_DUP_BUCKETS)   // LDS of one wavefront for a k-source merge
+#define EST_LDS_MERGE_BYTES(k) ((k) * 1664u + 512u)   // LDS of one wavefront for a k-source merge: staged keys 128 x 8, passed-on keys 64 x 8, accept masks 128 per source; scalars
 #define EST_LDS_SCAN_BYTES(rb) (3616u + 4u * (rb))      // ... for a scan whose replica slots hold rb members
 
 enum { EST_OP_SCAN = 0, EST_OP_MERGE = 1, EST_OP_LAT = 2 };
@@ -35,7 +34,10 @@ struct EstOp {
     int32_t out_ring;             // -1 for LAT
     uint32_t acc_idx;             // MERGE/LAT: which accept-mask array [n] to use
     uint32_t has_cnt;             // MERGE/LAT: some query draws from more than one source
-    uint64_t cnt_off;             // byte offset of this op's counters inside one candidate's counter area
+    uint64_t tab_off;             // MERGE/LAT: byte offset of this op's time tables inside one candidate's table area
+    uint32_t tab_mask;            // MERGE/LAT: bit j = source j feeds some query together with another source and has a
+                                  // table (uint32 [tab_len], indexed by query: the time of the query's element in source j)
+    uint32_t tab_len;             // MERGE/LAT: entries of one table (queries, rounded up)
     uint32_t rep_off;             // SCAN: word offset of the replica table inside one candidate's area
     uint32_t r_max;               // SCAN: replica table width (largest replica count of the stage in this run)
     uint64_t slot_off;            // SCAN: word offset of the member slots inside one candidate's slot area
@@ -57,6 +59,7 @@ struct EstPlan {
 struct EstStatus {
     uint64_t src_union[EST_MAX_STAGES + 1];  // per stage (and the sink): union of nearest-visited-ancestor sets
     uint32_t multi[EST_MAX_STAGES + 1];      // some visiting query has more than one such ancestor
+    uint64_t multi_union[EST_MAX_STAGES + 1];  // union of those queries' nearest-visited-ancestor sets
     uint32_t n_visit[EST_MAX_STAGES + 1];    // queries visiting the stage ([S] = n)
     uint32_t r_max[EST_MAX_STAGES];          // largest replica count per stage over all candidates
     uint32_t b_max[EST_MAX_STAGES];          // largest max-batch per stage over all candidates
@@ -66,11 +69,6 @@ struct EstStatus {
     uint32_t sim_error;                      // set by the simulation kernel on an inconsistency
     uint32_t next_cfg;                       // work counter: next candidate to hand to a free wavefront
     uint32_t pad;
-    // diagnostics (only counted when per-candidate timing is requested)
-    uint64_t dbg_cnt[8 + 4 * EST_MAX_STAGES + 8];  // general steps, shortcut steps, shortcut elements, B=1 steps, B=1 elements,
-                                             // merge rounds, merge elements, scan calls; then per stage: general steps,
-                                             // queries in general steps, queries in shortcut steps, ticks in the
-                                             // stage's scan; then ticks in merges, in the sink, in the selection
 };
 
 struct EstStageCfg {  // same layout as est_stage_cfg_t
@@ -108,10 +106,10 @@ struct EstSimArgs {
     uint64_t *rings;    uint64_t ring_stride;    // elements
     uint32_t *rep;      uint64_t rep_stride;     // words
     uint32_t *slots;    uint64_t slot_stride;    // words
-    uint8_t *counters;  uint64_t cnt_stride;     // bytes
+    uint8_t *tabs;      uint64_t tab_stride;     // bytes: the time tables of the merges that join several streams
     uint32_t *lat;      uint64_t lat_stride;     // words
     EstStatus *status;
-    uint64_t *dbg_ticks;           // optional [n_cfg]: 100 MHz ticks each candidate took (diagnostics)
+    uint64_t *dbg_ticks;           // optional: [n_cfg] 100 MHz ticks each candidate took, then [n_cfg][EST_MAX_STAGES][8] counters (diagnostics)
     uint32_t *p99; uint32_t *miss; uint64_t *cost;   // [n_cfg] results
     // Shared upstream stages (Section 4.3: the candidates of one planner step differ from a common base
     // in one model, so everything upstream of the change is simulated once).  Only read by the kernel

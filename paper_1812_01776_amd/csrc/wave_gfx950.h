@@ -1,4 +1,4 @@
-// Wavefront-level primitives for gfx950 (64 lanes).  One workgroup is one wavefront.
+// Wavefront-level primitives for gfx950 (64 lanes).  They act inside one wavefront; a workgroup may hold several.
 // Every function here must be called by all 64 lanes in wave-uniform control flow.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -81,6 +81,14 @@ EST_DEV void sync() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+// The same for LDS only: earlier LDS writes of any lane are visible to later LDS reads of any lane of
+// this wavefront.  Does not wait for outstanding global loads or stores.
+EST_DEV void sync_lds() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 EST_DEV void lds_add(uint32_t *p, uint32_t v) { atomicAdd(p, v); }

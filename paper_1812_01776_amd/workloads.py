@@ -196,14 +196,22 @@ def _visit_prob(s, pa, pb):
 
 
 def _fixed_stage(lat, s, demand_qps, rng):
-    """A seeded (hw, B, R) for a stage that is not swept, with B/L(B)*R >= 1.5 x the stage's demand
-    where 16 replicas can reach that; otherwise the largest-capacity choice."""
+    """A seeded (hw, B, R) for a stage that is not swept, with capacity R * B / L(B) >= 1.5 x the
+    stage's demand: the (hardware type, batch size) pairs are tried in a seeded random order and the
+    first that reaches the capacity with at most 16 replicas is taken; if none does, the pair with the
+    largest capacity at 16 replicas."""
     H = lat.shape[1]
-    hw = int(rng.integers(0, H))
-    b = int(rng.choice([8, 16, 32, 64]))
-    per_replica = b / (float(lat[s, hw, b - 1]) * 1e-6)
-    r = int(np.ceil(1.5 * demand_qps / per_replica))
-    return hw, b, min(max(r, 1), 16)
+    pairs = [(h, b) for h in range(H) for b in (8, 16, 32, 64)]
+    best = None
+    for i in rng.permutation(len(pairs)):
+        hw, b = pairs[int(i)]
+        per_replica = b / (float(lat[s, hw, b - 1]) * 1e-6)
+        r = int(np.ceil(1.5 * demand_qps / per_replica))
+        if r <= 16:
+            return hw, b, max(r, 1)
+        if best is None or per_replica > best[0]:
+            best = (per_replica, hw, b)
+    return best[1], best[2], 16
 
 
 def w4(n=1_000_000):
@@ -230,6 +238,31 @@ def w4(n=1_000_000):
         bt[:, s] = np.array([grid[i][0] for i in range(16)], np.uint8)[g]
         rp[:, s] = np.array([grid[i][1] for i in range(16)], np.uint16)[g]
     return Workload("W4", W45_PARENTS, lat, cost, arr, mask, hw, bt, rp, 250_000)
+
+
+def w4_provisioned(n=1_000_000, n_configs=16, seed=2404):
+    """W4's pipeline, profiles, trace and masks with candidates that are provisioned for the load
+    (the regime a planner's search spends its time in, around the SLO boundary): per stage a seeded
+    batch size in {1, 2, 4, 8}, the hardware type with the lowest latency at that batch size, and
+    replicas = ceil(f x demand / (B / L(B))) with a seeded head-room f in [0.9, 1.3], up to the 64
+    replicas the interface allows.  The head-room grows with the candidate index, so the set runs
+    from slightly overloaded through barely stable to comfortably feasible."""
+    w = w4(n=n)
+    S = w.n_stages
+    prng = np.random.default_rng(1004 + 500)
+    pa, pb = prng.uniform(0.3, 1.0, size=2)  # the branch probabilities w4() drew
+    rng = np.random.default_rng(seed)
+    hw = np.zeros((n_configs, S), np.uint8); bt = np.zeros((n_configs, S), np.uint8); rp = np.zeros((n_configs, S), np.uint16)
+    for c in range(n_configs):
+        lo = 0.9 + 0.3 * c / max(n_configs - 1, 1)
+        for s in range(S):
+            b = int(rng.choice([1, 2, 4, 8]))
+            h = int(np.argmin(w.lat_us[s, :, b - 1]))
+            f = float(rng.uniform(lo, lo + 0.1))
+            per_replica = b / (float(w.lat_us[s, h, b - 1]) * 1e-6)
+            r = int(np.ceil(f * 5000.0 * _visit_prob(s, pa, pb) / per_replica))
+            hw[c, s] = h; bt[c, s] = b; rp[c, s] = min(max(r, 1), 64)
+    return Workload("W4p", w.parents, w.lat_us, w.cost_uusd_hr, w.arrival_us, w.visit_mask, hw, bt, rp, w.slo_us)
 
 
 def w5(n=2_000_000, n_base=4096):
@@ -384,6 +417,41 @@ def backlog_case(seed):
     bt = rng.choice(sizes, size=(C, S)).astype(np.uint8)
     rp = rng.choice([1, 1, 2, 2, 3, 4, 5, 8], size=(C, S)).astype(np.uint16)
     return Workload("backlog%d" % seed, parents, lat, cost, arr, mask, hw, bt, rp, int(lat.max()))
+
+
+def grouped_case(seed, n=None):
+    """A small pipeline under bursts: queries arrive in groups of 4..48 at the same microsecond, the stages
+    take large batches whose service time is several times the gap between groups, on enough replicas
+    that every group finds one idle -- many batches are in flight at once and leave in completion order.
+    Every second seed puts all times on a 100-us grid (completions tie), every third seed is the W4/W5
+    fork-join shape, every fifth gives some stage too few replicas for part of the trace."""
+    rng = np.random.default_rng(3000 + seed)
+    n = int(rng.integers(2000, 5000)) if n is None else n
+    C, H, Bmax = 4, 2, 64
+    if seed % 3 == 2:
+        parents = [[], [0], [1], [1], [2, 3], [4]]
+    else:
+        parents = [[]] + [[s - 1] for s in range(1, int(rng.integers(2, 5)))]
+    S = len(parents)
+    quantum = 100 if seed % 2 == 0 else 1
+    a = rng.integers(8000, 40000, size=(S, H))
+    c = rng.integers(50, 800, size=(S, H))
+    lat = (a[:, :, None] + c[:, :, None] * np.arange(1, Bmax + 1)[None, None, :]).astype(np.uint32)
+    lat = np.maximum(lat // quantum * quantum, quantum).astype(np.uint32)
+    sizes = rng.integers(4, 49, size=n)
+    starts = np.cumsum(rng.integers(1500, 7000, size=n) // quantum * quantum)
+    arr = np.repeat(starts, sizes)[:n].astype(np.uint32)
+    mask = np.zeros(n, np.uint32)
+    for s in range(S):
+        p = 1.0 if (rng.random() < 0.6 or s == 0 or s == S - 1) else rng.uniform(0.4, 1.0)
+        mask |= (rng.random(n) < p).astype(np.uint32) << np.uint32(s)
+    cost = np.full((S, H), 5, np.uint64)
+    hw = rng.integers(0, H, size=(C, S)).astype(np.uint8)
+    bt = rng.choice([48, 64, 64, 32], size=(C, S)).astype(np.uint8)
+    rp = rng.integers(12, 17, size=(C, S)).astype(np.uint16)
+    if seed % 5 == 4:
+        rp[:, int(rng.integers(0, S))] = rng.integers(2, 6, size=C)
+    return Workload("grouped%d" % seed, parents, lat, cost, arr, mask, hw, bt, rp, int(lat.max()) * 2)
 
 
 def planner_case(seed, n=1500):

@@ -94,6 +94,7 @@ EST_DEV uint32_t prefix_excl_u32(uint32_t v) {
 }
 
 EST_DEV void sync() { (void)emu::exchange(0, 8); }
+EST_DEV void sync_lds() { (void)emu::exchange(0, 16); }  // (memory here is host memory either way)
 
 EST_DEV void lds_add(uint32_t *p, uint32_t v) { *p += v; }
 EST_DEV void atomic_or_u64(uint64_t *p, uint64_t v) { *p |= v; }

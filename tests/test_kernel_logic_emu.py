@@ -63,6 +63,18 @@ def test_backlog_lockstep_and_horizon_cases_match_oracle(seed):
     _compare(workloads.backlog_case(seed))
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_bursts_of_large_groups_match_oracle(seed, tmp_path, monkeypatch):
+    # groups of queries that become ready together, large batches, many of them in flight at once; the
+    # step counters confirm that the light-load step for large groups is the one that ran
+    w = workloads.grouped_case(seed, n=1200)
+    dump = tmp_path / "ticks.bin"
+    monkeypatch.setenv("EST_DEBUG_TICKS", str(dump))
+    _compare(w)
+    d = np.fromfile(dump, dtype=np.uint64)[w.n_configs:].reshape(w.n_configs, 32, 8)
+    assert d[:, :w.n_stages, 4].sum() > 0
+
+
 def test_wide_batches_many_replicas_and_ring_wrap():
     """R up to 16, B up to 64 and enough queries for the bounded rings to wrap several times; every
     time a multiple of 10 so that batches complete together and have to be merged by query index."""
@@ -194,4 +206,4 @@ def test_diagnostics_variant_gives_the_same_results(tmp_path, monkeypatch):
     monkeypatch.setenv("EST_DEBUG_TICKS", str(dump))
     _compare(w)
     d = np.fromfile(dump, dtype=np.uint64)
-    assert d.size == w.n_configs * (1 + 4 * 32) + 8 + 4 * 32 + 8
+    assert d.size == w.n_configs * (1 + 8 * 32)
