@@ -224,6 +224,73 @@ EST_DEV uint64_t sort_time_query(uint32_t e, uint32_t q, uint64_t VM, uint32_t b
 // free again, so the earliest free replica is lane 0 and batches complete in lane order.
 enum { SCAN_INRING = 256 };
 
+// Write the members of the batches in the table lanes of tie, which all complete at time mv, merged by
+// query index, to out[base ...]; returns their number.  (Times clamped at the horizon need no order:
+// everything downstream of a clamped time is clamped too, so those are concatenated.)
+EST_DEV uint32_t emit_tied(const EstOp &op, const uint32_t *lslots, uint64_t tie, uint32_t mv, uint32_t rcnt, uint32_t rslot,
+                           uint64_t *out, uint32_t omask, uint32_t base) {
+    const uint32_t ln = wv::lane();
+    const uint32_t bm = wv::uniform(op.b_max);
+    const uint64_t tkey = (uint64_t)mv << 32;
+    uint32_t total = 0;
+    if (mv == 0xFFFFFFFFu) {
+        for (uint64_t m = tie; m; m &= m - 1) {
+            const uint32_t r = ctz64(m);
+            const uint32_t cr = wv::bcast(rcnt, r), sl = wv::bcast(rslot, r);
+            if (ln < cr) out[(base + total + ln) & omask] = tkey | lslots[sl * bm + ln];
+            total += cr;
+        }
+        return total;
+    }
+    // rank every member among all of them
+    for (uint64_t m = tie; m; m &= m - 1) {
+        const uint32_t r = ctz64(m);
+        const uint32_t cr = wv::bcast(rcnt, r), sl = wv::bcast(rslot, r);
+        const uint32_t x = ln < cr ? lslots[sl * bm + ln] : 0u;
+        uint32_t rank = ln;
+        for (uint64_t m2 = tie; m2; m2 &= m2 - 1) {
+            const uint32_t r2 = ctz64(m2);
+            const uint32_t c2 = wv::bcast(rcnt, r2), sl2 = wv::bcast(rslot, r2);
+            if (r2 == r || ln >= cr) continue;
+            const uint32_t *s2 = lslots + sl2 * bm;
+            uint32_t lo = 0, hi = c2;
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (s2[mid] < x) lo = mid + 1; else hi = mid;
+            }
+            rank += lo;
+        }
+        if (ln < cr) out[(base + rank) & omask] = tkey | x;
+        total += cr;
+    }
+    return total;
+}
+
+// Older waiting batches (table lanes in woven, ascending completion times, all different from the new
+// ones) leave together with new queries: the new ones, whose completion times are ke in the lanes of emitm,
+// have been placed already, each shifted by the members of the older batches that finish before it; here the
+// older batches are written into the gaps, those that complete together merged by query index.
+EST_DEV void weave_out(const EstOp &op, const uint32_t *lslots, uint64_t woven, uint64_t emitm, uint32_t ke, uint32_t rend,
+                       uint32_t rcnt, uint32_t rslot, uint64_t *out, uint32_t omask, uint32_t wr) {
+    const uint32_t ln = wv::lane();
+    const uint32_t bm = wv::uniform(op.b_max);
+    uint32_t before = 0;
+    for (uint64_t pm = woven; pm;) {
+        const uint32_t j = ctz64(pm);
+        const uint32_t ej = wv::bcast(rend, j);
+        const uint64_t tie = pm & wv::ballot(rend == ej);
+        const uint32_t pos = wr + before + popc64(emitm & wv::ballot(ke < ej));
+        if ((tie & (tie - 1)) == 0) {
+            const uint32_t cj = wv::bcast(rcnt, j), sj = wv::bcast(rslot, j);
+            if (ln < cj) out[(pos + ln) & omask] = ((uint64_t)ej << 32) | lslots[sj * bm + ln];
+            before += cj;
+        } else {
+            before += emit_tied(op, lslots, tie, ej, rcnt, rslot, out, omask, pos);
+        }
+        pm &= ~tie;
+    }
+}
+
 // Emit, in (completion time, query index) order, the batches whose replica-table lanes are in E
 // (ascending lanes = ascending completion time).  Batches that complete at the same time are
 // merged by query index.  Stops early (returns false) when the output ring cannot take the next
@@ -248,38 +315,7 @@ EST_DEV bool scan_emit(const EstOp &op, const uint32_t *lslots, uint64_t E, uint
             uint32_t total = 0;
             for (uint64_t m = tie; m; m &= m - 1) total += wv::bcast(rcnt, ctz64(m));
             if (total > space) return false;
-            if (mv == 0xFFFFFFFFu) {
-                // clamped at the horizon: relative order cannot matter (everything downstream of a
-                // clamped time is clamped too): concatenate
-                uint32_t base = wr;
-                for (uint64_t m = tie; m; m &= m - 1) {
-                    const uint32_t r = ctz64(m);
-                    const uint32_t cr = wv::bcast(rcnt, r), sl = wv::bcast(rslot, r);
-                    if (ln < cr) out[(base + ln) & omask] = tkey | lslots[sl * bm + ln];
-                    base += cr;
-                }
-            } else {
-                // several batches complete together: rank every member among all of them
-                for (uint64_t m = tie; m; m &= m - 1) {
-                    const uint32_t r = ctz64(m);
-                    const uint32_t cr = wv::bcast(rcnt, r), sl = wv::bcast(rslot, r);
-                    const uint32_t x = ln < cr ? lslots[sl * bm + ln] : 0u;
-                    uint32_t rank = ln;
-                    for (uint64_t m2 = tie; m2; m2 &= m2 - 1) {
-                        const uint32_t r2 = ctz64(m2);
-                        const uint32_t c2 = wv::bcast(rcnt, r2), sl2 = wv::bcast(rslot, r2);
-                        if (r2 == r || ln >= cr) continue;
-                        const uint32_t *s2 = lslots + sl2 * bm;
-                        uint32_t lo = 0, hi = c2;
-                        while (lo < hi) {
-                            const uint32_t mid = (lo + hi) >> 1;
-                            if (s2[mid] < x) lo = mid + 1; else hi = mid;
-                        }
-                        rank += lo;
-                    }
-                    if (ln < cr) out[(wr + rank) & omask] = tkey | x;
-                }
-            }
+            emit_tied(op, lslots, tie, mv, rcnt, rslot, out, omask, wr);
             wr += total;
             space -= total;
         }
@@ -313,7 +349,6 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     uint32_t *linv = ltab + 328;           // 64: linv[d-1] = ceil(65536 / d), so that floor(x / d) = x * linv[d-1] >> 16 for x <= 64
     uint32_t *lslots = ltab + 392;
     const uint8_t *acc = c.a->acc + (uint64_t)op.acc_idx * c.a->acc_stride;
-    const uint64_t below = lanes_below(ln);
     linv[ln] = (65536u + ln) / (ln + 1u);
     const uint32_t inv_b = (65536u + B - 1u) / B, inv_r = (65536u + R - 1u) / R;
 
@@ -446,7 +481,8 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 const uint32_t tl = wv::bcast(rend, R - 1);
                 uint32_t nacc = 0;
                 if (tl < sat_add(f0, LB)) {
-                    const uint32_t kb = (ln * inv_b) >> 16;        // my batch
+                    const uint32_t lo = wv::opaque(ln);
+                    const uint32_t kb = (lo * inv_b) >> 16;        // my batch
                     const uint32_t kd = (kb * inv_r) >> 16, km = kb - kd * R;
                     const uint64_t ft = (uint64_t)wv::shfl(rend, km) + (uint64_t)kd * LB;
                     const uint32_t fk = ft >= 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)ft;
@@ -523,7 +559,8 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 m = (B > 1 && !final) ? w - 1u : w;  // (for B > 1 the last query may yet be joined by the next)
                 x = sat_add(rdy, L1);
             } else if (B == 1) {
-                const uint32_t kd = (ln * inv_r) >> 16, km = ln - kd * R;
+                const uint32_t lo = wv::opaque(ln);
+                const uint32_t kd = (lo * inv_r) >> 16, km = lo - kd * R;
                 const uint64_t st = (uint64_t)wv::shfl(rend, km) + (uint64_t)kd * L1;  // when my replica is free for me
                 const uint64_t en = st + L1;
                 x = en >= 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)en;
@@ -644,7 +681,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             bool done = false;
             if (m >= 16 && 4u * G <= m) {
                 // my run: lanes [start, nh)
-                const uint64_t upto = below | (1ull << ln);
+                const uint64_t upto = lanes_below(wv::opaque(ln) + 1u);
                 const uint32_t start = 63u - (uint32_t)__builtin_clzll((hA & upto) | 1ull);
                 const uint64_t later = ln == 63 ? 0ull : (hA >> (ln + 1));
                 const uint32_t nh = later ? ln + 1u + ctz64(later) : m;
@@ -726,7 +763,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 const uint32_t rlen = ln < nruns ? lstart[ln + 1u] - lstart[ln] : 0u;
                 if (wv::ballot(rlen > B)) {
                     // some run is longer than a batch: cut the runs into pieces of B
-                    const uint64_t upto = below | (1ull << ln);
+                    const uint64_t upto = lanes_below(wv::opaque(ln) + 1u);
                     const uint32_t off = ln - start;
                     heads = WM & wv::ballot(off == B * ((off * inv_b) >> 16));  // first query of each group
                     bid = popc64(heads & upto) - 1u;                               // group index of this lane
@@ -745,14 +782,10 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 const uint32_t ngroups = popc64(heads);
                 const uint64_t usable = REP & lanes_below(ngroups) & wv::ballot(rend <= lrdy[ln < ngroups ? ln : 0]);
                 const uint32_t p = usable == ~0ull ? 64u : ctz64(~usable);     // >= 1: entry 0 is idle now
-                // a tie between two older waiting batches caps the run (their order is settled elsewhere),
-                // and no new completion time may equal an older waiting one
+                // no new completion time may equal an older waiting one (older ones that tie with each other are
+                // merged by query index when they leave)
                 const uint64_t busyp = wv::ballot(rcnt > 0);  // all of these end after r0
-                const uint32_t rend_next = wv::shl1(rend);
-                const uint32_t rcnt_next = wv::shl1(rcnt);
-                const uint64_t tiep = lanes_below(R - 1u) & wv::ballot(rend > r0) & wv::ballot(rend == rend_next) & (busyp | wv::ballot(rcnt_next > 0));
-                const uint32_t ecap = tiep ? wv::bcast(rend, ctz64(tiep)) : 0xFFFFFFFFu;
-                uint64_t okm = WM & wv::ballot(e < ecap) & wv::ballot(g <= B);  // (ecap <= 2^32-1: a clamped time never passes)
+                uint64_t okm = WM & wv::ballot(e != 0xFFFFFFFFu) & wv::ballot(g <= B);  // (a clamped time never passes)
                 for (uint64_t pm = busyp; pm; pm &= pm - 1) {
                     const uint32_t ep = wv::bcast(rend, ctz64(pm));
                     okm &= wv::ballot(e != ep);
@@ -790,7 +823,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                     for (uint64_t pm = busyp; pm; pm &= pm - 1) {
                         const uint32_t j = ctz64(pm);
                         const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j);
-                        if ((!tau_inf && ej >= tau) || ej >= ecap) break;  // sorted: the rest finish later (or tie) and keep waiting
+                        if (!tau_inf && ej >= tau) break;  // sorted: the rest finish later and keep waiting
                         woven |= 1ull << j;
                         extra += cj;
                     }
@@ -830,14 +863,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                             if (ej < ke) shift += cj;
                         }
                         if (emit_me) out[(wr + orank + shift) & omask] = key;
-                        uint32_t before = 0;
-                        for (uint64_t pm = woven; pm; pm &= pm - 1) {
-                            const uint32_t j = ctz64(pm);
-                            const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j), sj = wv::bcast(rslot, j);
-                            const uint32_t pos = wr + before + popc64(emitm & wv::ballot(ke < ej));
-                            if (ln < cj) out[(pos + ln) & omask] = ((uint64_t)ej << 32) | lslots[sj * bm + ln];
-                            before += cj;
-                        }
+                        weave_out(op, lslots, woven, emitm, ke, rend, rcnt, rslot, out, omask, wr);
                         if ((woven >> ln) & 1ull) rcnt = 0;
                         wr += ns + extra;
                         space -= ns + extra;
@@ -904,25 +930,26 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             // batch replaced on its replica inside the block finished by that later start, hence before tau.
             const uint64_t WM = lanes_below(w);
             const bool final = staged <= 64 && rraw == in.wr && in.fin;
-            const uint32_t rend_next = wv::shl1(rend), rcnt_next = wv::shl1(rcnt);
             const uint64_t busyp = wv::ballot(rcnt > 0);
-            const uint64_t tiep = lanes_below(R - 1u) & wv::ballot(rend == rend_next) & (busyp | wv::ballot(rcnt_next > 0));
-            const uint32_t ecap = tiep ? wv::bcast(rend, ctz64(tiep)) : 0xFFFFFFFFu;  // two older batches tie there: settled elsewhere
             // working table: free time, and packed (members waiting << 16 | batch of this block on the entry, 0xFF = none, << 8 | slot)
             uint32_t trend = rend, tinfo = (rcnt << 16) | 0xFF00u | rslot;
             uint32_t vE = 0, vS = 0, vA = 0, vB = 0;                          // per batch (lane k): end, slot, first lane, size
             uint64_t heads = 0;
             uint32_t a = 0, K = 0;
+            uint32_t cap = 0xFFFFFFFFu;  // a new batch completes together with an older waiting one at this time: nothing from there on leaves in this step
             while (a < w) {
                 const uint32_t f = wv::uniform(trend);
+                const uint32_t ti0 = wv::uniform(tinfo);
+                // the entry taken loses its slot, so its batch (of this block, or an older one still waiting) has to leave in this step
+                if (f >= cap && (((ti0 >> 8) & 0xFFu) != 0xFFu || (ti0 >> 16) != 0u)) break;
                 const uint32_t T = umax(f, wv::bcast(rdy, a));
                 const uint32_t ready = popc64(WM & wv::ballot(rdy <= T));
                 const uint32_t b = umin(B, ready - a);
                 if (!(b == B || ready < w || final)) break;  // more members may still arrive
                 const uint32_t e = sat_add(T, wv::bcast(Lmine, b - 1u));
-                if (e >= ecap) break;                       // (ecap <= 2^32-1: a clamped time never passes)
-                if (wv::ballot(tinfo >= 0x10000u) & wv::ballot(trend == e)) break;  // would tie with an older waiting batch
-                const uint32_t slot0 = wv::uniform(tinfo) & 0xFFu;
+                if (e == 0xFFFFFFFFu) break;                // (a clamped time never passes)
+                if (cap == 0xFFFFFFFFu && (wv::ballot(tinfo >= 0x10000u) & wv::ballot(trend == e))) cap = e;  // the pair is merged by query index when it leaves, later
+                const uint32_t slot0 = ti0 & 0xFFu;
                 const bool mine = ln == K;
                 vE = mine ? e : vE; vS = mine ? slot0 : vS; vA = mine ? a : vA; vB = mine ? b : vB;
                 // the earliest entry leaves the table, the new one goes in behind everything that ends no later
@@ -940,25 +967,30 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             bool done = false;
             if (K >= 2) {
                 const uint32_t f_next = wv::uniform(trend);
-                const bool tau_inf = final && a >= w;
+                bool tau_inf = final && a >= w;
                 const uint32_t r_next = wv::bcast(rdy, a < w ? a : w - 1u);  // what follows is ready no earlier
-                const uint32_t tau = tau_inf ? 0xFFFFFFFFu : sat_add(umax(f_next, r_next), L1);
+                uint32_t tau = tau_inf ? 0xFFFFFFFFu : sat_add(umax(f_next, r_next), L1);
                 const uint32_t kb = wv::rank_below(heads >> 1);             // my batch (lane 0 starts batch 0)
                 const uint32_t e = wv::shfl(vE, kb), st = wv::shfl(vA, kb), myslot = wv::shfl(vS, kb);
                 const uint64_t AM = lanes_below(a);
+                if (cap != 0xFFFFFFFFu && (tau_inf || cap < tau)) {
+                    tau = cap;
+                    tau_inf = false;
+                }
                 const uint64_t safem = AM & (tau_inf ? ~0ull : wv::ballot(e < tau));
-                const bool safe = ln < a && (tau_inf || e < tau);
                 const uint32_t nsafe = popc64(safem);
                 uint32_t extra = 0;
-                uint64_t woven = 0;
+                uint64_t woven = 0, clash = 0;  // clash: a new batch that leaves now completes together with an older one (excluded by the cap)
                 for (uint64_t pm = busyp; pm; pm &= pm - 1) {
                     const uint32_t j = ctz64(pm);
                     const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j);
-                    if ((!tau_inf && ej >= tau) || ej >= ecap) break;  // sorted: the rest finish later (or tie) and keep waiting
+                    if (!tau_inf && ej >= tau) break;  // sorted: the rest finish later and keep waiting
                     woven |= 1ull << j;
                     extra += cj;
+                    clash |= safem & wv::ballot(e == ej);
                 }
-                if (nsafe + extra <= space) {
+                const bool safe = ln < a && (tau_inf || e < tau);
+                if (nsafe + extra <= space && clash == 0) {
                     const uint32_t eprev = wv::shr1(e), qprev = wv::shr1(q), kprev = wv::shr1(kb);
                     uint64_t key = safe ? (((uint64_t)e << 32) | q) : ~0ull;
                     // in output order already?  (only checked when the safe queries are the leading ones)
@@ -974,14 +1006,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                         if (ej < ke) shift += cj;
                     }
                     if (emit_me) out[(wr + ln + shift) & omask] = key;
-                    uint32_t before = 0;
-                    for (uint64_t pm = woven; pm; pm &= pm - 1) {
-                        const uint32_t j = ctz64(pm);
-                        const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j), sj = wv::bcast(rslot, j);
-                        const uint32_t pos = wr + before + popc64(lanes_below(nsafe) & wv::ballot(ke < ej));
-                        if (ln < cj) out[(pos + ln) & omask] = ((uint64_t)ej << 32) | lslots[sj * bm + ln];
-                        before += cj;
-                    }
+                    weave_out(op, lslots, woven, lanes_below(nsafe), ke, rend, rcnt, rslot, out, omask, wr);
                     wr += nsafe + extra;
                     space -= nsafe + extra;
                     EST_CHK_ORDER(7);
@@ -1000,7 +1025,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                     if (isrep) {
                         rend = trend;
                         rslot = tinfo & 0xFFu;
-                        rcnt = tk == 0xFFu ? ((late || trend >= ecap) ? tinfo >> 16 : 0u) : (late ? bsz : 0u);
+                        rcnt = tk == 0xFFu ? (late ? tinfo >> 16 : 0u) : (late ? bsz : 0u);
                     }
                     wv::sync_lds();
                     lhead += a;

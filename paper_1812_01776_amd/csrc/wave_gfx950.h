@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #define EST_DEV __device__ __forceinline__
+#define EST_DEV_NOINLINE __device__ __attribute__((noinline))
 #define EST_UNROLL _Pragma("unroll")
 #define EST_CHECK(cond) ((void)0)
 
@@ -45,6 +46,13 @@ EST_DEV bool lane_in(uint64_t m) { return __builtin_amdgcn_inverse_ballot_w64(m)
 // number of set bits of m below this lane's position (m must be the same in every lane)
 EST_DEV uint32_t rank_below(uint64_t m) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
+// v, hidden from the optimiser: what is computed from the result inside a loop is not moved out of the loop
+// (where it would hold registers for the whole loop)
+EST_DEV uint32_t opaque(uint32_t v) {
+    asm volatile("" : "+v"(v));
+    return v;
 }
 
 EST_DEV uint32_t uniform(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }

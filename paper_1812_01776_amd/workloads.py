@@ -454,6 +454,42 @@ def grouped_case(seed, n=None):
     return Workload("grouped%d" % seed, parents, lat, cost, arr, mask, hw, bt, rp, int(lat.max()) * 2)
 
 
+def provisioned_case(seed, n=None):
+    """A small pipeline provisioned at 80-100 % utilisation with small batches on many replicas (the
+    regime around the SLO boundary): an upstream stage batches, so the next stages see groups of queries
+    that become ready together and cut them into several batches started at the same instant on
+    different replicas -- completions tie all the time and have to be merged by query index.  Service
+    times are set from the utilisation; every third seed is a fork-join, every second quantises times."""
+    rng = np.random.default_rng(4000 + seed)
+    n = int(rng.integers(3000, 7000)) if n is None else n
+    C, H, Bmax = 4, 1, 16
+    if seed % 3 == 2:
+        parents = [[], [0], [0], [1, 2], [3]]
+    else:
+        parents = [[]] + [[s - 1] for s in range(1, int(rng.integers(2, 5)))]
+    S = len(parents)
+    rate = 5000.0
+    quantum = 10 if seed % 2 == 0 else 1
+    gaps = np.rint(rng.gamma(0.5, 2.0 / rate, size=n) * 1e6).astype(np.int64) // quantum * quantum
+    arr = np.cumsum(gaps).astype(np.uint32)
+    bt = rng.choice([1, 2, 2, 4, 8], size=(C, S)).astype(np.uint8)
+    rp = rng.integers(6, 33, size=(C, S)).astype(np.uint16)
+    lat = np.zeros((S, H, Bmax), np.uint32)
+    for s in range(S):
+        b, r = int(bt[0, s]), int(rp[0, s])
+        lb = r * b * float(rng.uniform(0.8, 1.0)) / rate * 1e6   # L(b) for that utilisation under the first candidate
+        a = 0.6 * lb
+        c = (lb - a) / b
+        lat[s, 0, :] = np.maximum(np.rint(a + c * np.arange(1, Bmax + 1)) // quantum * quantum, quantum)
+    mask = np.zeros(n, np.uint32)
+    for s in range(S):
+        p = 1.0 if (rng.random() < 0.7 or s == 0 or s == S - 1) else rng.uniform(0.5, 1.0)
+        mask |= (rng.random(n) < p).astype(np.uint32) << np.uint32(s)
+    cost = np.full((S, H), 5, np.uint64)
+    hw = np.zeros((C, S), np.uint8)
+    return Workload("prov%d" % seed, parents, lat, cost, arr, mask, hw, bt, rp, int(lat.max()) * 3)
+
+
 def planner_case(seed, n=1500):
     """A small pipeline for the greedy planner: three hardware types per stage (fast and expensive,
     medium, slow and cheap -- in seeded index order), batching that amortises a fixed cost, an

@@ -11,6 +11,7 @@
 #include <stdlib.h>
 
 #define EST_DEV static inline
+#define EST_DEV_NOINLINE static
 #define EST_UNROLL
 #define EST_CHECK(cond)                                                                       \
     do {                                                                                      \
@@ -69,6 +70,8 @@ EST_DEV uint32_t rank_below(uint64_t m) {
     const uint32_t l = emu::lane();
     return (uint32_t)__builtin_popcountll(m & (l >= 64 ? ~0ull : ((1ull << l) - 1ull)));
 }
+
+EST_DEV uint32_t opaque(uint32_t v) { return v; }
 
 EST_DEV uint32_t uniform(uint32_t v) { return (uint32_t)emu::exchange(v, 4)[0]; }
 

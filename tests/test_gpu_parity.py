@@ -99,6 +99,14 @@ def test_bursts_of_large_groups(seed):
     _compare(workloads.grouped_case(seed))
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_provisioned_small_batches_with_tied_completions(seed):
+    """Pipelines at 80-100 % utilisation with small batches on many replicas downstream of a batching stage
+    (the regime around the SLO boundary): groups are cut into several batches that start at the same
+    instant, completions tie and leave merged by query index."""
+    _compare(workloads.provisioned_case(seed))
+
+
 def test_replica_and_batch_limits():
     """R = 64 and B = 64, the largest the interface allows."""
     w = workloads.random_case(7, S=2, n=5000, C=4, max_b=64, max_r=4, dag="linear")

@@ -75,6 +75,13 @@ def test_bursts_of_large_groups_match_oracle(seed, tmp_path, monkeypatch):
     assert d[:, :w.n_stages, 4].sum() > 0
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_provisioned_small_batches_with_tied_completions_match_oracle(seed):
+    # 80-100 % utilisation, small batches on many replicas downstream of a batching stage: groups cut into
+    # several batches that start together, so completions tie and leave merged by query index
+    _compare(workloads.provisioned_case(seed, n=1500))
+
+
 def test_wide_batches_many_replicas_and_ring_wrap():
     """R up to 16, B up to 64 and enough queries for the bounded rings to wrap several times; every
     time a multiple of 10 so that batches complete together and have to be merged by query index."""
