@@ -1037,12 +1037,23 @@ uint64_t estimator_workspace_bytes(const estimator_t *h, uint64_t n, uint64_t n_
     if (!h) return 0;
     const uint32_t S = h->dag.S;
     const uint64_t n_pad = align_up(std::max<uint64_t>(n, 1), 256);
-    // every stage forking: an unbounded out ring, a bounded in ring, counters, full slots
+    // every stage forking: an unbounded out ring, a bounded in ring, full slots
     const uint64_t cap_b = pow2ceil(EST_MAX_REPLICAS * EST_MAX_BATCH + 64 * EST_KMAX + 65);
     uint64_t per_cfg = (4ull * EST_MAX_RINGS + EST_MAX_EDGES + EST_MAX_OPS) * 4;
     per_cfg += (uint64_t)S * (std::max(cap_b, pow2ceil(std::max<uint64_t>(n, 1))) + cap_b) * 8;
     per_cfg += (uint64_t)S * (2 * EST_MAX_REPLICAS + EST_MAX_REPLICAS * EST_MAX_BATCH) * 4;
-    per_cfg += (uint64_t)(S + 1) * align_up(n, 16);
+    // time tables of joins: a stage (or the sink) can be fed by several streams at once when it has several
+    // parents, or a parent that has (a query that skips that parent takes its ready time from further up);
+    // one table per stream, at most EST_KMAX and at most one per ancestor plus the arrivals
+    {
+        bool joins[EST_MAX_STAGES + 1];
+        for (uint32_t c = 0; c <= S; ++c) {
+            const uint32_t b = h->dag.parent_off[c], e = h->dag.parent_off[c + 1];
+            joins[c] = e - b >= 2;
+            for (uint32_t i = b; i < e; ++i) joins[c] = joins[c] || joins[h->dag.parent_idx[i]];
+            if (joins[c]) per_cfg += (uint64_t)std::min<uint32_t>(EST_KMAX, c + 1) * align_up(n, 64) * 4;
+        }
+    }
     per_cfg += n * 4 + 64;
     uint64_t fixed = n_pad * 8 + (uint64_t)(S + 1) * n_pad + n_cfg * 16 + 16 * 256;
     return fixed + per_cfg * std::max<uint64_t>(n_cfg, 1);
