@@ -59,25 +59,6 @@ __global__ __launch_bounds__(256) void est_cfg_kernel(EstCfgArgs a) {
     estdev::cfg_thread(a, blockIdx.x * blockDim.x + threadIdx.x, gridDim.x * blockDim.x);
 }
 
-// Lane-layout check of the wavefront primitives: out[i][lane] for the input v = 7 * lane + 3
-// (i = 0..5: shr1, shl1, xor1, xor2, xor4, xor8) and for sort_lanes of a scrambled input at widths
-// 2..64 (i = 6..11).
-__global__ __launch_bounds__(64) void est_wave_selftest_kernel(uint32_t *out) {
-    const uint32_t ln = threadIdx.x;
-    const uint32_t v = 7u * ln + 3u;
-    out[0 * 64 + ln] = wv::shr1(v);
-    out[1 * 64 + ln] = wv::shl1(v);
-    out[2 * 64 + ln] = wv::xor1(v);
-    out[3 * 64 + ln] = wv::xor2(v);
-    out[4 * 64 + ln] = wv::xor4(v);
-    out[5 * 64 + ln] = wv::xor8(v);
-    const uint32_t scr = (ln * 37u + 11u) & 63u;  // a permutation of 0..63
-    uint32_t i = 6;
-    for (uint32_t width = 2; width <= 64; width <<= 1, ++i)
-        out[i * 64 + ln] = estdev::sort_lanes(ln < width ? scr : 0xFFFFFFFFu, width);
-    out[12 * 64 + ln] = wv::rank_below(0xF0F0A5A5C3C3FF01ull);
-}
-
 uint32_t blocks_for(uint64_t items, uint32_t per_block, uint32_t max_blocks) {
     uint64_t b = (items + per_block - 1) / per_block;
     if (b < 1) b = 1;
@@ -205,25 +186,3 @@ float event_ms(void *start, void *stop) {
 }
 
 }  // namespace estbe
-
-// Runs the lane-layout check kernel and copies its 13 x 64 results to host memory.  Returns 0 on
-// success.  Used by the GPU tests only.
-extern "C" int est_selftest_wave(uint32_t *host_out) {
-    uint32_t *d = nullptr;
-    if (check(hipMalloc((void **)&d, 13 * 64 * 4), "hipMalloc")) return 1;
-    est_wave_selftest_kernel<<<1, 64>>>(d);
-    int rc = check(hipGetLastError(), "est_wave_selftest_kernel");
-    rc = rc || check(hipMemcpy(host_out, d, 13 * 64 * 4, hipMemcpyDeviceToHost), "hipMemcpy");
-    (void)hipFree(d);
-    return rc;
-}
-
-// Workgroups of the simulation kernel that the runtime expects to fit on one compute unit for a
-// given LDS size per wavefront (diagnostics).
-extern "C" int est_debug_occupancy(uint32_t lds_bytes_per_wave) {
-    int blocks = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_kernel<false, 4>, 64 * EST_WAVES_PER_BLOCK,
-                                                     (size_t)lds_bytes_per_wave * EST_WAVES_PER_BLOCK) != hipSuccess)
-        return -1;
-    return blocks;
-}

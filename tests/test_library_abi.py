@@ -35,6 +35,15 @@ def test_exports_every_declared_symbol(lib):
     assert sorted(binding.SYMBOLS) == names
 
 
+def test_exports_nothing_the_header_does_not_declare():
+    """Every dynamic function symbol the library defines with C linkage is declared in include/estimator.h."""
+    import subprocess
+    out = subprocess.check_output(["nm", "-D", "--defined-only", binding.LIB_PATH], text=True)
+    exported = sorted(parts[2] for parts in (l.split() for l in out.splitlines())
+                      if len(parts) == 3 and parts[1] in "TW" and not parts[2].startswith("_"))
+    assert exported == _declared_functions(), exported
+
+
 def test_create_rejects_bad_arguments_before_touching_the_device(lib):
     h = ctypes.c_void_p()
     assert lib.estimator_create(None, None, ctypes.byref(h)) == binding.EST_EINVAL
