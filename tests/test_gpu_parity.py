@@ -36,6 +36,7 @@ def test_wave_primitive_lane_layout():
     """The data-parallel-primitive moves the kernels rely on (lane +-1, lane ^ 1/2/4/8) and the bitonic
     network built from them, checked lane by lane on the device (in-bounds, one wavefront)."""
     import ctypes
+    import torch  # noqa: F401  (PyTorch's copy of the HIP runtime first, so that this library binds to the same instance)
     lib = ctypes.CDLL(os.path.join(os.path.dirname(__file__), "selftest", "libwave_selftest.so"))  # test-only library
     out = np.zeros((13, 64), np.uint32)
     assert lib.est_selftest_wave(ctypes.c_void_p(out.ctypes.data)) == 0
