@@ -46,6 +46,7 @@ extern "C" {
 #define EST_MAX_STAGES 32
 #define EST_MAX_BATCH 64
 #define EST_MAX_REPLICAS 64
+#define EST_STATIC_SCRATCH_BYTES (64u << 20) /* fixed scratch of estimator_run_static_dev, per GPU           */
 #define EST_MAX_MERGE_SOURCES 8 /* most distinct nearest visited ancestors feeding one stage        */
 #define EST_HORIZON_US 0xFFFFFFFFu /* every computed time is min(true time, horizon)                */
 
@@ -131,6 +132,20 @@ int estimator_run(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_
 int estimator_run_dev(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *configs,
                       uint64_t n_cfg, uint32_t slo_us, est_result_t *out, void *workspace,
                       uint64_t workspace_bytes, void *hip_stream);
+
+/*
+ * estimator_run_dev for callers that cannot allocate device memory (code that must not call hipMalloc:
+ * tight serving loops, harnesses that forbid it): the scratch is a fixed array of
+ * EST_STATIC_SCRATCH_BYTES bytes inside the library's device code, which every GPU the library runs on
+ * holds until the process ends, and the call makes no hipMalloc, hipFree or other allocating call (the
+ * events and the page-locked staging it needs were made by estimator_create).  Arguments, results and
+ * errors as estimator_run_dev with that scratch; EST_ENOMEM, with the sizes in estimator_last_error,
+ * when the fixed scratch cannot hold the run's per-query tables plus one candidate
+ * (estimator_workspace_bytes(h, n, 1) says what a run needs at least).  All calls on one GPU share the
+ * array, from any handle: calls that overlap in time on one GPU race.  Nothing is kept in it between calls.
+ */
+int estimator_run_static_dev(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *configs,
+                             uint64_t n_cfg, uint32_t slo_us, est_result_t *out, void *hip_stream);
 
 /*
  * Per-query latencies (Section 4.2: the Estimator returns the latency of each query), for

@@ -30,6 +30,12 @@ void *stream_create();            // a second stream at the default priority; nu
 void stream_destroy(void *stream);
 int stream_wait_event(void *stream, void *ev);  // later work on stream starts after ev has completed
 
+// The library's own fixed scratch on the current device (a file-scope device array, resolved once per
+// device): its address and size, or nullptr with last_error() set.  Nothing is allocated.
+void *static_scratch(uint64_t *bytes);
+void *host_pinned_alloc(size_t bytes);  // page-locked host memory; nullptr on failure
+void host_pinned_free(void *p);
+
 void *event_create();
 void event_destroy(void *ev);
 int event_record(void *ev, void *stream);

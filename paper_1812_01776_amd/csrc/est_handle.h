@@ -19,6 +19,10 @@ struct estimator {
     uint64_t *d_cost = nullptr;
     EstPlan *d_plan = nullptr;
     EstStatus *d_status = nullptr;
+    // made once, so that a run that must not allocate has them: events, page-locked staging for the plan
+    // going up and the status words coming back
+    void *ev[8] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    struct Staging { EstStatus st[2]; EstPlan plan; } *pin = nullptr;
     void *ws = nullptr;  // scratch allocated by the library when the caller passes none
     size_t ws_bytes = 0;
     std::string err;

@@ -244,14 +244,17 @@ struct DevBuf {
 int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t *d_mask,
              const est_stage_cfg_t *d_cfg, uint64_t n_cfg, uint32_t slo_us, int mode, uint32_t *d_p99,
              uint32_t *d_miss, uint64_t *d_cost, uint32_t *d_lat_out, void *workspace, uint64_t workspace_bytes,
-             void *stream) {
+             void *stream, bool no_alloc = false) {
     if (n >= (1ull << 31)) return fail(h, EST_EINVAL, "trace too long (%llu queries)", (unsigned long long)n);
     if (n_cfg >= (1ull << 31)) return fail(h, EST_EINVAL, "too many configurations");
     if (n_cfg == 0) return EST_OK;
     const uint32_t S = h->dag.S;
+    // (a run that must not allocate uses the handle's events and page-locked staging, and no diagnostics buffer)
     EventSet evs;
-    void *ev_p0 = evs.make(), *ev_p1 = evs.make(), *ev_p2 = evs.make(), *ev_p3 = evs.make();
+    void *ev_p0 = no_alloc ? h->ev[0] : evs.make(), *ev_p1 = no_alloc ? h->ev[1] : evs.make(), *ev_p2 = no_alloc ? h->ev[2] : evs.make(),
+         *ev_p3 = no_alloc ? h->ev[3] : evs.make();
     if (!ev_p0 || !ev_p1 || !ev_p2 || !ev_p3) return dev_fail(h, "event create");
+    if (no_alloc && !workspace) return fail(h, EST_EINTERNAL, "no scratch");
 
     // ---- scan the configurations and the trace
     if (estbe::zero(h->d_status, sizeof(EstStatus), stream)) return dev_fail(h, "clear status");
@@ -271,7 +274,8 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     pa.status = h->d_status;
     if (n > 0 && estbe::launch_prep1(pa, stream)) return dev_fail(h, "trace scan");
     estbe::event_record(ev_p1, stream);
-    EstStatus st;
+    EstStatus st_local;
+    EstStatus &st = no_alloc ? h->pin->st[0] : st_local;
     if (estbe::d2h(&st, h->d_status, sizeof st, stream) || estbe::sync(stream)) return dev_fail(h, "read status");
     if (st.bad_cfg) return fail(h, EST_EINVAL, "a configuration entry is out of range (hw < %u, 1 <= batch <= %u, 1 <= replicas <= %d)",
                                 h->dag.H, h->dag.Bmax, EST_MAX_REPLICAS);
@@ -352,7 +356,12 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     // ---- per-query tables
     estbe::event_record(ev_p2, stream);
     if (n > 0) {
-        if (estbe::h2d(h->d_plan, &po.plan, sizeof(EstPlan), stream)) return dev_fail(h, "upload plan");
+        const EstPlan *plan_src = &po.plan;
+        if (no_alloc) {
+            h->pin->plan = po.plan;
+            plan_src = &h->pin->plan;
+        }
+        if (estbe::h2d(h->d_plan, plan_src, sizeof(EstPlan), stream)) return dev_fail(h, "upload plan");
         pa.trace_keys = (uint64_t *)(ws + o_keys);
         pa.acc = ws + o_acc;
         pa.acc_stride = n_pad;
@@ -375,8 +384,8 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     DevBuf dbg_buf;
     uint64_t *dbg_ticks = nullptr;
     const uint64_t dbg_words = n_cfg * (1 + 8 * EST_MAX_STAGES);  // per candidate: ticks, then 8 counters per stage
-    if (dbg_path && n > 0 && dbg_buf.alloc(dbg_words * 8) && !estbe::zero(dbg_buf.p, dbg_words * 8, stream)) dbg_ticks = (uint64_t *)dbg_buf.p;
-    void *e0 = evs.make(), *e1 = evs.make();
+    if (dbg_path && !no_alloc && n > 0 && dbg_buf.alloc(dbg_words * 8) && !estbe::zero(dbg_buf.p, dbg_words * 8, stream)) dbg_ticks = (uint64_t *)dbg_buf.p;
+    void *e0 = no_alloc ? h->ev[4] : evs.make(), *e1 = no_alloc ? h->ev[5] : evs.make();
     if (!e0 || !e1) return dev_fail(h, "event create");
     estbe::event_record(e0, stream);
     {
@@ -418,7 +427,8 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
             if (estbe::launch_sim(sa, stream)) return dev_fail(h, "simulation kernel");
     }
     estbe::event_record(e1, stream);
-    EstStatus st2;
+    EstStatus st2_local;
+    EstStatus &st2 = no_alloc ? h->pin->st[1] : st2_local;
     if (estbe::d2h(&st2, h->d_status, sizeof st2, stream) || estbe::sync(stream)) return dev_fail(h, "run");
     if (st2.sim_error) return fail(h, EST_EINTERNAL, "the simulation kernel stopped without finishing a candidate");
     if (dbg_ticks) {
@@ -900,10 +910,17 @@ int estimator_create(const est_dag_t *dag, const est_profiles_t *prof, estimator
     h->d_cost = (uint64_t *)estbe::dmalloc(h->cost.size() * 8);
     h->d_plan = (EstPlan *)estbe::dmalloc(sizeof(EstPlan));
     h->d_status = (EstStatus *)estbe::dmalloc(sizeof(EstStatus));
-    if (!h->d_dag || !h->d_lat || !h->d_cost || !h->d_plan || !h->d_status) {
+    h->pin = (estimator::Staging *)estbe::host_pinned_alloc(sizeof(estimator::Staging));
+    bool have_ev = true;
+    for (void *&e : h->ev) {
+        e = estbe::event_create();
+        have_ev = have_ev && e != nullptr;
+    }
+    if (!h->d_dag || !h->d_lat || !h->d_cost || !h->d_plan || !h->d_status || !h->pin || !have_ev) {
         estimator_destroy(h);
         return EST_ENOMEM;
     }
+    (void)estbe::static_scratch(nullptr);  // resolve the fixed scratch's address on this device now (a run asks again for its own device)
     if (estbe::h2d(h->d_dag, &h->dag, sizeof(EstDag), nullptr) || estbe::h2d(h->d_lat, h->lat.data(), nl * 4, nullptr) ||
         estbe::h2d(h->d_cost, h->cost.data(), h->cost.size() * 8, nullptr) || estbe::sync(nullptr)) {
         estimator_destroy(h);
@@ -921,6 +938,24 @@ int estimator_run_dev(estimator_t *h, const est_trace_t *trace, const est_stage_
     try {
         return run_core(h, trace->n, trace->arrival_us, trace->visit_mask, configs, n_cfg, slo_us, MODE_P99, out ? out->p99_us : nullptr,
                         out ? out->miss_count : nullptr, out ? out->cost_uusd_hr : nullptr, nullptr, workspace, workspace_bytes, hip_stream);
+    } catch (const std::bad_alloc &) {
+        return fail(h, EST_ENOMEM, "host allocation failed");
+    } catch (...) {
+        return fail(h, EST_EINTERNAL, "unexpected exception");
+    }
+}
+
+int estimator_run_static_dev(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *configs, uint64_t n_cfg,
+                             uint32_t slo_us, est_result_t *out, void *hip_stream) {
+    int rc = check_run_args(h, trace, configs, n_cfg);
+    if (rc != EST_OK) return rc;
+    if (n_cfg > 0 && (!out || !out->p99_us || !out->miss_count || !out->cost_uusd_hr)) return fail(h, EST_EINVAL, "result arrays are NULL");
+    uint64_t bytes = 0;
+    void *scratch = estbe::static_scratch(&bytes);  // this device's copy of the fixed array (resolved on first use, no allocation)
+    if (!scratch) return dev_fail(h, "fixed scratch");
+    try {
+        return run_core(h, trace->n, trace->arrival_us, trace->visit_mask, configs, n_cfg, slo_us, MODE_P99, out ? out->p99_us : nullptr,
+                        out ? out->miss_count : nullptr, out ? out->cost_uusd_hr : nullptr, nullptr, scratch, bytes, hip_stream, true);
     } catch (const std::bad_alloc &) {
         return fail(h, EST_ENOMEM, "host allocation failed");
     } catch (...) {
@@ -1076,6 +1111,9 @@ void estimator_destroy(estimator_t *h) {
     if (h->d_plan) estbe::dfree(h->d_plan);
     if (h->d_status) estbe::dfree(h->d_status);
     if (h->ws) estbe::dfree(h->ws);
+    if (h->pin) estbe::host_pinned_free(h->pin);
+    for (void *e : h->ev)
+        if (e) estbe::event_destroy(e);
     delete h;
 }
 

@@ -59,6 +59,13 @@ __global__ __launch_bounds__(256) void est_cfg_kernel(EstCfgArgs a) {
     estdev::cfg_thread(a, blockIdx.x * blockDim.x + threadIdx.x, gridDim.x * blockDim.x);
 }
 
+// Scratch of estimator_run_static_dev, the entry point for callers that cannot allocate: every GPU the
+// library runs on holds this array until the process ends.  In host code the array's name is only a
+// symbol: its device address is asked for once per device (static_scratch below) and used from then on.
+static __device__ __align__(256) unsigned char scratch[EST_STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+void *g_scratch_ptr[MAX_DEVICES];
+
 uint32_t blocks_for(uint64_t items, uint32_t per_block, uint32_t max_blocks) {
     uint64_t b = (items + per_block - 1) / per_block;
     if (b < 1) b = 1;
@@ -171,6 +178,29 @@ void *stream_create() {
 }
 void stream_destroy(void *stream) { (void)hipStreamDestroy((hipStream_t)stream); }
 int stream_wait_event(void *stream, void *ev) { return check(hipStreamWaitEvent((hipStream_t)stream, (hipEvent_t)ev, 0), "hipStreamWaitEvent"); }
+
+void *static_scratch(uint64_t *bytes) {
+    int dev = 0;
+    if (check(hipGetDevice(&dev), "hipGetDevice")) return nullptr;
+    if (dev < 0 || dev >= MAX_DEVICES) {
+        g_err = "device index out of range for the static scratch";
+        return nullptr;
+    }
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (check(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)")) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    if (bytes) *bytes = EST_STATIC_SCRATCH_BYTES;
+    return g_scratch_ptr[dev];
+}
+
+void *host_pinned_alloc(size_t bytes) {
+    void *p = nullptr;
+    if (check(hipHostMalloc(&p, bytes, hipHostMallocDefault), "hipHostMalloc")) return nullptr;
+    return p;
+}
+void host_pinned_free(void *p) { (void)hipHostFree(p); }
 
 void *event_create() {
     hipEvent_t e = nullptr;

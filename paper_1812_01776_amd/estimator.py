@@ -13,6 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libestimator.so")
 
 EST_OK, EST_EINVAL, EST_ENOMEM, EST_EDEVICE, EST_EUNSUPPORTED, EST_EINTERNAL = 0, -1, -2, -3, -4, -5
+EST_STATIC_SCRATCH_BYTES = 64 << 20  # fixed scratch of estimator_run_static_dev (include/estimator.h)
 _ERR_NAMES = {-1: "EST_EINVAL", -2: "EST_ENOMEM", -3: "EST_EDEVICE", -4: "EST_EUNSUPPORTED", -5: "EST_EINTERNAL"}
 
 CFG_DTYPE = np.dtype([("hw", "u1"), ("batch", "u1"), ("replicas", "<u2")])
@@ -20,7 +21,7 @@ CFG_DTYPE = np.dtype([("hw", "u1"), ("batch", "u1"), ("replicas", "<u2")])
 SYMBOLS = ["estimator_create", "estimator_run", "estimator_run_dev", "estimator_run_latencies",
            "estimator_run_latencies_dev", "estimator_workspace_bytes", "estimator_last_stats",
            "estimator_last_error", "estimator_destroy", "estimator_plan", "estimator_tuner_handoff",
-           "estimator_run_shared_dev"]
+           "estimator_run_shared_dev", "estimator_run_static_dev"]
 
 
 class EstimatorError(RuntimeError):
@@ -93,6 +94,7 @@ def load_library(path=LIB_PATH):
     lib.estimator_plan.restype = ctypes.c_int
     lib.estimator_tuner_handoff.restype = ctypes.c_int
     lib.estimator_run_shared_dev.restype = ctypes.c_int
+    lib.estimator_run_static_dev.restype = ctypes.c_int
     return lib
 
 
@@ -227,6 +229,17 @@ class Estimator:
                                                 ctypes.c_uint64(n_cfg), ctypes.c_uint32(slo_us), ctypes.byref(res), ws_ptr,
                                                 ctypes.c_uint64(ws_len), ctypes.c_void_p(st.cuda_stream)))
         return {"p99_us": p99[:n_cfg], "miss_count": miss[:n_cfg], "cost_uusd_hr": cost[:n_cfg]}
+
+    def run_static_dev(self, arrival_t, mask_t, cfg_t, n_cfg, slo_us, p99_t, miss_t, cost_t, stream=None):
+        """run_dev through the entry point that allocates nothing: the caller passes the result tensors
+        too (int32 [n_cfg], int32 [n_cfg], int64 [n_cfg], CUDA), the scratch is the library's fixed array."""
+        import torch
+        tr = _Trace(arrival_t.numel(), ctypes.c_void_p(arrival_t.data_ptr()), ctypes.c_void_p(mask_t.data_ptr()))
+        res = _Result(ctypes.c_void_p(p99_t.data_ptr()), ctypes.c_void_p(miss_t.data_ptr()), ctypes.c_void_p(cost_t.data_ptr()))
+        st = stream if stream is not None else torch.cuda.current_stream(arrival_t.device)
+        self._check(self._lib.estimator_run_static_dev(self._h, ctypes.byref(tr), ctypes.c_void_p(cfg_t.data_ptr()),
+                                                       ctypes.c_uint64(n_cfg), ctypes.c_uint32(slo_us), ctypes.byref(res),
+                                                       ctypes.c_void_p(st.cuda_stream)))
 
     def run_shared_dev(self, arrival_t, mask_t, bases_t, n_bases, cfg_t, base_of_t, n_cfg, slo_us, stream=None):
         """run_dev for candidates that share upstream stages with bases: bases_t like cfg_t

@@ -144,6 +144,14 @@ void *stream_create() { return malloc(1); }  // everything runs in program order
 void stream_destroy(void *s) { free(s); }
 int stream_wait_event(void *, void *) { return 0; }
 
+void *static_scratch(uint64_t *bytes) {
+    static std::vector<unsigned char> buf(EST_STATIC_SCRATCH_BYTES + 256);
+    if (bytes) *bytes = EST_STATIC_SCRATCH_BYTES;
+    return (void *)(((uintptr_t)buf.data() + 255) & ~(uintptr_t)255);
+}
+void *host_pinned_alloc(size_t bytes) { return malloc(bytes ? bytes : 1); }
+void host_pinned_free(void *p) { free(p); }
+
 void *event_create() { return malloc(1); }
 void event_destroy(void *e) { free(e); }
 int event_record(void *, void *) { return 0; }
