@@ -378,26 +378,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     uint32_t wr = wv::uniform(c.st[P.wr_off + op.out_ring]);
     uint32_t space = wv::uniform(ring_space(c, op.out_ring, wr));
     bool progress = false, finished = false;
-#ifdef EST_EMU_CHECKS
-    uint32_t chk_wr = wr;  // everything written from here on is verified to be in order, step by step
-    int chk_path = 0;
-#define EST_CHK_ORDER(tag)                                                                             \
-    do {                                                                                               \
-        wv::sync();                                                                                    \
-        if (ln == 0)                                                                                   \
-            for (uint32_t i_ = chk_wr > 0 ? chk_wr : 1; i_ < wr; ++i_) {                               \
-                const uint64_t a_ = out[(i_ - 1) & omask], b_ = out[i_ & omask];                       \
-                if ((uint32_t)(b_ >> 32) != 0xFFFFFFFFu && !(a_ < b_)) {                               \
-                    fprintf(stderr, "order violated by path %d at out[%u]: %llx then %llx (stage %u)\n", tag, i_, (unsigned long long)a_, (unsigned long long)b_, s); \
-                    abort();                                                                           \
-                }                                                                                      \
-            }                                                                                          \
-        chk_wr = wr;                                                                                   \
-        (void)chk_path;                                                                                \
-    } while (0)
-#else
-#define EST_CHK_ORDER(tag) ((void)0)
-#endif
+    EST_CHK_ORDER_INIT();  // (host-side emulation only: everything written from here on is verified to be in order, step by step)
     uint32_t fp_skip = 0;   // general batches still to do before the light-load shortcut is tried again
     uint32_t sat_skip = 0;  // the same for the backlog shortcut
     uint32_t single_skip = 0;  // and for the one-query-per-batch shortcut

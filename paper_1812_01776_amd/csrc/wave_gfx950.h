@@ -8,6 +8,8 @@
 #define EST_DEV_NOINLINE __device__ __attribute__((noinline))
 #define EST_UNROLL _Pragma("unroll")
 #define EST_CHECK(cond) ((void)0)
+#define EST_CHK_ORDER_INIT() ((void)0)
+#define EST_CHK_ORDER(tag) ((void)0)
 
 namespace wv {
 

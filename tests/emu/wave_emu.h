@@ -21,6 +21,23 @@
         }                                                                                     \
     } while (0)
 
+// Order check of a scan's output (used inside scan_run, where out, omask, wr, ln and s are in scope): after
+// every step, what the step wrote must ascend by (time, query), except at the horizon.
+#define EST_CHK_ORDER_INIT() uint32_t chk_wr = wr
+#define EST_CHK_ORDER(tag)                                                                             \
+    do {                                                                                               \
+        wv::sync();                                                                                    \
+        if (ln == 0)                                                                                   \
+            for (uint32_t i_ = chk_wr > 0 ? chk_wr : 1; i_ < wr; ++i_) {                               \
+                const uint64_t a_ = out[(i_ - 1) & omask], b_ = out[i_ & omask];                       \
+                if ((uint32_t)(b_ >> 32) != 0xFFFFFFFFu && !(a_ < b_)) {                               \
+                    fprintf(stderr, "order violated by path %d at out[%u]: %llx then %llx (stage %u)\n", tag, i_, (unsigned long long)a_, (unsigned long long)b_, s); \
+                    abort();                                                                           \
+                }                                                                                      \
+            }                                                                                          \
+        chk_wr = wr;                                                                                   \
+    } while (0)
+
 namespace emu {
 uint32_t lane();
 // all 64 lanes deposit v, then every lane may read any lane's value through the returned array
