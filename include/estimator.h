@@ -240,8 +240,9 @@ int estimator_plan(estimator_t *h, const est_trace_t *trace, uint32_t slo_us, ui
  *           i.e. mu_num = batch * 10^6, mu_den = latency in us).
  *   rho_m = lambda * s_m / (replicas * mu_m), lambda = n / (last arrival - first arrival), s_m = share
  *           of the queries that visit the model (the tuner's replica rule k_m = ceil(r s_m / (mu_m rho_m))
- *           gives back the planned replica count at r = lambda)  = rho_num / rho_den, rho_den == 0
- *           when the trace spans no time.
+ *           gives back the planned replica count at r = lambda)  = rho_num / rho_den; when the trace
+ *           spans no time (fewer than two queries, or all arrivals equal) there is no rate and rho_m is
+ *           reported as 0 / 0: test rho_den before dividing.
  * All ratios are exact integer pairs.  trace and config ([S]) are HOST pointers.
  */
 #define EST_MAX_WINDOWS 32

@@ -417,7 +417,8 @@ extern "C" int estimator_tuner_handoff(estimator_t *h, const est_trace_t *trace,
         r.mu_num[s] = (uint64_t)config[s].batch * 1000000ull;
         r.mu_den[s] = L;
         // lambda s_m / (R mu_m) = (n / span) (visits / n) / (R batch / L) = visits L / (span R batch)   (times in us cancel)
-        r.rho_num[s] = visits * L;
+        // (a trace that spans no time has no rate: 0 / 0, which the caller must test for before dividing)
+        r.rho_num[s] = span ? visits * L : 0;
         r.rho_den[s] = span * config[s].replicas * config[s].batch;
     }
     *out = r;

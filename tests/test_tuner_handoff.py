@@ -43,6 +43,39 @@ def test_envelope_of_evenly_spaced_arrivals():
         assert q == min(n, -(-w // g))  # ceil(w / g) arrivals fit a half-open window of width w
 
 
+def test_ratios_hand_computed():
+    """mu_m and rho_m on numbers worked out by hand.  1,001 arrivals 1,000 us apart span exactly one
+    second, so lambda = 1,001 queries/s.  Model 0: every query, batch 4 in 8,000 us (mu = 4 / 8 ms =
+    500 queries/s) on 3 replicas: rho = 1001 / (3 * 500).  Model 1: every second query (501 of 1,001),
+    batch 1 in 2,500 us (mu = 400/s) on 2 replicas: rho = 1001 * (501 / 1001) / (2 * 400) = 501 / 800.
+    And the identity that gives the ratio its meaning (Section 5): at r = lambda the tuner's rule
+    k_m = ceil(r s_m / (mu_m rho_m)) gives back the planned replicas."""
+    n = 1001
+    arr = (np.arange(n) * 1000).astype(np.uint32)
+    mask = np.where(np.arange(n) % 2 == 0, 3, 1).astype(np.uint32)
+    lat = np.zeros((2, 1, 4), np.uint32)
+    lat[0, 0] = [5000, 6000, 7000, 8000]
+    lat[1, 0] = [2500, 2600, 2700, 2800]
+    cfg = [(0, 4, 3), (0, 1, 2)]
+    (mu0, rho0), (mu1, rho1) = envelope_oracle.ratios(lat, arr, mask, cfg)
+    assert (mu0, rho0) == (Fraction(500), Fraction(1001, 1500))
+    assert (mu1, rho1) == (Fraction(400), Fraction(501, 800))
+    lam = Fraction(1001)
+    for (mu, rho), share, (_, _, replicas) in zip(((mu0, rho0), (mu1, rho1)), (Fraction(1), Fraction(501, 1001)), cfg):
+        k = lam * share / (mu * rho)
+        assert k == replicas and -(-k.numerator // k.denominator) == replicas
+    # the same identity on a random pipeline, for every model
+    w = workloads.random_case(47, S=4, n=500, C=1)
+    triples = [(int(w.cfg_hw[0, s]), int(w.cfg_batch[0, s]), int(w.cfg_replicas[0, s])) for s in range(w.n_stages)]
+    lam = Fraction(500 * 1_000_000, int(w.arrival_us[-1]) - int(w.arrival_us[0]))
+    for s, ((mu, rho), (_, _, replicas)) in enumerate(zip(envelope_oracle.ratios(w.lat_us, w.arrival_us, w.visit_mask, triples), triples)):
+        share = Fraction(int(((w.visit_mask >> s) & 1).sum()), 500)
+        if share:
+            k = lam * share / (mu * rho)
+            assert -(-k.numerator // k.denominator) == replicas
+    assert envelope_oracle.ratios(lat, arr[:1], mask[:1], cfg)[0][1] is None  # no time span, no rate
+
+
 def _same_as_oracle(est, w, ts):
     cfg = binding.pack_configs(w.cfg_hw[:1], w.cfg_batch[:1], w.cfg_replicas[:1])[0]
     got = est.tuner_handoff(w.arrival_us, w.visit_mask, cfg, ts)
@@ -68,7 +101,7 @@ def test_handoff_rejects_bad_arguments():
         est.tuner_handoff(w.arrival_us, w.visit_mask, cfg, 0)
     assert ei.value.code == binding.EST_EINVAL
     one = est.tuner_handoff(w.arrival_us[:1], w.visit_mask[:1], cfg, 5)  # a single query: no time span
-    assert one["max_queries"][0] == 1 and all(rd == 0 for _, rd in one["rho"])
+    assert one["max_queries"][0] == 1 and all((rn, rd) == (0, 0) for rn, rd in one["rho"])
 
 
 @pytest.mark.gpu
