@@ -70,6 +70,12 @@ EST_DEV uint64_t *est_dbg_rec(const EstSimArgs *a, uint32_t t, uint32_t s) {
     return a->dbg_ticks + a->n_cfg + ((uint64_t)t * EST_MAX_STAGES + s) * 8;
 }
 
+// Ring cursors and the other state words of a candidate are written by the operation that owns them and read
+// by its neighbours, which may run in another wavefront of the workgroup (several wavefronts per candidate):
+// they are read and written through these (the value is the same in every lane).
+EST_DEV uint32_t ld_st(const uint32_t *p) { return wv::load_shared(p); }
+EST_DEV void st_st(uint32_t *p, uint32_t v) { wv::store_shared(p, v); }
+
 struct View {
     const uint64_t *base;
     uint32_t mask, wr, fin;
@@ -93,8 +99,8 @@ EST_DEV View view_of(const Ctx &c, int32_t ring) {
         const EstRing &R = c.P->rings[ring];
         v.base = c.rings + R.off;
         v.mask = R.cap_mask;
-        v.wr = c.st[c.P->wr_off + ring];
-        v.fin = c.st[c.P->fin_off + ring];
+        v.fin = ld_st(&c.st[c.P->fin_off + ring]);  // (before the cursor: a stream seen as ended is seen whole)
+        v.wr = ld_st(&c.st[c.P->wr_off + ring]);
     }
     return v;
 }
@@ -114,7 +120,7 @@ EST_DEV View uniform_view_of(const Ctx &c, int32_t ring) {
 EST_DEV uint32_t ring_space(const Ctx &c, int32_t ring, uint32_t wr) {
     const EstRing &R = c.P->rings[ring];
     uint32_t used = 0;
-    for (uint32_t i = 0; i < R.n_cons; ++i) used = umax(used, wr - c.st[c.P->rd_off + R.cons_edge[i]]);
+    for (uint32_t i = 0; i < R.n_cons; ++i) used = umax(used, wr - ld_st(&c.st[c.P->rd_off + R.cons_edge[i]]));
     EST_CHECK(used <= R.cap_mask + 1u);
     return R.cap_mask + 1u - used;
 }
@@ -1108,11 +1114,12 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             }
         }
     }
+    wv::sync();  // what was written to the output ring is in place before its cursor moves
     if (ln == 0) {
-        c.st[P.rd_off + op.src_edge[0]] = cursor;
-        c.st[P.wr_off + op.out_ring] = wr;
+        st_st(&c.st[P.rd_off + op.src_edge[0]], cursor);
+        st_st(&c.st[P.wr_off + op.out_ring], wr);
         if (finished) {
-            c.st[P.fin_off + op.out_ring] = 1;
+            st_st(&c.st[P.fin_off + op.out_ring], 1);
             c.st[P.done_off + opi] = 1;
         }
     }
@@ -1196,7 +1203,7 @@ EST_UNROLL
             rc += umin(left, 256u);
             progress = true;
         }
-        if (ln == 0) c.st[P.rd_off + op.src_edge[0]] = rc;
+        if (ln == 0) st_st(&c.st[P.rd_off + op.src_edge[0]], rc);
     } else {
         // Several sources.  A query fed by several of them is ready at the largest of its times: of its
         // elements only the one with the largest key (time, query; equal times: the higher source) is passed
@@ -1414,20 +1421,21 @@ EST_UNROLL
         }
         // staged but not consumed: read again next time
         if (ln == 0)
-            for (uint32_t j = 0; j < K; ++j) c.st[P.rd_off + op.src_edge[j]] = s_rd[j] - (s_tail[j] - s_head[j]);
+            for (uint32_t j = 0; j < K; ++j) st_st(&c.st[P.rd_off + op.src_edge[j]], s_rd[j] - (s_tail[j] - s_head[j]));
     }
 
     if (DIAG && c.a->dbg_ticks && ln == 0) { uint64_t *po = est_dbg_rec(c.a, c.t, EST_MAX_STAGES - 1); po[3] += d_rounds; po[4] += d_elems; po[5] += 1; }
     const uint32_t miss_all = is_lat ? wv::sum_u32(miss) : 0u;
+    wv::sync();  // what was written to the output ring is in place before its cursor moves
     if (ln == 0) {
         if (is_lat) {
             c.st[P.miss_off + 1] = wr;
             c.st[P.miss_off] += miss_all;
         } else {
-            c.st[P.wr_off + op.out_ring] = wr;
+            st_st(&c.st[P.wr_off + op.out_ring], wr);
         }
         if (finished) {
-            if (!is_lat) c.st[P.fin_off + op.out_ring] = 1;
+            if (!is_lat) st_st(&c.st[P.fin_off + op.out_ring], 1);
             c.st[P.done_off + opi] = 1;
         }
     }
@@ -1440,13 +1448,10 @@ EST_UNROLL
 // One wavefront = one candidate.  Every loop ends: an operation that consumes or emits nothing
 // reports no progress, and a full pass over the operations without progress stops the candidate with
 // an error flag.
-template <bool DIAG, bool MEMO>
-EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *lds) {
-    const uint32_t ln = wv::lane();
-    const EstPlan &P = *a.plan;
+EST_DEV Ctx make_ctx(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *lds) {
     Ctx c;
     c.a = &a;
-    c.P = &P;
+    c.P = a.plan;
     c.st = a.state + (uint64_t)slot * a.state_stride;
     c.rings = a.rings + (uint64_t)slot * a.ring_stride;
     c.rep = a.rep + (uint64_t)slot * a.rep_stride;
@@ -1456,19 +1461,39 @@ EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *
     c.cfg = a.cfg + (uint64_t)t * a.dag->S;
     c.lds = lds;
     c.t = t;
+    c.memo_rings = 0;
+    c.cap_rings = nullptr;
+    return c;
+}
 
+// A candidate's scratch before its first operation: cursors and flags zero, every replica idle at t = 0 and
+// owning one slot, no element of any joined stream looked at yet.
+EST_DEV void sim_init(const EstSimArgs &a, const Ctx &c) {
+    const uint32_t ln = wv::lane();
+    const EstPlan &P = *c.P;
     for (uint32_t i = ln; i < P.state_words; i += 64) c.st[i] = 0;
     for (uint64_t i = ln; i < a.rep_stride; i += 64) c.rep[i] = 0;
     wv::sync();
-    for (uint32_t opi = 0; opi < P.n_ops; ++opi) {  // every replica starts idle at t = 0 and owns one slot
+    for (uint32_t opi = 0; opi < P.n_ops; ++opi) {
         const EstOp &op = P.ops[opi];
         if (op.type == EST_OP_SCAN && ln < op.r_max) c.rep[op.rep_off + 2 * op.r_max + ln] = ln;
     }
     {
-        uint32_t *tw = (uint32_t *)c.tab;  // no element of any joined stream has been looked at yet
+        uint32_t *tw = (uint32_t *)c.tab;
         for (uint64_t i = ln; i < a.tab_stride / 4; i += 64) tw[i] = 0xFFFFFFFFu;
     }
     wv::sync();
+}
+
+// One wavefront = one candidate.  Every loop ends: an operation that consumes or emits nothing
+// reports no progress, and a full pass over the operations without progress stops the candidate with
+// an error flag.
+template <bool DIAG, bool MEMO>
+EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *lds) {
+    const uint32_t ln = wv::lane();
+    const EstPlan &P = *a.plan;
+    Ctx c = make_ctx(a, t, slot, lds);
+    sim_init(a, c);
     c.memo_rings = 0;
     c.cap_rings = nullptr;
     if (MEMO) {
@@ -1518,6 +1543,31 @@ EST_DEV void sim_wave(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *
             break;
         }
     }
+}
+
+// Several wavefronts per candidate (for calls with fewer candidates than the device has room for: the time
+// of such a call is the time of one simulation, Section 4.2).  The operations of the candidate are dealt out
+// to the wavefronts of a workgroup (EstOp::owner), which then run as a pipeline: streams between operations of
+// different wavefronts are the same rings, their cursors read and written through ld_st / st_st.  One call =
+// one pass of wavefront `wave` over its own operations.  Returns bit 0: progress, bit 1: all of them are done.
+EST_DEV void mw_init(const EstSimArgs &a, uint32_t t, uint32_t slot) {
+    const Ctx c = make_ctx(a, t, slot, nullptr);
+    sim_init(a, c);
+}
+
+EST_DEV uint32_t mw_pass(const EstSimArgs &a, uint32_t t, uint32_t slot, uint64_t *lds, uint32_t wave) {
+    const EstPlan &P = *a.plan;
+    const Ctx c = make_ctx(a, t, slot, lds);
+    bool progress = false, alldone = true;
+    for (uint32_t opi = 0; opi < P.n_ops; ++opi) {
+        const EstOp &op = P.ops[opi];
+        if (wv::uniform(op.owner) != wave) continue;
+        if (wv::uniform(c.st[P.done_off + opi])) continue;  // (written by this wavefront only)
+        const bool p = op.type == EST_OP_SCAN ? scan_run<false, false>(c, op, opi) : merge_run<false, false>(c, op, opi);
+        progress = progress || p;
+        alldone = alldone && wv::uniform(c.st[P.done_off + opi]) != 0;
+    }
+    return (progress ? 1u : 0u) | (alldone ? 2u : 0u);
 }
 
 // ------------------------------------------------------------------------------------------ P99

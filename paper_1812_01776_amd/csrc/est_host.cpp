@@ -175,6 +175,25 @@ int build_plan(estimator *h, const EstStatus &st, uint64_t n, PlanOut &po) {
     }
     P.n_ops = no;
     P.n_edges = ne;
+    {
+        // several wavefronts per candidate: the operations, in pipeline order, are cut into EST_MW_WAVES runs of
+        // about equal work (elements an operation reads), so that neighbouring wavefronts are neighbouring pipeline sections
+        std::vector<uint64_t> work(no);
+        uint64_t total = 0;
+        for (uint32_t i = 0; i < no; ++i) {
+            const EstOp &op = P.ops[i];
+            uint64_t wk = 0;
+            for (uint32_t j = 0; j < op.n_src; ++j)
+                wk += op.src_ring[j] == EST_SRC_TRACE ? n : (op.type == EST_OP_SCAN && !op.filtered ? st.n_visit[op.stage] : n);
+            work[i] = std::max<uint64_t>(wk, 1);
+            total += work[i];
+        }
+        uint64_t acc = 0;
+        for (uint32_t i = 0; i < no; ++i) {
+            P.ops[i].owner = (uint32_t)std::min<uint64_t>(EST_MW_WAVES - 1, acc * EST_MW_WAVES / total);
+            acc += work[i];
+        }
+    }
     P.max_src = 1;
     for (uint32_t i = 0; i < no; ++i) P.max_src = std::max(P.max_src, P.ops[i].n_src);
     po.lds_bytes = (uint32_t)align_up(std::max<uint64_t>(EST_LDS_MERGE_BYTES(P.max_src), EST_LDS_SCAN_BYTES(max_rb)), 256);
@@ -339,6 +358,12 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     // would only wait
     uint64_t n_slots = std::min<uint64_t>((ws_bytes - fixed - 8 * 256) / per_cfg, n_cfg);
     n_slots = std::min<uint64_t>(n_slots, std::max<uint32_t>(estbe::max_resident_waves(po.lds_bytes), 1));
+    // A call with so few candidates that most of the device would stay empty gives every candidate a workgroup
+    // of EST_MW_WAVES wavefronts instead of one wavefront (EST_WAVES_PER_CANDIDATE = 1 or 4 overrides the choice).
+    bool several = n > 0 && po.plan.n_ops >= 2 && n_cfg <= n_slots && n_cfg * EST_MW_WAVES <= estbe::max_resident_waves(po.lds_bytes) / 2;
+    if (const char *e = getenv("EST_WAVES_PER_CANDIDATE")) several = n > 0 && atoi(e) == EST_MW_WAVES;
+    if (getenv("EST_DEBUG_TICKS") && !no_alloc) several = false;  // (the step counters are per wavefront)
+    if (several) n_slots = std::min<uint64_t>(n_slots, std::max<uint32_t>(estbe::max_resident_groups(po.lds_bytes), 1));
     uint64_t at = fixed;
     auto area = [&](uint64_t bytes_per_cfg) {
         uint64_t a0 = at;
@@ -424,7 +449,7 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
         sa.dbg_ticks = dbg_ticks;
         sa.p99 = s_p99; sa.miss = s_miss; sa.cost = s_cost;
         if (mode == MODE_P99 || n > 0)
-            if (estbe::launch_sim(sa, stream)) return dev_fail(h, "simulation kernel");
+            if (several ? estbe::launch_sim_mw(sa, stream) : estbe::launch_sim(sa, stream)) return dev_fail(h, "simulation kernel");
     }
     estbe::event_record(e1, stream);
     EstStatus st2_local;
@@ -449,6 +474,7 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     memset(&ss, 0, sizeof ss);
     ss.n_launches = 1;
     ss.n_slots = (uint32_t)n_slots;
+    ss.waves_per_candidate = several ? EST_MW_WAVES : 1;
     ss.sim_ms = estbe::event_ms(e0, e1);
     ss.prep_ms = estbe::event_ms(ev_p0, ev_p1) + estbe::event_ms(ev_p2, ev_p3);
     for (uint32_t s = 0; s < S; ++s) ss.stage_visits += st.n_visit[s];
@@ -820,6 +846,7 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
     est_stats_t &ss = h->stats;
     memset(&ss, 0, sizeof ss);
     ss.n_launches = (uint32_t)((capture ? 2 : 1) * n_rounds);
+    ss.waves_per_candidate = 1;
     ss.n_slots = (uint32_t)n_slots;
     ss.capture_ms = capture_ms;
     ss.sim_ms = estbe::event_ms(e0, e2);

@@ -34,6 +34,48 @@ void est_sim_kernel(EstSimArgs a) {
     if (slot < a.n_slots) estdev::slot_loop<DIAG, MEMO>(a, slot, lds + (size_t)wave * (a.lds_bytes / 8));
 }
 
+// Several wavefronts per candidate: a workgroup of EST_MW_WAVES wavefronts owns one scratch slot and takes
+// candidates from the work counter; the candidate's operations are dealt out to the wavefronts (EstOp::owner),
+// which run them as a pipeline through the rings.  A wavefront that finds nothing to do waits a little and looks
+// again; every wait is bounded (a stuck candidate sets the error flag and every wavefront leaves).
+constexpr uint32_t MW_IDLE_LIMIT = 1u << 24;
+__global__ __launch_bounds__(64 * EST_MW_WAVES) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void est_sim_mw_kernel(EstSimArgs a) {
+    extern __shared__ uint64_t lds[];  // EST_MW_WAVES x a.lds_bytes
+    __shared__ uint32_t next_t;
+    const uint32_t wave = threadIdx.x >> 6;
+    const uint32_t slot = blockIdx.x;
+    uint64_t *my_lds = lds + (size_t)wave * (a.lds_bytes / 8);
+    for (;;) {
+        if (threadIdx.x == 0) next_t = atomicAdd(&a.status->next_cfg, 1u);
+        __syncthreads();
+        const uint32_t t = next_t;
+        __syncthreads();
+        if (t >= a.n_cfg) break;
+        if (a.n > 0) {
+            if (wave == 0) estdev::mw_init(a, t, slot);
+            __syncthreads();
+            for (uint32_t idle = 0;;) {
+                const uint32_t r = estdev::mw_pass(a, t, slot, my_lds, wave);
+                if (r & 2u) break;
+                if (r & 1u) {
+                    idle = 0;
+                    continue;
+                }
+                // waiting for a neighbour: give the other wavefronts the issue slots, give up if it never comes
+                if (++idle > MW_IDLE_LIMIT || wv::load_shared(&a.status->sim_error)) {
+                    if (wv::lane() == 0) a.status->sim_error = 1;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(4);
+            }
+        }
+        __syncthreads();
+        if (wave == 0 && !a.lat_by_qid) estdev::select_wave(a, t, slot, my_lds);
+        __syncthreads();
+    }
+}
+
 // The kernel is built for four wavefronts per SIMD (128 registers per lane) and for five (96 registers, a
 // few spills): the second is used when the LDS need of the launch lets five workgroups share a compute
 // unit, where the extra wavefront hides more latency than the spills cost.
@@ -135,6 +177,20 @@ int launch_prep2(const EstPrepArgs &a, void *stream) {
 int launch_envelope(const EstEnvArgs &a, void *stream) {
     est_envelope_kernel<<<blocks_for(a.n, 256 * 16, 8192), 256, 0, (hipStream_t)stream>>>(a);  // 16 queries in a row per thread
     return check(hipGetLastError(), "est_envelope_kernel");
+}
+int launch_sim_mw(const EstSimArgs &a, void *stream) {
+    const size_t lds = (size_t)a.lds_bytes * EST_MW_WAVES;
+    est_sim_mw_kernel<<<dim3(a.n_slots), dim3(64 * EST_MW_WAVES), lds, (hipStream_t)stream>>>(a);
+    return check(hipGetLastError(), "est_sim_mw_kernel");
+}
+uint32_t max_resident_groups(uint32_t lds_bytes_per_wave) {
+    int dev = 0, cus = 0, blocks = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_mw_kernel, 64 * EST_MW_WAVES, (size_t)lds_bytes_per_wave * EST_MW_WAVES) != hipSuccess ||
+        blocks < 1)
+        blocks = 1;
+    return (uint32_t)cus * (uint32_t)blocks;
 }
 int launch_sim(const EstSimArgs &a, void *stream) {
     const uint32_t blocks = (a.n_slots + EST_WAVES_PER_BLOCK - 1) / EST_WAVES_PER_BLOCK;

@@ -5,6 +5,7 @@
 #include "../../include/estimator.h"  // EST_MAX_STAGES and the other public limits
 
 #define EST_WAVE 64
+#define EST_MW_WAVES 4            // wavefronts that share one candidate in calls that leave the device mostly empty
 #define EST_KMAX EST_MAX_MERGE_SOURCES   // sources of one merge operation (accept masks are 8 bits)
 #define EST_MAX_OPS 72          // <= 2 per stage + the latency sink
 #define EST_MAX_RINGS 66
@@ -43,7 +44,7 @@ struct EstOp {
     uint64_t slot_off;            // SCAN: word offset of the member slots inside one candidate's slot area
     uint32_t b_max;               // SCAN: slot width (largest max-batch of the stage in this run)
     uint32_t filtered;            // SCAN: only the source elements whose accept mask has bit 0 set visit the stage
-    uint32_t rp;                  // SCAN: r_max rounded up to a power of two
+    uint32_t owner;               // which wavefront of the workgroup runs the operation when a candidate has several (0 .. EST_MW_WAVES-1)
     uint32_t pad;
 };
 

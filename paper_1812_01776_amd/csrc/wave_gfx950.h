@@ -101,6 +101,10 @@ EST_DEV void sync_lds() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// A word that another wavefront of the workgroup may write or read (the same address and value in every lane)
+EST_DEV uint32_t load_shared(const uint32_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
+EST_DEV void store_shared(uint32_t *p, uint32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP); }
+
 EST_DEV void lds_add(uint32_t *p, uint32_t v) { atomicAdd(p, v); }
 EST_DEV void atomic_or_u64(uint64_t *p, uint64_t v) { atomicOr((unsigned long long *)p, (unsigned long long)v); }
 EST_DEV void atomic_or_u32(uint32_t *p, uint32_t v) { atomicOr(p, v); }

@@ -69,7 +69,8 @@ PLAN_ACTIONS = ("init", "batch", "replica", "hw")
 class Stats(ctypes.Structure):
     _fields_ = [("n_launches", ctypes.c_uint32), ("n_slots", ctypes.c_uint32), ("sim_ms", ctypes.c_float),
                 ("prep_ms", ctypes.c_float), ("stage_visits", ctypes.c_uint64), ("workspace_bytes", ctypes.c_uint64),
-                ("capture_ms", ctypes.c_float), ("ops_run_fraction", ctypes.c_float)]
+                ("capture_ms", ctypes.c_float), ("ops_run_fraction", ctypes.c_float),
+                ("waves_per_candidate", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
 
 def load_library(path=LIB_PATH):

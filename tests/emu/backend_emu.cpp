@@ -138,6 +138,37 @@ int launch_sim(const EstSimArgs &a, void *) {
     }
     return 0;
 }
+// Several wavefronts per candidate: the wavefronts of a workgroup take turns, one pass over their own operations
+// each, until all are done (a full turn without progress is a stuck candidate).
+int launch_sim_mw(const EstSimArgs &a, void *) {
+    static uint64_t lds[EST_MW_WAVES][(64 * 1024) / 8];
+    if (a.lds_bytes > sizeof lds[0]) abort();
+    for (uint32_t t = 0; t < a.n_cfg; ++t) {
+        const uint32_t slot = t % a.n_slots;
+        memset(lds, 0x5A, sizeof lds);
+        if (a.n > 0) {
+            emu::run_wave([&] { estdev::mw_init(a, t, slot); });
+            uint32_t done = 0;
+            while (done != (1u << EST_MW_WAVES) - 1u) {
+                bool progress = false;
+                for (uint32_t wv_ = 0; wv_ < EST_MW_WAVES; ++wv_) {
+                    if ((done >> wv_) & 1u) continue;
+                    uint32_t r = 0;
+                    emu::run_wave([&] { uint32_t x = estdev::mw_pass(a, t, slot, lds[wv_], wv_); if (wv::lane() == 0) r = x; });
+                    if (r & 2u) done |= 1u << wv_;
+                    progress = progress || (r & 3u);
+                }
+                if (!progress) {
+                    a.status->sim_error = 1;
+                    break;
+                }
+            }
+        }
+        if (!a.lat_by_qid) emu::run_wave([&] { estdev::select_wave(a, t, slot, lds[0]); });
+    }
+    return 0;
+}
+uint32_t max_resident_groups(uint32_t) { return 2; }
 uint32_t max_resident_waves(uint32_t) { return 3; }
 
 void *stream_create() { return malloc(1); }  // everything runs in program order here

@@ -113,6 +113,8 @@ EST_DEV uint32_t prefix_excl_u32(uint32_t v) {
     return s;
 }
 
+EST_DEV uint32_t load_shared(const uint32_t *p) { return *(const volatile uint32_t *)p; }
+EST_DEV void store_shared(uint32_t *p, uint32_t v) { *(volatile uint32_t *)p = v; }
 EST_DEV void sync() { (void)emu::exchange(0, 8); }
 EST_DEV void sync_lds() { (void)emu::exchange(0, 16); }  // (memory here is host memory either way)
 

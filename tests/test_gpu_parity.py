@@ -15,6 +15,14 @@ pytestmark = pytest.mark.gpu
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
 
+@pytest.fixture(params=["1", "4"], ids=["wave_per_candidate", "workgroup_per_candidate"])
+def waves(request, monkeypatch):
+    """Both ways a candidate is run: by one wavefront, or (what calls with few candidates get by default) by a
+    workgroup of four wavefronts that share its operations as a pipeline."""
+    monkeypatch.setenv("EST_WAVES_PER_CANDIDATE", request.param)
+    return int(request.param)
+
+
 def _compare(w, latencies=True, est=None):
     own = est is None
     est = est or binding.Estimator(w.parents, w.lat_us, w.cost_uusd_hr)
@@ -59,7 +67,7 @@ def _hand_examples():
 
 
 @pytest.mark.parametrize("ex", _hand_examples(), ids=lambda e: e["name"])
-def test_hand_traces(ex):
+def test_hand_traces(ex, waves):
     S = len(ex["parents"])
     Bm = max(len(x) for x in ex["L"])
     lat = np.array([[list(x) + [x[-1]] * (Bm - len(x))] for x in ex["L"]], dtype=np.uint32)
@@ -73,19 +81,19 @@ def test_hand_traces(ex):
 
 
 @pytest.mark.parametrize("seed", range(60))
-def test_random_dags(seed):
+def test_random_dags(seed, waves):
     _compare(workloads.random_case(seed, tie_heavy=(seed % 2 == 0)))
 
 
 @pytest.mark.parametrize("seed", range(56))
-def test_backlog_lockstep_and_horizon_cases(seed):
+def test_backlog_lockstep_and_horizon_cases(seed, waves):
     """Overloaded pipelines: full batches in rotation, replicas in lock step (tied completions), maximum
     batch size 1 with ties out of query order, queueing that runs into the horizon."""
     _compare(workloads.backlog_case(seed))
 
 
 @pytest.mark.parametrize("seed", range(6))
-def test_wide_batches_many_replicas_ties(seed):
+def test_wide_batches_many_replicas_ties(seed, waves):
     """R up to 16, B up to 64, several thousand queries (bounded rings wrap, ragged tails), times on a
     10-us grid so that batches complete together."""
     _compare(workloads.random_case(100 + seed, S=4, n=6000 + 37 * seed, C=24, max_b=64, max_r=16, tie_heavy=True,
@@ -93,7 +101,7 @@ def test_wide_batches_many_replicas_ties(seed):
 
 
 @pytest.mark.parametrize("seed", range(20))
-def test_bursts_of_large_groups(seed):
+def test_bursts_of_large_groups(seed, waves):
     """Queries that become ready in groups of 4..48, large batches whose service time is several times the
     gap between groups, many batches in flight at once (the light-load step for large groups), with ties
     on a 100-us grid, the fork-join shape, and stages that are short of replicas for part of the trace."""
@@ -101,14 +109,14 @@ def test_bursts_of_large_groups(seed):
 
 
 @pytest.mark.parametrize("seed", range(24))
-def test_provisioned_small_batches_with_tied_completions(seed):
+def test_provisioned_small_batches_with_tied_completions(seed, waves):
     """Pipelines at 80-100 % utilisation with small batches on many replicas downstream of a batching stage
     (the regime around the SLO boundary): groups are cut into several batches that start at the same
     instant, completions tie and leave merged by query index."""
     _compare(workloads.provisioned_case(seed))
 
 
-def test_replica_and_batch_limits():
+def test_replica_and_batch_limits(waves):
     """R = 64 and B = 64, the largest the interface allows."""
     w = workloads.random_case(7, S=2, n=5000, C=4, max_b=64, max_r=4, dag="linear")
     w.cfg_replicas[:] = np.array([[64, 1], [64, 64], [1, 64], [33, 17]], np.uint16)
@@ -116,7 +124,7 @@ def test_replica_and_batch_limits():
     _compare(w)
 
 
-def test_degenerate_inputs():
+def test_degenerate_inputs(waves):
     w = workloads.random_case(3, S=3, n=40, C=3, dag="linear")
     est = binding.Estimator(w.parents, w.lat_us, w.cost_uusd_hr)
     cfg = binding.pack_configs(w.cfg_hw, w.cfg_batch, w.cfg_replicas)
@@ -137,7 +145,7 @@ def test_degenerate_inputs():
     est.close()
 
 
-def test_clock_saturates_at_the_horizon():
+def test_clock_saturates_at_the_horizon(waves):
     rng = np.random.default_rng(1)
     n = 4000
     arr = (np.uint64(3_000_000_000) + np.cumsum(rng.integers(0, 2000, size=n)).astype(np.uint64)).astype(np.uint32)
@@ -266,6 +274,17 @@ def test_w4_full_sweep_sampled_against_oracle():
     est.close()
 
 
+def test_w3_workgroup_per_candidate_long_trace(monkeypatch):
+    """64 candidates of W3 at the full 100,000 queries, each run by a workgroup of four wavefronts (fork, three
+    branches, join): every per-query latency, P99, misses and cost against the live oracle."""
+    monkeypatch.setenv("EST_WAVES_PER_CANDIDATE", "4")
+    w = workloads.w3().subset(cfg_index=np.arange(3, 8192, 128))
+    est = binding.Estimator(w.parents, w.lat_us, w.cost_uusd_hr)
+    _compare(w, est=est)
+    assert est.stats()["waves_per_candidate"] == 4
+    est.close()
+
+
 def test_w4_pipeline_provisioned_candidates_full_trace():
     """W4's pipeline and full trace with 16 candidates provisioned around the SLO boundary (from slightly
     overloaded to comfortably feasible: the regime a planner's search works in): P99, misses, cost and
@@ -277,6 +296,7 @@ def test_w4_pipeline_provisioned_candidates_full_trace():
     est = binding.Estimator(w.parents, w.lat_us, w.cost_uusd_hr)
     cfg = binding.pack_configs(w.cfg_hw, w.cfg_batch, w.cfg_replicas)
     got = est.run(w.arrival_us, w.visit_mask, cfg, w.slo_us)
+    assert est.stats()["waves_per_candidate"] == 4  # (a call this small gives every candidate a workgroup)
     _check_rows(w, exp, got["p99_us"], got["miss_count"], got["cost_uusd_hr"], est, lat_rows=16)
     est.close()
 

@@ -82,6 +82,18 @@ def test_provisioned_small_batches_with_tied_completions_match_oracle(seed):
     _compare(workloads.provisioned_case(seed, n=1500))
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_several_wavefronts_per_candidate_match_oracle(seed, monkeypatch):
+    # the candidate's operations dealt out to four wavefronts that run as a pipeline through the rings
+    monkeypatch.setenv("EST_WAVES_PER_CANDIDATE", "4")
+    w = [workloads.random_case, workloads.backlog_case, workloads.grouped_case, workloads.provisioned_case][seed % 4](seed)
+    if w.n_queries > 1500:
+        w = w.subset(n_queries=1500)
+    est = emu_lib.make(w)
+    _compare(w, est=est)
+    assert est.stats()["waves_per_candidate"] == 4
+
+
 def test_wide_batches_many_replicas_and_ring_wrap():
     """R up to 16, B up to 64 and enough queries for the bounded rings to wrap several times; every
     time a multiple of 10 so that batches complete together and have to be merged by query index."""
