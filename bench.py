@@ -304,7 +304,7 @@ def main():
             finally:
                 del os.environ["EST_DEBUG_TICKS"]
             d = np.fromfile(os.path.join(td, "ticks.bin"), dtype=np.uint64)
-        rec = d[len(sel):].reshape(len(sel), 32, 8).astype(np.float64)
+        rec = d[len(sel):].reshape(len(sel), 32, 16).astype(np.float64)
         stg, oth = rec[:, :S, :], rec[:, 31, :]
         fast, gen = stg[:, :, 3].sum(), oth[:, 7].sum()
         tot = fast + gen

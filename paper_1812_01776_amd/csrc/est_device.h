@@ -62,12 +62,13 @@ struct Ctx {
     const uint64_t *cap_rings;
 };
 
-// Diagnostics record of candidate t and stage s: 8 words (general steps, ticks in the stage's scan, shortcut
-// steps, queries in shortcut steps, of which: lean light-load, light-load, one-per-batch, block of batches).
+// Diagnostics record of candidate t and stage s: EST_DBG_WORDS words (general steps, ticks in the stage's scan,
+// shortcut steps, queries in shortcut steps, of which: lean light-load, light-load, one-per-batch, block of batches;
+// then ticks spent in steps that ended as: lean light-load, light-load, one-per-batch, block, backlog or horizon, general).
 // The record of stage EST_MAX_STAGES-1 holds what belongs to no stage: ticks in merges, in the sink, in the
 // selection, merge rounds, merge output elements, merge calls, scan calls, queries in general steps.
 EST_DEV uint64_t *est_dbg_rec(const EstSimArgs *a, uint32_t t, uint32_t s) {
-    return a->dbg_ticks + a->n_cfg + ((uint64_t)t * EST_MAX_STAGES + s) * 8;
+    return a->dbg_ticks + a->n_cfg + ((uint64_t)t * EST_MAX_STAGES + s) * EST_DBG_WORDS;
 }
 
 // Ring cursors and the other state words of a candidate are written by the operation that owns them and read
@@ -272,6 +273,36 @@ EST_DEV uint32_t emit_tied(const EstOp &op, const uint32_t *lslots, uint64_t tie
     return total;
 }
 
+// Number of lanes whose value is below x (<= x with incl), for values that ascend with the lane: a binary search
+// over the lanes, the same for every lane's own x.
+EST_DEV uint32_t lanes_less(uint32_t v, uint32_t x, bool incl) {
+    uint32_t pos = 0;
+EST_UNROLL
+    for (uint32_t step = 32; step >= 1; step >>= 1) {
+        const uint32_t y = wv::shfl(v, pos + step - 1u);
+        if (incl ? y <= x : y < x) pos += step;
+    }
+    const uint32_t y = wv::shfl(v, 63u);  // (pos is 63 only when the first 63 lanes all pass)
+    if (pos == 63u && (incl ? y <= x : y < x)) pos = 64u;
+    return pos;
+}
+
+// The batches in the table lanes of E (ascending completion times, no two of them equal) written out in table
+// order in one sweep: off (the members of the lanes of E before mine, e.g. from emit_offsets) turns an output
+// position into a batch and a member.  Every member goes to out[base + its position + extra of its batch], where
+// extra is a per-batch displacement (lane = table lane; 0 to write them back to back).
+EST_DEV void emit_many(const EstOp &op, const uint32_t *lslots, uint32_t total, uint32_t off, uint32_t extra, uint32_t rend,
+                       uint32_t rslot, uint64_t *out, uint32_t omask, uint32_t base) {
+    const uint32_t ln = wv::lane();
+    const uint32_t bm = wv::uniform(op.b_max);
+    for (uint32_t i0 = 0; i0 < total; i0 += 64) {
+        const uint32_t i = i0 + ln;
+        const uint32_t l = lanes_less(off, i, true) - 1u;  // the last lane whose batch starts at or before position i
+        const uint32_t o = wv::shfl(off, l), e = wv::shfl(rend, l), sl = wv::shfl(rslot, l), x = wv::shfl(extra, l);
+        if (i < total) out[(base + i + x) & omask] = ((uint64_t)e << 32) | lslots[sl * bm + (i - o)];
+    }
+}
+
 // Older waiting batches (table lanes in woven, ascending completion times, all different from the new
 // ones) leave together with new queries: the new ones, whose completion times are ke in the lanes of emitm,
 // have been placed already, each shifted by the members of the older batches that finish before it; here the
@@ -297,6 +328,42 @@ EST_DEV void weave_out(const EstOp &op, const uint32_t *lslots, uint64_t woven, 
     }
 }
 
+// New queries (their keys in the lanes of emit_me, rank orank among them, ns in all, ascending by rank) leave
+// together with the older waiting batches in the table lanes of woven (extra members in all, completion times
+// different from every new one): everything is written to out[wr ...] in (time, query) order.  With many older
+// batches and no two of them completing together, both sides find their places by binary searches over the
+// other side (lscr: 64 words of LDS scratch); otherwise batch by batch.
+EST_DEV void weave_all(const EstOp &op, const uint32_t *lslots, uint32_t *lscr, uint64_t woven, uint32_t extra, bool emit_me, uint64_t emitm,
+                       uint32_t orank, uint32_t ns, uint64_t key, uint32_t rend, uint32_t rcnt, uint32_t rslot, uint64_t *out,
+                       uint32_t omask, uint32_t wr) {
+    const uint32_t ln = wv::lane();
+    const uint32_t ke = (uint32_t)(key >> 32);
+    const uint64_t tied = woven & ~1ull & wv::ballot(rend == wv::shr1(rend));
+    if (popc64(woven) >= 6 && tied == 0) {
+        const uint32_t c = wv::lane_in(woven) ? rcnt : 0u;
+        const uint32_t off = wv::prefix_excl_u32(c);
+        const uint32_t pos = lanes_less(rend, ke, false);            // table lanes that are free before my completion time
+        const uint32_t before = wv::shfl(off, pos);                  // members of the woven batches among them
+        if (emit_me) out[(wr + orank + (pos < 64u ? before : extra)) & omask] = key;
+        wv::sync_lds();
+        if (emit_me) lscr[orank] = ke;
+        wv::sync_lds();
+        const uint32_t kc = ln < ns ? lscr[ln] : 0xFFFFFFFFu;        // the new completion times in rank order
+        const uint32_t nb = lanes_less(kc, rend, false);             // new queries that leave before my batch
+        emit_many(op, lslots, extra, off, nb, rend, rslot, out, omask, wr);
+        wv::sync_lds();
+        return;
+    }
+    uint32_t shift = 0;
+    for (uint64_t pm = woven; pm; pm &= pm - 1) {
+        const uint32_t j = ctz64(pm);
+        const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j);
+        if (ej < ke) shift += cj;
+    }
+    if (emit_me) out[(wr + orank + shift) & omask] = key;
+    weave_out(op, lslots, woven, emitm, ke, rend, rcnt, rslot, out, omask, wr);
+}
+
 // Emit, in (completion time, query index) order, the batches whose replica-table lanes are in E
 // (ascending lanes = ascending completion time).  Batches that complete at the same time are
 // merged by query index.  Stops early (returns false) when the output ring cannot take the next
@@ -305,6 +372,23 @@ EST_DEV bool scan_emit(const EstOp &op, const uint32_t *lslots, uint64_t E, uint
                        uint32_t rslot, uint64_t *out, uint32_t omask, uint32_t &wr, uint32_t &space, bool &progress) {
     const uint32_t ln = wv::lane();
     const uint32_t bm = wv::uniform(op.b_max);
+    if (popc64(E) >= 3) {
+        // several batches, no two completing together, and room for all of them: one sweep.  (The table is in
+        // order of time, so two batches of E with the same time have only lanes of that time between them: a lane
+        // of E whose time equals its left neighbour's is taken as a tie, whatever that neighbour holds.)
+        const uint64_t tied = E & ~1ull & wv::ballot(rend == wv::shr1(rend));
+        const uint32_t c = wv::lane_in(E) ? rcnt : 0u;
+        const uint32_t off = wv::prefix_excl_u32(c);
+        const uint32_t total = wv::bcast(off, 63) + wv::bcast(c, 63);
+        if (tied == 0 && total <= space) {
+            emit_many(op, lslots, total, off, 0u, rend, rslot, out, omask, wr);
+            wr += total;
+            space -= total;
+            if (wv::lane_in(E)) rcnt = 0;
+            progress = true;
+            return true;
+        }
+    }
     while (E) {
         const uint32_t l0 = ctz64(E);
         const uint32_t mv = wv::bcast(rend, l0);
@@ -391,6 +475,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     uint32_t blk_skip = 0;     // and for the block of batches
     uint32_t lean_skip = 0;    // and for the light-load step on large groups
     uint32_t cf_skip = 0;      // and for the closed forms of one query per batch
+    uint64_t d_tk[6] = {0, 0, 0, 0, 0, 0}, tk0 = 0;  // diagnostics: ticks by the kind of step that ended the iteration
     uint32_t d_gen = 0, d_gene = 0, d_fp = 0, d_fpe = 0, d_b1 = 0, d_b1e = 0, d_sat = 0, d_sate = 0, d_hz = 0, d_blk = 0, d_blke = 0, d_lean = 0, d_leane = 0;  // diagnostics
 
     for (;;) {
@@ -435,6 +520,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         // every step below works on a window of up to 64 queries and may emit as many: with less room
         // than that in the output ring, let the reader run first rather than squeeze batches through
         if (space < 64u) break;
+        if (DIAG) tk0 = wv::ticks();
         const uint32_t w = umin(staged, 64u);
         const uint64_t key = ln < w ? lkey[(lhead + ln) & (SCAN_INRING - 1)] : ~0ull;
         const uint32_t rdy = (uint32_t)(key >> 32);
@@ -453,6 +539,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             space -= m;
             lhead += m;
             d_hz += m;
+            if (DIAG) d_tk[4] += wv::ticks() - tk0;
             progress = true;
             continue;
         }
@@ -518,6 +605,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                             wv::sync_lds();
                             lhead += na;
                             ++d_sat; d_sate += na;
+                            if (DIAG) d_tk[4] += wv::ticks() - tk0;
                             progress = true;
                             continue;
                         }
@@ -563,6 +651,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 if (isrep) rend = tnew;
                 lhead += m;
                 ++d_b1; d_b1e += m;
+                if (DIAG) d_tk[2] += wv::ticks() - tk0;
                 progress = true;
                 continue;
             }
@@ -629,6 +718,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 wr += m;
                 space -= m;
                 ++d_b1; d_b1e += m;
+                if (DIAG) d_tk[2] += wv::ticks() - tk0;
                 EST_CHK_ORDER(1);
                 // the table becomes the last R completion times
                 const uint32_t keep = R > m ? R - m : 0u;  // old entries that stay
@@ -704,6 +794,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                     wv::sync_lds();
                     lhead += m;
                     ++d_lean; d_leane += m;
+                    if (DIAG) d_tk[0] += wv::ticks() - tk0;
                     progress = true;
                     done = true;
                 }
@@ -842,15 +933,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                         }
                         const bool emit_me = inv ? ln < ns : safe;
                         const uint64_t emitm = inv ? lanes_below(ns) : safem;
-                        const uint32_t ke = (uint32_t)(key >> 32);
-                        uint32_t shift = 0;
-                        for (uint64_t pm = woven; pm; pm &= pm - 1) {
-                            const uint32_t j = ctz64(pm);
-                            const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j);
-                            if (ej < ke) shift += cj;
-                        }
-                        if (emit_me) out[(wr + orank + shift) & omask] = key;
-                        weave_out(op, lslots, woven, emitm, ke, rend, rcnt, rslot, out, omask, wr);
+                        weave_all(op, lslots, lrdy, woven, extra, emit_me, emitm, orank, ns, key, rend, rcnt, rslot, out, omask, wr);
                         if ((woven >> ln) & 1ull) rcnt = 0;
                         wr += ns + extra;
                         space -= ns + extra;
@@ -900,6 +983,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 }
             }
             ++d_fp; d_fpe += m;
+            if (DIAG && m > 0) d_tk[1] += wv::ticks() - tk0;
             if (m < 3) fp_skip = 6;  // not the regime for this shortcut: leave it alone for a few batches
             if (m > 0) continue;
             if (space == 0) break;
@@ -985,15 +1069,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                                          (safem & ~1ull & (wv::ballot(eprev > e) | (wv::ballot(eprev == e) & wv::ballot(qprev > q)))) == 0;
                     if (!ordered) key = sort_time_query(e, q, safem, wv::uniform(rdy));
                     const bool emit_me = ln < nsafe;
-                    const uint32_t ke = (uint32_t)(key >> 32);
-                    uint32_t shift = 0;
-                    for (uint64_t pm = woven; pm; pm &= pm - 1) {
-                        const uint32_t j = ctz64(pm);
-                        const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j);
-                        if (ej < ke) shift += cj;
-                    }
-                    if (emit_me) out[(wr + ln + shift) & omask] = key;
-                    weave_out(op, lslots, woven, lanes_below(nsafe), ke, rend, rcnt, rslot, out, omask, wr);
+                    weave_all(op, lslots, ltab + 192, woven, extra, emit_me, lanes_below(nsafe), ln, nsafe, key, rend, rcnt, rslot, out, omask, wr);
                     wr += nsafe + extra;
                     space -= nsafe + extra;
                     EST_CHK_ORDER(7);
@@ -1017,6 +1093,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                     wv::sync_lds();
                     lhead += a;
                     ++d_blk; d_blke += a;
+                    if (DIAG) d_tk[3] += wv::ticks() - tk0;
                     progress = true;
                     done = true;
                 }
@@ -1064,6 +1141,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         }
         lhead += b;
         d_gene += b;
+        if (DIAG) d_tk[5] += wv::ticks() - tk0;
         progress = true;
     }
 
@@ -1071,6 +1149,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         uint64_t *pc = est_dbg_rec(c.a, c.t, s);  // per candidate and stage (one writer: no atomics)
         pc[0] += d_gen; pc[2] += d_fp + d_b1 + d_sat + d_blk + d_lean; pc[3] += d_fpe + d_b1e + d_sate + d_hz + d_blke + d_leane;
         pc[4] += d_leane; pc[5] += d_fpe; pc[6] += d_b1e; pc[7] += d_blke;
+        for (uint32_t i = 0; i < 6; ++i) pc[8 + i] += d_tk[i];
         uint64_t *po = est_dbg_rec(c.a, c.t, EST_MAX_STAGES - 1);
         po[6] += 1; po[7] += d_gene;
     }

@@ -408,7 +408,7 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     const char *dbg_path = getenv("EST_DEBUG_TICKS");
     DevBuf dbg_buf;
     uint64_t *dbg_ticks = nullptr;
-    const uint64_t dbg_words = n_cfg * (1 + 8 * EST_MAX_STAGES);  // per candidate: ticks, then 8 counters per stage
+    const uint64_t dbg_words = n_cfg * (1 + (uint64_t)EST_DBG_WORDS * EST_MAX_STAGES);  // per candidate: ticks, then the counters per stage
     if (dbg_path && !no_alloc && n > 0 && dbg_buf.alloc(dbg_words * 8) && !estbe::zero(dbg_buf.p, dbg_words * 8, stream)) dbg_ticks = (uint64_t *)dbg_buf.p;
     void *e0 = no_alloc ? h->ev[4] : evs.make(), *e1 = no_alloc ? h->ev[5] : evs.make();
     if (!e0 || !e1) return dev_fail(h, "event create");

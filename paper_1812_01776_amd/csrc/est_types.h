@@ -5,6 +5,7 @@
 #include "../../include/estimator.h"  // EST_MAX_STAGES and the other public limits
 
 #define EST_WAVE 64
+#define EST_DBG_WORDS 16          // diagnostics: words per candidate and stage
 #define EST_MW_WAVES 4            // wavefronts that share one candidate in calls that leave the device mostly empty
 #define EST_KMAX EST_MAX_MERGE_SOURCES   // sources of one merge operation (accept masks are 8 bits)
 #define EST_MAX_OPS 72          // <= 2 per stage + the latency sink

@@ -344,11 +344,11 @@ def test_w4_w5_all_configs_trace_prefix(name):
 
 def test_diagnostics_variant_gives_the_same_results(tmp_path, monkeypatch):
     """EST_DEBUG_TICKS=<file> launches the kernel variant compiled with step counters and dumps them:
-    per candidate the wavefront's run time, then per candidate and stage eight counters."""
+    per candidate the wavefront's run time, then per candidate and stage sixteen counters."""
     w = workloads.random_case(21, S=4, n=1500, C=6, max_b=8, max_r=4)
     dump = tmp_path / "ticks.bin"
     monkeypatch.setenv("EST_DEBUG_TICKS", str(dump))
     _compare(w)
     d = np.fromfile(dump, dtype=np.uint64)
-    assert d.size == w.n_configs * (1 + 8 * 32)
+    assert d.size == w.n_configs * (1 + 16 * 32)
     assert (d[:w.n_configs] > 0).all()

@@ -71,7 +71,7 @@ def test_bursts_of_large_groups_match_oracle(seed, tmp_path, monkeypatch):
     dump = tmp_path / "ticks.bin"
     monkeypatch.setenv("EST_DEBUG_TICKS", str(dump))
     _compare(w)
-    d = np.fromfile(dump, dtype=np.uint64)[w.n_configs:].reshape(w.n_configs, 32, 8)
+    d = np.fromfile(dump, dtype=np.uint64)[w.n_configs:].reshape(w.n_configs, 32, 16)
     assert d[:, :w.n_stages, 4].sum() > 0
 
 
@@ -225,4 +225,4 @@ def test_diagnostics_variant_gives_the_same_results(tmp_path, monkeypatch):
     monkeypatch.setenv("EST_DEBUG_TICKS", str(dump))
     _compare(w)
     d = np.fromfile(dump, dtype=np.uint64)
-    assert d.size == w.n_configs * (1 + 8 * 32)
+    assert d.size == w.n_configs * (1 + 16 * 32)
