@@ -64,7 +64,8 @@ struct Ctx {
 
 // Diagnostics record of candidate t and stage s: EST_DBG_WORDS words (general steps, ticks in the stage's scan,
 // shortcut steps, queries in shortcut steps, of which: lean light-load, light-load, one-per-batch, block of batches;
-// then ticks spent in steps that ended as: lean light-load, light-load, one-per-batch, block, backlog or horizon, general).
+// then ticks spent in steps that ended as: lean light-load, light-load, one-per-batch, block, backlog or horizon, general;
+// then ticks in the recurrence of the block steps and the batches those ran ahead).
 // The record of stage EST_MAX_STAGES-1 holds what belongs to no stage: ticks in merges, in the sink, in the
 // selection, merge rounds, merge output elements, merge calls, scan calls, queries in general steps.
 EST_DEV uint64_t *est_dbg_rec(const EstSimArgs *a, uint32_t t, uint32_t s) {
@@ -475,6 +476,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     uint32_t blk_skip = 0;     // and for the block of batches
     uint32_t lean_skip = 0;    // and for the light-load step on large groups
     uint32_t cf_skip = 0;      // and for the closed forms of one query per batch
+    uint64_t d_blkl = 0, d_blkk = 0;  // diagnostics: ticks in the recurrence of the block step, batches it ran ahead
     uint64_t d_tk[6] = {0, 0, 0, 0, 0, 0}, tk0 = 0;  // diagnostics: ticks by the kind of step that ended the iteration
     uint32_t d_gen = 0, d_gene = 0, d_fp = 0, d_fpe = 0, d_b1 = 0, d_b1e = 0, d_sat = 0, d_sate = 0, d_hz = 0, d_blk = 0, d_blke = 0, d_lean = 0, d_leane = 0;  // diagnostics
 
@@ -554,7 +556,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 const uint32_t LB = wv::bcast(Lmine, B - 1);
                 const uint32_t tl = wv::bcast(rend, R - 1);
                 uint32_t nacc = 0;
-                if (tl < sat_add(f0, LB)) {
+                if (tl < wv::sat_add_uniform(f0, LB)) {
                     const uint32_t lo = wv::opaque(ln);
                     const uint32_t kb = (lo * inv_b) >> 16;        // my batch
                     const uint32_t kd = (kb * inv_r) >> 16, km = kb - kd * R;
@@ -769,7 +771,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 const uint32_t e0 = wv::uniform(e), last_old = wv::bcast(rend, R - 1u);
                 if (bad == 0 && (G == R || e0 > last_old)) {
                     const bool tau_inf = final && m >= w;
-                    const uint32_t tau = tau_inf ? 0xFFFFFFFFu : sat_add(wv::bcast(rdy, umin(m, w - 1u)), L1);
+                    const uint32_t tau = tau_inf ? 0xFFFFFFFFu : wv::sat_add_uniform(wv::bcast(rdy, umin(m, w - 1u)), L1);
                     const uint64_t E = wv::ballot(rcnt > 0) & (tau_inf ? ~0ull : wv::ballot(rend < tau));
                     if (E && !scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress)) break;  // wait for the consumer
                     EST_CHK_ORDER(8);
@@ -864,9 +866,11 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 // merged by query index when they leave)
                 const uint64_t busyp = wv::ballot(rcnt > 0);  // all of these end after r0
                 uint64_t okm = WM & wv::ballot(e != 0xFFFFFFFFu) & wv::ballot(g <= B);  // (a clamped time never passes)
-                for (uint64_t pm = busyp; pm; pm &= pm - 1) {
-                    const uint32_t ep = wv::bcast(rend, ctz64(pm));
-                    okm &= wv::ballot(e != ep);
+                if (busyp) {
+                    // (one search over the table per lane; an entry that no longer holds members counts as well, which
+                    // only ends the run early)
+                    const uint32_t pos = lanes_less(rend, e, false);  // the first table lane that is free no earlier than e
+                    okm &= ~wv::ballot(wv::shfl(rend, pos & 63u) == e && pos < 64u);
                 }
                 okm &= final ? ~0ull : (wv::ballot(nh < w) | wv::ballot(g == B));                    // the whole group is in view (or it is full)
                 okm &= wv::ballot(bid < p) | wv::ballot(lend[bid >= p ? bid - p : 0u] <= rdy);     // its replica is free again
@@ -875,7 +879,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                     // the next batch starts no earlier than the next query's ready time; if the run took
                     // the whole window, that is at least the window's last ready time
                     bool tau_inf = m >= w && final;                      // nothing follows at all
-                    uint32_t tau = tau_inf ? 0xFFFFFFFFu : sat_add(wv::bcast(rdy, umin(m, w - 1u)), L1);
+                    uint32_t tau = tau_inf ? 0xFFFFFFFFu : wv::sat_add_uniform(wv::bcast(rdy, umin(m, w - 1u)), L1);
                     uint64_t safem = lanes_below(m) & (tau_inf ? ~0ull : wv::ballot(e < tau));
                     if (safem != lanes_below(m)) {
                         // Some batch of the run would have to wait.  Waiting batches cost slot traffic and
@@ -884,7 +888,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                         // looked at again with more of the input in view.
                         const uint32_t m2 = ctz64(~safem);               // (the first query of its group)
                         if (m2 >= 16) {
-                            const uint32_t tau2 = sat_add(wv::bcast(rdy, m2), L1);
+                            const uint32_t tau2 = wv::sat_add_uniform(wv::bcast(rdy, m2), L1);
                             if ((lanes_below(m2) & ~wv::ballot(e < tau2)) == 0) {
                                 m = m2;
                                 tau = tau2;
@@ -895,16 +899,10 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                     }
                     const bool safe = ln < m && (tau_inf || e < tau);
                     const uint32_t ns = popc64(safem);
-                    // older waiting batches that finish before tau go out with the run
-                    uint32_t extra = 0;
-                    uint64_t woven = 0;
-                    for (uint64_t pm = busyp; pm; pm &= pm - 1) {
-                        const uint32_t j = ctz64(pm);
-                        const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j);
-                        if (!tau_inf && ej >= tau) break;  // sorted: the rest finish later and keep waiting
-                        woven |= 1ull << j;
-                        extra += cj;
-                    }
+                    // older waiting batches that finish before tau go out with the run (the table is in order of
+                    // time: the rest finish later and keep waiting)
+                    const uint64_t woven = tau_inf ? busyp : busyp & wv::ballot(rend < tau);
+                    const uint32_t extra = woven ? wv::sum_u32(wv::lane_in(woven) ? rcnt : 0u) : 0u;
                     if (ns + extra > space) {
                         m = 0;  // leave it to the general path (or to the consumer)
                     } else {
@@ -1004,45 +1002,64 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             const uint64_t busyp = wv::ballot(rcnt > 0);
             // working table: free time, and packed (members waiting << 16 | batch of this block on the entry, 0xFF = none, << 8 | slot)
             uint32_t trend = rend, tinfo = (rcnt << 16) | 0xFF00u | rslot;
-            uint32_t vE = 0, vS = 0, vA = 0, vB = 0;                          // per batch (lane k): end, slot, first lane, size
+            uint32_t vE = 0, vP = 0;                                          // per batch (lane k): end, and slot << 16 | first lane << 8 | size
             uint64_t heads = 0;
             uint32_t a = 0, K = 0;
             uint32_t cap = 0xFFFFFFFFu;  // a new batch completes together with an older waiting one at this time: nothing from there on leaves in this step
-            while (a < w) {
+            const uint64_t tkl = DIAG ? wv::ticks() : 0;
+            const uint32_t wf = final ? 65u : w;  // a batch that is not full is decided once a query ready later is in view (or none can follow)
+            // (one exit and one branch per batch: the tests are combined as integers, which keeps them on the scalar unit)
+            for (uint32_t go = 1u; go;) {
                 const uint32_t f = wv::uniform(trend);
                 const uint32_t ti0 = wv::uniform(tinfo);
-                // the entry taken loses its slot, so its batch (of this block, or an older one still waiting) has to leave in this step
-                if (f >= cap && (((ti0 >> 8) & 0xFFu) != 0xFFu || (ti0 >> 16) != 0u)) break;
                 const uint32_t T = umax(f, wv::bcast(rdy, a));
-                const uint32_t ready = popc64(WM & wv::ballot(rdy <= T));
+                // (lanes beyond the window hold 2^32-1: they count only when T is the horizon, and then the step ends here)
+                const uint32_t ready = popc64(wv::ballot(rdy <= T));
                 const uint32_t b = umin(B, ready - a);
-                if (!(b == B || ready < w || final)) break;  // more members may still arrive
-                const uint32_t e = sat_add(T, wv::bcast(Lmine, b - 1u));
-                if (e == 0xFFFFFFFFu) break;                // (a clamped time never passes)
-                if (cap == 0xFFFFFFFFu && (wv::ballot(tinfo >= 0x10000u) & wv::ballot(trend == e))) cap = e;  // the pair is merged by query index when it leaves, later
-                const uint32_t slot0 = ti0 & 0xFFu;
-                const bool mine = ln == K;
-                vE = mine ? e : vE; vS = mine ? slot0 : vS; vA = mine ? a : vA; vB = mine ? b : vB;
-                // the earliest entry leaves the table, the new one goes in behind everything that ends no later
-                const uint32_t p = popc64(REP & ~1ull & wv::ballot(trend <= e));
-                const uint32_t ne = wv::shl1(trend), ni = wv::shl1(tinfo);
-                if (ln < p) {
-                    trend = ne; tinfo = ni;
-                } else if (ln == p) {
-                    trend = e; tinfo = (K << 8) | slot0;
+                const uint32_t e = wv::sat_add_uniform(T, wv::bcast(Lmine, b - 1u));
+                // stop: more members may still arrive | a clamped time never passes
+                const uint32_t stop = wv::flag_ne_and_ge(b, B, ready, wf) | wv::flag_ge(e, 0xFFFFFFFFu);
+                go = 0u;
+                if (stop == 0u) {
+                    // the earliest entry leaves the table, the new one goes in behind everything that ends no later (the
+                    // entry that leaves is free by T < e, so it is counted; lanes beyond the table hold 2^32-1 > e)
+                    const uint32_t p = popc64(wv::ballot(trend <= e)) - 1u;
+                    const uint32_t slot0 = ti0 & 0xFFu;
+                    uint32_t more = 1u;
+                    if (wv::bcast(trend, p) == e) {
+                        // completes together with an entry of the table; if that is an older batch still waiting, the pair is
+                        // merged by query index when it leaves, later: nothing from this time on leaves in this step, and the
+                        // block ends here (an entry taken after this would lose its slot and have to leave)
+                        const uint32_t e2 = wv::opaque_uniform(e);
+                        const uint64_t tiem = wv::ballot(tinfo >= 0x10000u) & wv::ballot(trend == e2);
+                        const uint32_t hit = wv::flag_ne((uint32_t)tiem | (uint32_t)(tiem >> 32), 0u);
+                        cap = hit ? e2 : cap;
+                        more = hit ^ 1u;
+                    }
+                    vE = wv::set_lane(vE, e, K);
+                    vP = wv::set_lane(vP, (slot0 << 16) | (a << 8) | b, K);
+                    const uint32_t ne = wv::shl1_any(trend), ni = wv::shl1_any(tinfo);  // (p < 64: lane 63 is never among the lanes below p)
+                    if (ln < p) {
+                        trend = ne; tinfo = ni;
+                    }
+                    trend = wv::set_lane(trend, e, p);
+                    tinfo = wv::set_lane(tinfo, (K << 8) | slot0, p);
+                    heads |= 1ull << a;
+                    a += b;
+                    ++K;
+                    go = more & wv::flag_lt(a, w);
                 }
-                heads |= 1ull << a;
-                a += b;
-                ++K;
+                go = wv::opaque_uniform(go);
             }
             bool done = false;
+            if (DIAG) { d_blkl += wv::ticks() - tkl; d_blkk += K; }
             if (K >= 2) {
                 const uint32_t f_next = wv::uniform(trend);
                 bool tau_inf = final && a >= w;
                 const uint32_t r_next = wv::bcast(rdy, a < w ? a : w - 1u);  // what follows is ready no earlier
-                uint32_t tau = tau_inf ? 0xFFFFFFFFu : sat_add(umax(f_next, r_next), L1);
+                uint32_t tau = tau_inf ? 0xFFFFFFFFu : wv::sat_add_uniform(umax(f_next, r_next), L1);
                 const uint32_t kb = wv::rank_below(heads >> 1);             // my batch (lane 0 starts batch 0)
-                const uint32_t e = wv::shfl(vE, kb), st = wv::shfl(vA, kb), myslot = wv::shfl(vS, kb);
+                const uint32_t e = wv::shfl(vE, kb), pk = wv::shfl(vP, kb), st = (pk >> 8) & 0xFFu, myslot = pk >> 16;
                 const uint64_t AM = lanes_below(a);
                 if (cap != 0xFFFFFFFFu && (tau_inf || cap < tau)) {
                     tau = cap;
@@ -1050,18 +1067,12 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 }
                 const uint64_t safem = AM & (tau_inf ? ~0ull : wv::ballot(e < tau));
                 const uint32_t nsafe = popc64(safem);
-                uint32_t extra = 0;
-                uint64_t woven = 0, clash = 0;  // clash: a new batch that leaves now completes together with an older one (excluded by the cap)
-                for (uint64_t pm = busyp; pm; pm &= pm - 1) {
-                    const uint32_t j = ctz64(pm);
-                    const uint32_t ej = wv::bcast(rend, j), cj = wv::bcast(rcnt, j);
-                    if (!tau_inf && ej >= tau) break;  // sorted: the rest finish later and keep waiting
-                    woven |= 1ull << j;
-                    extra += cj;
-                    clash |= safem & wv::ballot(e == ej);
-                }
+                // older waiting batches that finish before tau leave with the block (the table is in order of time).  None of
+                // them completes together with a new batch that leaves now: such a pair would have set the cap.
+                const uint64_t woven = tau_inf ? busyp : busyp & wv::ballot(rend < tau);
+                const uint32_t extra = woven ? wv::sum_u32(wv::lane_in(woven) ? rcnt : 0u) : 0u;
                 const bool safe = ln < a && (tau_inf || e < tau);
-                if (nsafe + extra <= space && clash == 0) {
+                if (nsafe + extra <= space) {
                     const uint32_t eprev = wv::shr1(e), qprev = wv::shr1(q), kprev = wv::shr1(kb);
                     uint64_t key = safe ? (((uint64_t)e << 32) | q) : ~0ull;
                     // in output order already?  (only checked when the safe queries are the leading ones)
@@ -1083,7 +1094,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                     // the working table becomes the table: older entries written out lose their members,
                     // entries of this block keep theirs if they wait
                     const uint32_t tk = (tinfo >> 8) & 0xFFu;
-                    const uint32_t bsz = wv::shfl(vB, tk);
+                    const uint32_t bsz = wv::shfl(vP, tk) & 0xFFu;
                     const bool late = !tau_inf && trend >= tau;
                     if (isrep) {
                         rend = trend;
@@ -1130,7 +1141,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         const uint32_t slot = wv::uniform(rslot);  // the earliest free replica takes the batch
         EST_CHECK(wv::uniform(rcnt) == 0 && slot < op.r_max);
         if (ln < b) lslots[slot * bm + ln] = q;
-        const uint32_t end = sat_add(T, wv::bcast(Lmine, b - 1));
+        const uint32_t end = wv::sat_add_uniform(T, wv::bcast(Lmine, b - 1));
         // drop lane 0 from the table and insert the new entry so that the table stays sorted
         const uint32_t p = popc64(REP & ~1ull & wv::ballot(rend <= end));
         const uint32_t nend = wv::shl1(rend), ncnt = wv::shl1(rcnt), nslot = wv::shl1(rslot);
@@ -1150,6 +1161,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         pc[0] += d_gen; pc[2] += d_fp + d_b1 + d_sat + d_blk + d_lean; pc[3] += d_fpe + d_b1e + d_sate + d_hz + d_blke + d_leane;
         pc[4] += d_leane; pc[5] += d_fpe; pc[6] += d_b1e; pc[7] += d_blke;
         for (uint32_t i = 0; i < 6; ++i) pc[8 + i] += d_tk[i];
+        pc[14] += d_blkl; pc[15] += d_blkk;
         uint64_t *po = est_dbg_rec(c.a, c.t, EST_MAX_STAGES - 1);
         po[6] += 1; po[7] += d_gene;
     }

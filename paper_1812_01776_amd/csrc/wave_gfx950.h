@@ -27,8 +27,10 @@ EST_DEV uint32_t bcast(uint32_t v, uint32_t l) {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)__builtin_amdgcn_readfirstlane((int)l));
 }
 
-// value of lane-1 (lane 0 keeps its own) / of lane+1 (lane 63 keeps its own)
+// value of lane-1 (lane 0 keeps its own) / of lane+1 (lane 63 keeps its own: shl1)
 EST_DEV uint32_t shr1(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x138, 0xF, 0xF, false); }
+// the same, except that lane 63 gets an unspecified value (no copy of the old value is needed first)
+EST_DEV uint32_t shl1_any(uint32_t v) { return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x130, 0xF, 0xF, true); }
 EST_DEV uint32_t shl1(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x130, 0xF, 0xF, false); }
 // value of lane ^ 1, ^ 2, ^ 4, ^ 8 (data-parallel-primitive moves inside a row of 16 lanes; every
 // lane has a source, so no previous value is carried)
@@ -57,7 +59,52 @@ EST_DEV uint32_t opaque(uint32_t v) {
     return v;
 }
 
+// v (the same in every lane), hidden from the optimiser and kept in a scalar register: a test of the result stays a
+// scalar compare and branch of its own instead of being merged with its neighbours into lane-mask arithmetic
+EST_DEV uint32_t opaque_uniform(uint32_t v) {
+    asm volatile("" : "+s"(v));
+    return v;
+}
+
+// 1 when a >= b (a != b), else 0, for operands that are the same in every lane: a scalar compare whose result is an
+// integer in a scalar register (several tests combined with & and | then cost one branch, and no lane masks)
+EST_DEV uint32_t flag_ge(uint32_t a, uint32_t b) {
+    uint32_t r;
+    asm("s_cmp_ge_u32 %1, %2\n\ts_cselect_b32 %0, 1, 0" : "=s"(r) : "s"(a), "s"(b) : "scc");
+    return r;
+}
+EST_DEV uint32_t flag_lt(uint32_t a, uint32_t b) {
+    uint32_t r;
+    asm("s_cmp_lt_u32 %1, %2\n\ts_cselect_b32 %0, 1, 0" : "=s"(r) : "s"(a), "s"(b) : "scc");
+    return r;
+}
+// 1 when a != b and c >= d (d at least 1), else 0
+EST_DEV uint32_t flag_ne_and_ge(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+    uint32_t r;
+    asm("s_cmp_lg_u32 %1, %2\n\ts_cselect_b32 %0, %3, 0\n\ts_cmp_ge_u32 %0, %4\n\ts_cselect_b32 %0, 1, 0"
+        : "=&s"(r) : "s"(a), "s"(b), "s"(c), "s"(d) : "scc");
+    return r;
+}
+EST_DEV uint32_t flag_ne(uint32_t a, uint32_t b) {
+    uint32_t r;
+    asm("s_cmp_lg_u32 %1, %2\n\ts_cselect_b32 %0, 1, 0" : "=s"(r) : "s"(a), "s"(b) : "scc");
+    return r;
+}
+
+// v with lane l replaced by x (l and x the same in every lane, l < 64): v_writelane_b32, reached through its
+// compiler intrinsic (this compiler declares no builtin for it), so wait states and m0 are the compiler's business.
+extern "C" __device__ uint32_t est_llvm_writelane(uint32_t x, uint32_t l, uint32_t v) __asm("llvm.amdgcn.writelane");
+EST_DEV uint32_t set_lane(uint32_t v, uint32_t x, uint32_t l) { return est_llvm_writelane(x, l, v); }
+
 EST_DEV uint32_t uniform(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+
+// min(t + d, 2^32 - 1) for operands that are the same in every lane, on the scalar unit (the compiler's own
+// saturating add exists on the vector unit only, with a trip there and back)
+EST_DEV uint32_t sat_add_uniform(uint32_t t, uint32_t d) {
+    uint32_t r;
+    asm("s_add_u32 %0, %1, %2\n\ts_cselect_b32 %0, -1, %0" : "=s"(r) : "s"(t), "s"(d) : "scc");
+    return r;
+}
 
 EST_DEV uint32_t min_u32(uint32_t v) {
 #pragma unroll
@@ -68,10 +115,13 @@ EST_DEV uint32_t min_u32(uint32_t v) {
     return uniform(v);
 }
 
+// (moves inside the rows of 16 lanes, then one scalar read per row: no trip through the LDS crossbar)
 EST_DEV uint32_t sum_u32(uint32_t v) {
-#pragma unroll
-    for (uint32_t d = 32; d >= 1; d >>= 1) v += shfl(v, lane() ^ d);
-    return uniform(v);
+    v += xor1(v);
+    v += xor2(v);
+    v += (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x124, 0xF, 0xF, true);  // + lane-4 (mod 16)
+    v += xor8(v);
+    return bcast(v, 0) + bcast(v, 16) + bcast(v, 32) + bcast(v, 48);
 }
 
 // exclusive prefix sum over lanes

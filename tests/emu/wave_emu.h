@@ -72,6 +72,8 @@ EST_DEV uint32_t bcast(uint32_t v, uint32_t l) {
 }
 
 EST_DEV uint32_t shr1(uint32_t v) { const uint64_t *x = emu::exchange(v, 9); uint32_t l = emu::lane(); return l == 0 ? v : (uint32_t)x[l - 1]; }
+// (lane 63: unspecified on the device; a value here that a wrong use would trip over)
+EST_DEV uint32_t shl1_any(uint32_t v) { const uint64_t *x = emu::exchange(v, 18); uint32_t l = emu::lane(); return l == 63 ? 0xDEADBEEFu : (uint32_t)x[l + 1]; }
 EST_DEV uint32_t shl1(uint32_t v) { const uint64_t *x = emu::exchange(v, 10); uint32_t l = emu::lane(); return l == 63 ? v : (uint32_t)x[l + 1]; }
 EST_DEV uint32_t xor1(uint32_t v) { return (uint32_t)emu::exchange(v, 11)[emu::lane() ^ 1u]; }
 EST_DEV uint32_t xor2(uint32_t v) { return (uint32_t)emu::exchange(v, 12)[emu::lane() ^ 2u]; }
@@ -89,6 +91,39 @@ EST_DEV uint32_t rank_below(uint64_t m) {
 }
 
 EST_DEV uint32_t opaque(uint32_t v) { return v; }
+EST_DEV uint32_t opaque_uniform(uint32_t v) { return v; }
+EST_DEV void check_uniform2(uint32_t a, uint32_t b, const char *what) {
+    const uint64_t mine = ((uint64_t)a << 32) | b;
+    const uint64_t *x = emu::exchange(mine, 17);
+    for (int i = 0; i < 64; ++i)
+        if (x[i] != mine) {
+            fprintf(stderr, "%s: operands not uniform\n", what);
+            abort();
+        }
+}
+EST_DEV uint32_t set_lane(uint32_t v, uint32_t x, uint32_t l) {
+    check_uniform2(x, l, "set_lane");
+    if (l >= 64) {
+        fprintf(stderr, "set_lane: lane %u out of range\n", l);
+        abort();
+    }
+    return emu::lane() == l ? x : v;
+}
+EST_DEV uint32_t flag_ge(uint32_t a, uint32_t b) { check_uniform2(a, b, "flag_ge"); return a >= b ? 1u : 0u; }
+EST_DEV uint32_t flag_lt(uint32_t a, uint32_t b) { check_uniform2(a, b, "flag_lt"); return a < b ? 1u : 0u; }
+EST_DEV uint32_t flag_ne_and_ge(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+    check_uniform2(a, b, "flag_ne_and_ge");
+    check_uniform2(c, d, "flag_ne_and_ge");
+    EST_CHECK(d >= 1u);
+    return (a != b && c >= d) ? 1u : 0u;
+}
+EST_DEV uint32_t flag_ne(uint32_t a, uint32_t b) { check_uniform2(a, b, "flag_ne"); return a != b ? 1u : 0u; }
+// (both operands must be the same in every lane: checked)
+EST_DEV uint32_t sat_add_uniform(uint32_t t, uint32_t d) {
+    check_uniform2(t, d, "sat_add_uniform");
+    const uint32_t r = t + d;
+    return r < t ? 0xFFFFFFFFu : r;
+}
 
 EST_DEV uint32_t uniform(uint32_t v) { return (uint32_t)emu::exchange(v, 4)[0]; }
 

@@ -46,7 +46,7 @@ def test_wave_primitive_lane_layout():
     import ctypes
     import torch  # noqa: F401  (PyTorch's copy of the HIP runtime first, so that this library binds to the same instance)
     lib = ctypes.CDLL(os.path.join(os.path.dirname(__file__), "selftest", "libwave_selftest.so"))  # test-only library
-    out = np.zeros((13, 64), np.uint32)
+    out = np.zeros((19, 64), np.uint32)
     assert lib.est_selftest_wave(ctypes.c_void_p(out.ctypes.data)) == 0
     ln = np.arange(64)
     v = 7 * ln + 3
@@ -59,6 +59,14 @@ def test_wave_primitive_lane_layout():
         assert out[6 + i][:width].tolist() == sorted(scr[:width].tolist()), width
     m = 0xF0F0A5A5C3C3FF01
     assert out[12].tolist() == [bin(m & ((1 << i) - 1)).count("1") for i in range(64)]
+    # the scalar-unit helpers
+    assert out[13][:63].tolist() == v[1:].tolist()
+    want = v.copy(); want[17] = 1000; want[41] = 1001
+    assert out[14].tolist() == want.tolist()
+    assert out[15].tolist() == [1000 + 0x200] * 64
+    assert out[16].tolist() == [0xFFFFFFFF] * 64
+    assert out[17].tolist() == [0b001010101] * 64
+    assert out[18].tolist() == (1000 + ln).tolist()
 
 
 def _hand_examples():
