@@ -275,30 +275,33 @@ EST_DEV uint32_t emit_tied(const EstOp &op, const uint32_t *lslots, uint64_t tie
 }
 
 // Number of lanes whose value is below x (<= x with incl), for values that ascend with the lane: a binary search
-// over the lanes, the same for every lane's own x.
-EST_DEV uint32_t lanes_less(uint32_t v, uint32_t x, bool incl) {
+// over the lanes, the same for every lane's own x.  Only the first width lanes are searched (a power of two, the
+// same in every lane): no lane from there on may pass the test.
+EST_DEV uint32_t lanes_less(uint32_t v, uint32_t x, bool incl, uint32_t width = 64u) {
     uint32_t pos = 0;
-EST_UNROLL
-    for (uint32_t step = 32; step >= 1; step >>= 1) {
+    for (uint32_t step = width >> 1; step >= 1; step >>= 1) {
         const uint32_t y = wv::shfl(v, pos + step - 1u);
         if (incl ? y <= x : y < x) pos += step;
     }
-    const uint32_t y = wv::shfl(v, 63u);  // (pos is 63 only when the first 63 lanes all pass)
-    if (pos == 63u && (incl ? y <= x : y < x)) pos = 64u;
+    const uint32_t y = wv::shfl(v, width - 1u);  // (pos is width-1 only when the lanes before that one all pass)
+    if (pos == width - 1u && (incl ? y <= x : y < x)) pos = width;
     return pos;
 }
+
+// The smallest power of two that is at least n (n from 1 to 64), at least 2
+EST_DEV uint32_t pow2_at_least(uint32_t n) { return n <= 2u ? 2u : 1u << (32u - (uint32_t)__builtin_clz(n - 1u)); }
 
 // The batches in the table lanes of E (ascending completion times, no two of them equal) written out in table
 // order in one sweep: off (the members of the lanes of E before mine, e.g. from emit_offsets) turns an output
 // position into a batch and a member.  Every member goes to out[base + its position + extra of its batch], where
 // extra is a per-batch displacement (lane = table lane; 0 to write them back to back).
 EST_DEV void emit_many(const EstOp &op, const uint32_t *lslots, uint32_t total, uint32_t off, uint32_t extra, uint32_t rend,
-                       uint32_t rslot, uint64_t *out, uint32_t omask, uint32_t base) {
+                       uint32_t rslot, uint64_t *out, uint32_t omask, uint32_t base, uint32_t tw) {
     const uint32_t ln = wv::lane();
     const uint32_t bm = wv::uniform(op.b_max);
     for (uint32_t i0 = 0; i0 < total; i0 += 64) {
         const uint32_t i = i0 + ln;
-        const uint32_t l = lanes_less(off, i, true) - 1u;  // the last lane whose batch starts at or before position i
+        const uint32_t l = lanes_less(off, i, true, tw) - 1u;  // the last lane whose batch starts at or before position i
         const uint32_t o = wv::shfl(off, l), e = wv::shfl(rend, l), sl = wv::shfl(rslot, l), x = wv::shfl(extra, l);
         if (i < total) out[(base + i + x) & omask] = ((uint64_t)e << 32) | lslots[sl * bm + (i - o)];
     }
@@ -336,22 +339,22 @@ EST_DEV void weave_out(const EstOp &op, const uint32_t *lslots, uint64_t woven, 
 // other side (lscr: 64 words of LDS scratch); otherwise batch by batch.
 EST_DEV void weave_all(const EstOp &op, const uint32_t *lslots, uint32_t *lscr, uint64_t woven, uint32_t extra, bool emit_me, uint64_t emitm,
                        uint32_t orank, uint32_t ns, uint64_t key, uint32_t rend, uint32_t rcnt, uint32_t rslot, uint64_t *out,
-                       uint32_t omask, uint32_t wr) {
+                       uint32_t omask, uint32_t wr, uint32_t tw) {
     const uint32_t ln = wv::lane();
     const uint32_t ke = (uint32_t)(key >> 32);
     const uint64_t tied = woven & ~1ull & wv::ballot(rend == wv::shr1(rend));
     if (popc64(woven) >= 6 && tied == 0) {
         const uint32_t c = wv::lane_in(woven) ? rcnt : 0u;
         const uint32_t off = wv::prefix_excl_u32(c);
-        const uint32_t pos = lanes_less(rend, ke, false);            // table lanes that are free before my completion time
+        const uint32_t pos = lanes_less(rend, ke, false, tw);        // table lanes that are free before my completion time
         const uint32_t before = wv::shfl(off, pos);                  // members of the woven batches among them
         if (emit_me) out[(wr + orank + (pos < 64u ? before : extra)) & omask] = key;
         wv::sync_lds();
         if (emit_me) lscr[orank] = ke;
         wv::sync_lds();
         const uint32_t kc = ln < ns ? lscr[ln] : 0xFFFFFFFFu;        // the new completion times in rank order
-        const uint32_t nb = lanes_less(kc, rend, false);             // new queries that leave before my batch
-        emit_many(op, lslots, extra, off, nb, rend, rslot, out, omask, wr);
+        const uint32_t nb = lanes_less(kc, rend, false, pow2_at_least(ns));  // new queries that leave before my batch
+        emit_many(op, lslots, extra, off, nb, rend, rslot, out, omask, wr, tw);
         wv::sync_lds();
         return;
     }
@@ -370,7 +373,7 @@ EST_DEV void weave_all(const EstOp &op, const uint32_t *lslots, uint32_t *lscr, 
 // merged by query index.  Stops early (returns false) when the output ring cannot take the next
 // group.
 EST_DEV bool scan_emit(const EstOp &op, const uint32_t *lslots, uint64_t E, uint32_t rend, uint32_t &rcnt,
-                       uint32_t rslot, uint64_t *out, uint32_t omask, uint32_t &wr, uint32_t &space, bool &progress) {
+                       uint32_t rslot, uint64_t *out, uint32_t omask, uint32_t &wr, uint32_t &space, bool &progress, uint32_t tw) {
     const uint32_t ln = wv::lane();
     const uint32_t bm = wv::uniform(op.b_max);
     if (popc64(E) >= 3) {
@@ -382,7 +385,7 @@ EST_DEV bool scan_emit(const EstOp &op, const uint32_t *lslots, uint64_t E, uint
         const uint32_t off = wv::prefix_excl_u32(c);
         const uint32_t total = wv::bcast(off, 63) + wv::bcast(c, 63);
         if (tied == 0 && total <= space) {
-            emit_many(op, lslots, total, off, 0u, rend, rslot, out, omask, wr);
+            emit_many(op, lslots, total, off, 0u, rend, rslot, out, omask, wr, tw);
             wr += total;
             space -= total;
             if (wv::lane_in(E)) rcnt = 0;
@@ -446,6 +449,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     // replica table, sorted by the time the replica is free again
     const bool isrep = ln < R;
     const uint64_t REP = lanes_below(R);  // (lanes beyond the table hold end = 2^32-1, count 0)
+    const uint32_t tw = pow2_at_least(R);  // searches over the table look at this many lanes
     uint32_t rend = isrep ? g_end[ln] : 0xFFFFFFFFu;
     uint32_t rcnt = isrep ? g_cnt[ln] : 0u;
     uint32_t rslot = isrep ? g_slot[ln] : 0u;
@@ -515,7 +519,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         if (staged == 0) {
             if (in.fin) {  // input exhausted for good: flush what is still in flight
                 const uint64_t E = wv::ballot(rcnt > 0);
-                if (!E || scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress)) finished = true;
+                if (!E || scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress, tw)) finished = true;
             }
             break;
         }
@@ -533,7 +537,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             // Every replica is busy up to the horizon: whatever is still queued starts and ends at the
             // horizon, where order no longer matters.  Waiting batches leave first, then the window.
             const uint64_t E = wv::ballot(rcnt > 0);
-            if (E && !scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress)) break;
+            if (E && !scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress, tw)) break;
             const uint32_t m = umin(w, space);
             if (m == 0) break;
             if (ln < m) out[(wr + ln) & omask] = 0xFFFFFFFF00000000ull | q;
@@ -578,7 +582,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                         if (popc64(E) * B + nd > space) {
                             nacc = 0;  // tight output ring: batch by batch
                         } else {
-                            scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress);
+                            scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress, tw);
                             const uint32_t eprev = wv::shr1(e), qprev = wv::shr1(q), kprev = wv::shr1(kb);
                             uint64_t okey = direct ? (((uint64_t)e << 32) | q) : ~0ull;
                             if (D & ~1ull & wv::ballot(eprev == e) & wv::ballot(qprev > q)) okey = sort_lanes64(okey);
@@ -773,7 +777,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                     const bool tau_inf = final && m >= w;
                     const uint32_t tau = tau_inf ? 0xFFFFFFFFu : wv::sat_add_uniform(wv::bcast(rdy, umin(m, w - 1u)), L1);
                     const uint64_t E = wv::ballot(rcnt > 0) & (tau_inf ? ~0ull : wv::ballot(rend < tau));
-                    if (E && !scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress)) break;  // wait for the consumer
+                    if (E && !scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress, tw)) break;  // wait for the consumer
                     EST_CHK_ORDER(8);
                     wv::sync_lds();  // the slots of batches just written out may be taken again
                     const uint32_t myslot = wv::shfl(rslot, gid);
@@ -820,7 +824,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             const uint32_t r0 = wv::uniform(rdy);
             const uint64_t idle0 = REP & wv::ballot(rend <= r0);
             const uint64_t E0 = idle0 & wv::ballot(rcnt > 0);
-            if (E0 && !scan_emit(op, lslots, E0, rend, rcnt, rslot, out, omask, wr, space, progress)) break;
+            if (E0 && !scan_emit(op, lslots, E0, rend, rcnt, rslot, out, omask, wr, space, progress, tw)) break;
             EST_CHK_ORDER(5);
             const uint32_t pidle = popc64(idle0);  // idle now: a prefix of the sorted table
             uint32_t m = 0;
@@ -869,7 +873,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 if (busyp) {
                     // (one search over the table per lane; an entry that no longer holds members counts as well, which
                     // only ends the run early)
-                    const uint32_t pos = lanes_less(rend, e, false);  // the first table lane that is free no earlier than e
+                    const uint32_t pos = lanes_less(rend, e, false, tw);  // the first table lane that is free no earlier than e
                     okm &= ~wv::ballot(wv::shfl(rend, pos & 63u) == e && pos < 64u);
                 }
                 okm &= final ? ~0ull : (wv::ballot(nh < w) | wv::ballot(g == B));                    // the whole group is in view (or it is full)
@@ -931,7 +935,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                         }
                         const bool emit_me = inv ? ln < ns : safe;
                         const uint64_t emitm = inv ? lanes_below(ns) : safem;
-                        weave_all(op, lslots, lrdy, woven, extra, emit_me, emitm, orank, ns, key, rend, rcnt, rslot, out, omask, wr);
+                        weave_all(op, lslots, lrdy, woven, extra, emit_me, emitm, orank, ns, key, rend, rcnt, rslot, out, omask, wr, tw);
                         if ((woven >> ln) & 1ull) rcnt = 0;
                         wr += ns + extra;
                         space -= ns + extra;
@@ -1080,7 +1084,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                                          (safem & ~1ull & (wv::ballot(eprev > e) | (wv::ballot(eprev == e) & wv::ballot(qprev > q)))) == 0;
                     if (!ordered) key = sort_time_query(e, q, safem, wv::uniform(rdy));
                     const bool emit_me = ln < nsafe;
-                    weave_all(op, lslots, ltab + 192, woven, extra, emit_me, lanes_below(nsafe), ln, nsafe, key, rend, rcnt, rslot, out, omask, wr);
+                    weave_all(op, lslots, ltab + 192, woven, extra, emit_me, lanes_below(nsafe), ln, nsafe, key, rend, rcnt, rslot, out, omask, wr, tw);
                     wr += nsafe + extra;
                     space -= nsafe + extra;
                     EST_CHK_ORDER(7);
@@ -1127,7 +1131,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         if (!decidable) break;
         // everything that completes by T leaves before this batch is dispatched
         const uint64_t E = wv::ballot(rcnt > 0) & wv::ballot(rend <= T);
-        if (E && !scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress)) break;
+        if (E && !scan_emit(op, lslots, E, rend, rcnt, rslot, out, omask, wr, space, progress, tw)) break;
         EST_CHK_ORDER(4);
         // members wait in the replica's slot sorted by query index
         if (b > 1) {

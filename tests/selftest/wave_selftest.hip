@@ -12,7 +12,8 @@
 // 2..64 (i = 6..11), rank_below of a fixed mask (12), and the scalar-unit helpers: shl1_any (13; lane 63
 // unspecified), set_lane twice (14), sat_add_uniform without and with overflow (15, 16), the flags (17: bit 0
 // flag_ge(5,5), bit 1 flag_ge(4,5), bit 2 flag_lt(4,5), bit 3 flag_lt(5,5), bit 4 flag_ne(4,5), bit 5 flag_ne(5,5),
-// bit 6 flag_ne_and_ge(1,2,7,7), bit 7 flag_ne_and_ge(2,2,7,7), bit 8 flag_ne_and_ge(1,2,6,7)), opaque_uniform (18).
+// bit 6 flag_ne_and_ge(1,2,7,7), bit 7 flag_ne_and_ge(2,2,7,7), bit 8 flag_ne_and_ge(1,2,6,7)), opaque_uniform (18),
+// prefix_excl_u32 and sum_u32 of scr^2 + 1 (19, 20).
 // (The operands are read from memory so that nothing is folded at compile time.)
 static __global__ __launch_bounds__(64) void est_wave_selftest_kernel(uint32_t *out, const uint32_t *in) {
     const uint32_t ln = threadIdx.x;
@@ -40,14 +41,16 @@ static __global__ __launch_bounds__(64) void est_wave_selftest_kernel(uint32_t *
                         (wv::flag_ne(c4, c5) << 4) | (wv::flag_ne(c5, c5) << 5) | (wv::flag_ne_and_ge(c1, c2, c7, c7) << 6) |
                         (wv::flag_ne_and_ge(c2, c2, c7, c7) << 7) | (wv::flag_ne_and_ge(c1, c2, c6, c7) << 8);
     out[18 * 64 + ln] = wv::opaque_uniform(k) + ln;
+    out[19 * 64 + ln] = wv::prefix_excl_u32(scr * scr + 1u);
+    out[20 * 64 + ln] = wv::sum_u32(scr * scr + 1u);
 }
 
 
-// Runs the lane-layout check kernel and copies its 19 x 64 results to host memory.  Returns 0 on success.
+// Runs the lane-layout check kernel and copies its 21 x 64 results to host memory.  Returns 0 on success.
 extern "C" int est_selftest_wave(uint32_t *host_out) {
     static const uint32_t operands[11] = {1, 2, 4, 5, 6, 7, 17, 41, 1000, 0xFFFFFF00u, 0x200};
     uint32_t *d = nullptr, *in = nullptr;
-    if (hipMalloc((void **)&d, 19 * 64 * 4) != hipSuccess) return 1;
+    if (hipMalloc((void **)&d, 21 * 64 * 4) != hipSuccess) return 1;
     if (hipMalloc((void **)&in, sizeof operands) != hipSuccess) {
         (void)hipFree(d);
         return 1;
@@ -56,7 +59,7 @@ extern "C" int est_selftest_wave(uint32_t *host_out) {
     if (!rc) {
         est_wave_selftest_kernel<<<1, 64>>>(d, in);
         rc = hipGetLastError() != hipSuccess;
-        rc = rc || hipMemcpy(host_out, d, 19 * 64 * 4, hipMemcpyDeviceToHost) != hipSuccess;
+        rc = rc || hipMemcpy(host_out, d, 21 * 64 * 4, hipMemcpyDeviceToHost) != hipSuccess;
     }
     (void)hipFree(d);
     (void)hipFree(in);

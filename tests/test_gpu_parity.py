@@ -46,7 +46,7 @@ def test_wave_primitive_lane_layout():
     import ctypes
     import torch  # noqa: F401  (PyTorch's copy of the HIP runtime first, so that this library binds to the same instance)
     lib = ctypes.CDLL(os.path.join(os.path.dirname(__file__), "selftest", "libwave_selftest.so"))  # test-only library
-    out = np.zeros((19, 64), np.uint32)
+    out = np.zeros((21, 64), np.uint32)
     assert lib.est_selftest_wave(ctypes.c_void_p(out.ctypes.data)) == 0
     ln = np.arange(64)
     v = 7 * ln + 3
@@ -67,6 +67,9 @@ def test_wave_primitive_lane_layout():
     assert out[16].tolist() == [0xFFFFFFFF] * 64
     assert out[17].tolist() == [0b001010101] * 64
     assert out[18].tolist() == (1000 + ln).tolist()
+    sq = scr * scr + 1
+    assert out[19].tolist() == (np.cumsum(sq) - sq).tolist()
+    assert out[20].tolist() == [int(sq.sum())] * 64
 
 
 def _hand_examples():
