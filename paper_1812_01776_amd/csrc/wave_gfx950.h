@@ -124,16 +124,19 @@ EST_DEV uint32_t sum_u32(uint32_t v) {
     return bcast(v, 0) + bcast(v, 16) + bcast(v, 32) + bcast(v, 48);
 }
 
-// exclusive prefix sum over lanes.  (Through the LDS crossbar: the variant built from row shifts and row
-// broadcasts measured 5 % slower on the whole sweep.)
+// exclusive prefix sum over lanes: shifts by 1, 2, 4, 8 inside the rows of 16 lanes (zeros come in at the row's
+// start), then the totals of the rows before a lane's own are added from scalar registers.  (Carrying the row
+// totals across with row broadcasts instead measured 5 % slower on the whole sweep.)
 EST_DEV uint32_t prefix_excl_u32(uint32_t v) {
     uint32_t x = v;
-#pragma unroll
-    for (uint32_t d = 1; d < 64; d <<= 1) {
-        uint32_t o = shfl(x, lane() - d);
-        if (lane() >= d) x += o;
-    }
-    return x - v;
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xF, 0xF, true);  // row_shr:1
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xF, 0xF, true);  // row_shr:2
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xF, 0xF, true);  // row_shr:4
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xF, 0xF, true);  // row_shr:8
+    const uint32_t t0 = bcast(x, 15), t1 = t0 + bcast(x, 31), t2 = t1 + bcast(x, 47);
+    const uint32_t row = lane() >> 4;
+    const uint32_t before = row == 0u ? 0u : row == 1u ? t0 : row == 2u ? t1 : t2;
+    return x + before - v;
 }
 
 // Make earlier memory writes (global and LDS) of any lane visible to later reads of any lane
