@@ -1298,27 +1298,27 @@ EST_UNROLL
         // element whose partner is unset or larger is not the last.  No counting, no read-modify-write.
         //
         // LDS: per source a ring of MERGE_RING staged keys (uint64) | per source 64 passed-on keys (uint64) |
-        // per source MERGE_RING accept masks (uint8) | per-source scalars (uint32 [12][EST_KMAX]).
+        // per source MERGE_RING accept masks (uint8).  The per-source scalars live in two vector registers, one
+        // lane per (field, source): reading one is a lane read into a scalar register, not a trip to LDS.
         const uint32_t KS = P.max_src;
         uint64_t *rkey = c.lds;
         uint64_t *lst = c.lds + KS * MERGE_RING;
         uint8_t *racc = (uint8_t *)(lst + KS * 64);
-        uint32_t *sc = (uint32_t *)(racc + KS * MERGE_RING);
-        uint32_t *s_rd = sc, *s_wr = sc + EST_KMAX, *s_fin = sc + 2 * EST_KMAX, *s_head = sc + 3 * EST_KMAX, *s_tail = sc + 4 * EST_KMAX,
-                 *s_mask = sc + 5 * EST_KMAX, *s_blo = sc + 6 * EST_KMAX, *s_bhi = sc + 7 * EST_KMAX, *nst = sc + 8 * EST_KMAX,
-                 *nfin = sc + 9 * EST_KMAX, *m_src = sc + 10 * EST_KMAX;
+        enum { F_RD = 0, F_WR = 8, F_FIN = 16, F_HEAD = 24, F_TAIL = 32, F_MASK = 40, F_BLO = 48, F_BHI = 56,  // va: lane = field + source
+               F_NFIN = 0, F_CONS = 8 };                                                                    // vb: passed on / consumed this round
+        uint32_t va = 0, vb = 0;
         const uint32_t tab_mask = wv::uniform(op.tab_mask), tab_len = wv::uniform(op.tab_len);
         uint32_t *tab0 = (uint32_t *)(c.tab + op.tab_off);
         for (uint32_t j = 0; j < K; ++j) {
-            const View sv = view_of<MEMO>(c, op.src_ring[j]);
-            if (ln == 0) {
-                s_rd[j] = c.st[P.rd_off + op.src_edge[j]];
-                s_wr[j] = sv.wr; s_fin[j] = sv.fin; s_mask[j] = sv.mask;
-                s_blo[j] = (uint32_t)(uintptr_t)sv.base; s_bhi[j] = (uint32_t)((uint64_t)(uintptr_t)sv.base >> 32);
-                s_head[j] = 0; s_tail[j] = 0; nst[j] = 0;
-            }
+            const View sv = uniform_view_of<MEMO>(c, op.src_ring[j]);
+            const uint64_t bp = (uint64_t)(uintptr_t)sv.base;
+            va = wv::set_lane(va, wv::uniform(c.st[P.rd_off + op.src_edge[j]]), F_RD + j);
+            va = wv::set_lane(va, sv.wr, F_WR + j);
+            va = wv::set_lane(va, sv.fin, F_FIN + j);
+            va = wv::set_lane(va, sv.mask, F_MASK + j);
+            va = wv::set_lane(va, wv::uniform((uint32_t)bp), F_BLO + j);
+            va = wv::set_lane(va, wv::uniform((uint32_t)(bp >> 32)), F_BHI + j);
         }
-        wv::sync_lds();
         for (;;) {
             if (!is_lat && space < 64u * K) break;  // wait for the consumer
             // ---- refill: every source with no more than a window staged takes up to 64 further elements; the
@@ -1334,11 +1334,11 @@ EST_UNROLL
                     wx[u] = 0;
                     kx[u] = 0;
                     if (j < K) {
-                        const uint32_t staged = wv::uniform(s_tail[j]) - wv::uniform(s_head[j]);
-                        const uint32_t rd = wv::uniform(s_rd[j]), left = wv::uniform(s_wr[j]) - rd;
+                        const uint32_t staged = wv::bcast(va, F_TAIL + j) - wv::bcast(va, F_HEAD + j);
+                        const uint32_t rd = wv::bcast(va, F_RD + j), left = wv::bcast(va, F_WR + j) - rd;
                         if (staged <= 64u && left > 0u) {
-                            const uint64_t *base = (const uint64_t *)(uintptr_t)(((uint64_t)wv::uniform(s_bhi[j]) << 32) | wv::uniform(s_blo[j]));
-                            const uint32_t smask = wv::uniform(s_mask[j]);
+                            const uint64_t *base = (const uint64_t *)(uintptr_t)(((uint64_t)wv::bcast(va, F_BHI + j) << 32) | wv::bcast(va, F_BLO + j));
+                            const uint32_t smask = wv::bcast(va, F_MASK + j);
                             wx[u] = umin(64u, left);
                             if (ln < wx[u]) kx[u] = base[(rd + ln) & smask];
                             some = true;
@@ -1357,28 +1357,25 @@ EST_UNROLL
                     if (!((am >> j) & 1u)) am = 0;  // not for this stage, or superseded by a nearer ancestor
                     if (((tab_mask >> j) & 1u) && (am & (am - 1u)))
                         tab0[(uint64_t)__builtin_popcount(tab_mask & ((1u << j) - 1u)) * tab_len + (uint32_t)kx[u]] = (uint32_t)(kx[u] >> 32);
-                    const uint32_t at = j * MERGE_RING + ((wv::uniform(s_tail[j]) + ln) & (MERGE_RING - 1u));
+                    const uint32_t tl = wv::bcast(va, F_TAIL + j);
+                    const uint32_t at = j * MERGE_RING + ((tl + ln) & (MERGE_RING - 1u));
                     if (ln < wx[u]) {
                         rkey[at] = kx[u];
                         racc[at] = (uint8_t)am;
                     }
-                    if (ln == 0) { nst[j] = wx[u]; }  // (added to the cursors below, once the ring positions have been read)
+                    va = wv::set_lane(va, tl + wx[u], F_TAIL + j);
+                    va = wv::set_lane(va, wv::bcast(va, F_RD + j) + wx[u], F_RD + j);
                 }
             }
-            if (any) {
-                wv::sync();  // (tables and staged elements: written above, read below by other lanes)
-                if (ln == 0)
-                    for (uint32_t j = 0; j < K; ++j) { s_tail[j] += nst[j]; s_rd[j] += nst[j]; nst[j] = 0; }
-                wv::sync_lds();
-            }
+            if (any) wv::sync();  // (tables and staged elements: written above, read below by other lanes)
             // ---- the window of every source: its first 64 staged elements
             uint32_t more = 0, total = 0;  // more, bit j: source j may hold elements beyond its window
             bool blocked = false, clamped = false;
             uint64_t bound = ~0ull;  // everything up to the smallest last key of a source that may hold more is final
             for (uint32_t j = 0; j < K; ++j) {
-                const uint32_t h = wv::uniform(s_head[j]), staged = wv::uniform(s_tail[j]) - h;
+                const uint32_t h = wv::bcast(va, F_HEAD + j), staged = wv::bcast(va, F_TAIL + j) - h;
                 const uint32_t w = umin(64u, staged);
-                const bool has_more = staged > 64u || wv::uniform(s_rd[j]) != wv::uniform(s_wr[j]) || !wv::uniform(s_fin[j]);
+                const bool has_more = staged > 64u || wv::bcast(va, F_RD + j) != wv::bcast(va, F_WR + j) || !wv::bcast(va, F_FIN + j);
                 if (has_more) more |= 1u << j;
                 total += w;
                 if (w == 0) {
@@ -1409,13 +1406,14 @@ EST_UNROLL
                     const uint32_t j = j0 + u;
                     kx[u] = 0; amx[u] = 0; t2x[u] = 0; px[u] = false;
                     if (j < K) {
-                        const uint32_t w = umin(64u, wv::uniform(s_tail[j]) - wv::uniform(s_head[j]));
-                        const uint32_t at = j * MERGE_RING + ((wv::uniform(s_head[j]) + ln) & (MERGE_RING - 1u));
+                        const uint32_t h = wv::bcast(va, F_HEAD + j);
+                        const uint32_t w = umin(64u, wv::bcast(va, F_TAIL + j) - h);
+                        const uint32_t at = j * MERGE_RING + ((h + ln) & (MERGE_RING - 1u));
                         if (ln < w) { kx[u] = rkey[at]; amx[u] = racc[at]; }
                         const uint64_t x = clamped ? eff_key(kx[u], j, ln) : kx[u];
                         const bool consumed = ln < w && x <= bound;  // a prefix of the window: a source's keys ascend
                         const uint32_t mj = popc64(wv::ballot(consumed));
-                        if (ln == 0) m_src[j] = mj;
+                        vb = wv::set_lane(vb, mj, F_CONS + j);
                         px[u] = consumed && amx[u] != 0u;
                         const uint32_t others = amx[u] & ~(1u << j);
                         if (px[u] && others != 0u) {
@@ -1447,7 +1445,7 @@ EST_UNROLL
                         const uint64_t F = wv::ballot(pass);
                         const uint32_t fr = wv::rank_below(F);
                         if (pass) lst[j * 64 + fr] = kx[u];
-                        if (ln == 0) nfin[j] = popc64(F);
+                        vb = wv::set_lane(vb, popc64(F), F_NFIN + j);
                         n_out += popc64(F);
                     }
                 }
@@ -1456,19 +1454,19 @@ EST_UNROLL
             wv::sync_lds();
             // ---- place every passed-on element: its rank in its own list plus the smaller elements of the others
             for (uint32_t j = 0; j < K; ++j) {
-                const uint32_t nf = wv::uniform(nfin[j]);
+                const uint32_t nf = wv::bcast(vb, F_NFIN + j);
                 if (nf == 0) continue;
                 const bool have = ln < nf;
                 const uint64_t rk = have ? lst[j * 64 + ln] : 0ull;
                 uint32_t rank = ln;
                 for (uint32_t j2 = 0; j2 < K; ++j2) {
-                    const uint32_t n2 = wv::uniform(nfin[j2]);
+                    const uint32_t n2 = wv::bcast(vb, F_NFIN + j2);
                     if (j2 == j || n2 == 0) continue;
                     const uint64_t *l2 = lst + j2 * 64;
+                    const uint32_t top = 1u << (31u - (uint32_t)__builtin_clz(n2));  // the largest power of two within the list
                     uint32_t lo = 0;  // elements of list j2 below rk (no two lists hold the same key: one element per query is passed on)
                     if (!clamped) {
-EST_UNROLL
-                        for (uint32_t step = 64; step >= 1; step >>= 1) {
+                        for (uint32_t step = top; step >= 1; step >>= 1) {
                             const uint32_t i = lo + step;
                             const bool in = i <= n2;
                             const uint64_t y = l2[in ? i - 1u : 0u];
@@ -1476,7 +1474,7 @@ EST_UNROLL
                         }
                     } else {
                         const uint64_t x = eff_key(rk, j, ln);
-                        for (uint32_t step = 64; step >= 1; step >>= 1) {
+                        for (uint32_t step = top; step >= 1; step >>= 1) {
                             const uint32_t i = lo + step;
                             const bool in = i <= n2;
                             const uint64_t y = eff_key(l2[in ? i - 1u : 0u], j2, in ? i - 1u : 0u);
@@ -1499,14 +1497,15 @@ EST_UNROLL
             }
             wr += n_out;
             if (!is_lat) space -= n_out;  // (nobody consumes while this operation runs)
-            if (ln == 0)
-                for (uint32_t j = 0; j < K; ++j) s_head[j] += m_src[j];
+            for (uint32_t j = 0; j < K; ++j) va = wv::set_lane(va, wv::bcast(va, F_HEAD + j) + wv::bcast(vb, F_CONS + j), F_HEAD + j);
             progress = true;
             wv::sync_lds();
         }
         // staged but not consumed: read again next time
-        if (ln == 0)
-            for (uint32_t j = 0; j < K; ++j) st_st(&c.st[P.rd_off + op.src_edge[j]], s_rd[j] - (s_tail[j] - s_head[j]));
+        for (uint32_t j = 0; j < K; ++j) {
+            const uint32_t back = wv::bcast(va, F_RD + j) - (wv::bcast(va, F_TAIL + j) - wv::bcast(va, F_HEAD + j));
+            if (ln == 0) st_st(&c.st[P.rd_off + op.src_edge[j]], back);
+        }
     }
 
     if (DIAG && c.a->dbg_ticks && ln == 0) { uint64_t *po = est_dbg_rec(c.a, c.t, EST_MAX_STAGES - 1); po[3] += d_rounds; po[4] += d_elems; po[5] += 1; }

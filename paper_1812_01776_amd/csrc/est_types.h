@@ -14,7 +14,7 @@
 #define EST_MAX_CONS 36         // consumers of one ring
 #define EST_TRACE_BIT 32        // bit of the "arrival trace" pseudo-source in a source set
 #define EST_SRC_TRACE (-1)
-#define EST_LDS_MERGE_BYTES(k) ((k) * 1664u + 512u)   // LDS of one wavefront for a k-source merge: staged keys 128 x 8, passed-on keys 64 x 8, accept masks 128 per source; scalars
+#define EST_LDS_MERGE_BYTES(k) ((k) * 1664u)   // LDS of one wavefront for a k-source merge: staged keys 128 x 8, passed-on keys 64 x 8, accept masks 128 per source
 #define EST_LDS_SCAN_BYTES(rb) (3616u + 4u * (rb))      // ... for a scan whose replica slots hold rb members
 
 enum { EST_OP_SCAN = 0, EST_OP_MERGE = 1, EST_OP_LAT = 2 };
