@@ -731,6 +731,10 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 const uint32_t told = wv::shfl(rend, ln + m);
                 const uint32_t tnew = wv::shfl(x, ln + m - R);
                 if (isrep) rend = ln < keep ? told : tnew;
+                // (old entries that stay hold no members, so they ended by some earlier start + L(1): no later than the new ends)
+                const uint32_t rbefore = wv::shr1(rend);
+                EST_CHECK(ln == 0 || !isrep || rend >= rbefore);
+                (void)rbefore;
                 lhead += m;
                 progress = true;
                 continue;
@@ -1828,7 +1832,7 @@ EST_DEV void cfg_thread(const EstCfgArgs &a, uint32_t tid, uint32_t nthreads) {
     for (uint64_t i = tid; i < a.n_cfg; i += nthreads) {
         for (uint32_t s = 0; s < d.S; ++s) {
             const EstStageCfg e = a.cfg[i * d.S + s];
-            if (e.hw >= d.H || e.batch < 1 || e.batch > d.Bmax || e.replicas < 1 || e.replicas > 64) bad = true;
+            if (e.hw >= d.H || e.batch < 1 || e.batch > d.Bmax || e.replicas < 1 || e.replicas > EST_MAX_REPLICAS) bad = true;
             rmax[s] = umax(rmax[s], e.replicas);
             bmax[s] = umax(bmax[s], e.batch);
         }

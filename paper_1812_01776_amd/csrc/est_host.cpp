@@ -611,7 +611,11 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
     //      candidates leave (a launch of a few hundred bases alone would leave most of the device idle for as
     //      long as one simulation takes)
     const uint64_t n_pad = align_up(std::max<uint64_t>(n, 1), 256);
-    const uint64_t cap_bytes = po.sz.state_words * 4 + cap_elems * 8 + po.sz.rep_words * 4 + po.sz.slot_words * 4 + po.sz.tab_bytes + 8 + 8;
+    // (the bases need the joins' time tables only when their launch runs a join)
+    uint64_t cap_tab_bytes = 0;
+    for (uint32_t i = 0; i < P.n_ops; ++i)
+        if (((needed >> i) & 1ull) && P.ops[i].tab_mask) cap_tab_bytes = po.sz.tab_bytes;
+    const uint64_t cap_bytes = po.sz.state_words * 4 + cap_elems * 8 + po.sz.rep_words * 4 + po.sz.slot_words * 4 + cap_tab_bytes + 8 + 8;
     const uint64_t per_cfg = po.sz.per_cfg_bytes(n, true) + 64;
     const uint32_t resident = std::max<uint32_t>(estbe::max_resident_waves(po.lds_bytes), 1);
     const uint64_t avail = ((uint64_t)estbe::mem_free() + h->ws_bytes) / 100 * 85;
@@ -682,7 +686,7 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
         o_crings[i] = take(nb * cap_elems * 8);
         o_crep[i] = take(nb * po.sz.rep_words * 4);
         o_cslots[i] = take(nb * po.sz.slot_words * 4);
-        o_ctab[i] = take(nb * po.sz.tab_bytes);
+        o_ctab[i] = take(nb * cap_tab_bytes);
     }
     auto area = [&](uint64_t bytes_per_cfg) {
         uint64_t a0 = at;
@@ -774,7 +778,7 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
         c2.rings = (uint64_t *)(ws + o_crings[ar]);  c2.ring_stride = cap_elems;
         c2.rep = (uint32_t *)(ws + o_crep[ar]);      c2.rep_stride = po.sz.rep_words;
         c2.slots = (uint32_t *)(ws + o_cslots[ar]);  c2.slot_stride = po.sz.slot_words;
-        c2.tabs = ws + o_ctab[ar];               c2.tab_stride = po.sz.tab_bytes;
+        c2.tabs = ws + o_ctab[ar];               c2.tab_stride = cap_tab_bytes;
         c2.lat = nullptr;
         c2.p99 = (uint32_t *)(ws + o_res_cap); c2.miss = (uint32_t *)(ws + o_res_cap); c2.cost = (uint64_t *)(ws + o_res_cap);
         c2.skip_ops = (const uint64_t *)(ws + o_skip_cap);
