@@ -214,6 +214,8 @@ def main():
                           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32", "data": "synthetic",
                           "config": {"workload": args.workload, "n_configs": C, "n_queries": w.n_queries, "bases": int(len(used)), "library_calls": calls,
                                      "kernel_ms": sim_ms, "kernel_ms_bases": cap_ms, "operations_run_fraction": float(sum(frac) / C),
+                                     "sharing": ("the library simulated every candidate on its own: the rounds the memory forces were estimated slower "
+                                                 "(EST_SHARED_ALWAYS=1 forces them)") if sum(frac) >= C else "upstream stages shared",
                                      "feasible_configs": int((p99 <= w.slo_us).sum())},
                           "cpu_baseline": cpu}))
         return

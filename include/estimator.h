@@ -169,7 +169,10 @@ int estimator_run_latencies(estimator_t *h, const est_trace_t *trace, const est_
  * The library allocates the scratch (cached in the handle like estimator_run_dev's).  The streams shared
  * by one base take 8 bytes x queries per shared stream; when those of all bases do not fit, the bases
  * are taken in rounds, the next round's bases running on a second stream of the library's own (default
- * priority) beside the current round's candidates.  All work has completed when the call returns.
+ * priority) beside the current round's candidates; when the rounds the memory forces are estimated to take
+ * longer than simulating every candidate on its own, the call does that instead (est_stats_t.ops_run_fraction
+ * then reads 1; the environment variable EST_SHARED_ALWAYS switches this off, for measurements).  All work has
+ * completed when the call returns.
  * Errors as estimator_run_dev; EST_EINVAL for a base_of entry out of range; EST_ENOMEM when not even
  * one base's streams fit beside one candidate's scratch; EST_EUNSUPPORTED for pipelines whose run
  * needs more than 64 operations or streams.

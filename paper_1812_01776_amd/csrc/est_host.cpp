@@ -623,8 +623,25 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
     uint64_t n_slots = std::min<uint64_t>(n_cfg, resident);
     uint64_t nb = n_bases;  // bases per round
     uint32_t n_areas = 1;
+    // what a base brings in candidate work, in units of one full simulation: its candidates x the share of the
+    // plan's elements they still move
+    double all_work = 0, run_work = 0;
+    for (uint32_t i = 0; i < P.n_ops; ++i) all_work += (double)st.n_visit[P.ops[i].stage];
+    for (uint64_t t = 0; t < n_cfg; ++t)
+        for (uint32_t i = 0; i < P.n_ops; ++i)
+            if (!((skip[t] >> i) & 1ull)) run_work += (double)st.n_visit[P.ops[i].stage];
+    const double work_per_base = std::max(run_work / std::max(all_work, 1.0) / (double)n_bases, 1e-3);
     if (fixed_est + n_bases * cap_bytes + per_cfg * n_slots > avail) {
         n_areas = 2;
+        // A round's bases run beside the previous round's candidates and last as long as the slowest full simulation
+        // among them; they stay hidden when the candidates of a round keep their wavefronts busy for at least that long.
+        // In units of an average full simulation a base brings work_per_base of candidate work (its candidates x the
+        // share of the plan's elements they still move), and the slowest of a round takes about two: so a round
+        // wants at least n_slots / (work_per_base / 2) bases, and the memory is split between candidate slots and
+        // the two capture areas in that proportion.
+        const double room = avail > fixed_est ? (double)(avail - fixed_est) : 0.0;
+        const double balanced = room / ((double)per_cfg + 2.0 * (double)cap_bytes * 2.0 / work_per_base);
+        n_slots = std::min<uint64_t>(n_slots, std::max<uint64_t>(64, (uint64_t)balanced));
         for (;;) {
             const uint64_t rest = avail > fixed_est + per_cfg * n_slots ? avail - fixed_est - per_cfg * n_slots : 0;
             nb = rest / (2 * cap_bytes);
@@ -645,6 +662,20 @@ int run_shared_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const u
     }
     const uint64_t n_rounds = (n_bases + nb - 1) / nb;
     if (n_rounds == 1) n_areas = 1;
+    if (n_rounds > 1 && !getenv("EST_SHARED_BASES_PER_ROUND") && !getenv("EST_SHARED_ALWAYS")) {
+        // Sharing is an optimisation, not a semantics: when the rounds the memory forces are estimated to take longer
+        // than simulating every candidate on its own, do that.  Times in units of one average full simulation on a
+        // full device: a round lasts as long as its bases (about two, the slowest of them) or its candidates, the
+        // launches of a round end on their own tails (x 1.3, measured), the first round's bases run alone.
+        const double per_round = std::max(2.0, (double)nb * work_per_base / (double)n_slots);
+        const double est_shared = 1.3 * (double)n_rounds * per_round + 2.0;
+        const double est_plain = (double)n_cfg / (double)std::min<uint64_t>(n_cfg, resident);
+        if (est_shared >= est_plain) {
+            const int rc = run_core(h, n, d_arrival, d_mask, d_cfg, n_cfg, slo_us, MODE_P99, d_p99, d_miss, d_cost, nullptr, nullptr, 0, stream);
+            if (rc == EST_OK) h->stats.ops_run_fraction = 1.0f;
+            return rc;
+        }
+    }
 
     // candidates grouped by round; inside a round those that run the most operations are handed out first,
     // so that a launch ends on short ones
