@@ -223,14 +223,15 @@ EST_DEV uint64_t sort_time_query(uint32_t e, uint32_t q, uint64_t VM, uint32_t b
 // ------------------------------------------------------------------------------------------ SCAN
 //
 // Per-wavefront working set of a scan, in LDS:
-//   in-ring   256 keys: the next elements of the stage's input stream,
+//   in-ring   128 or 256 keys (EstPlan::scan_ring: the smaller one where it lets one more wavefront share a SIMD):
+//             the next elements of the stage's input stream,
 //             refilled from the source ring in chunks (and filtered on the way, when only some
 //             elements of the source visit the stage);
 //   slots     one per replica: the members of the replica's last batch, sorted by query index,
 //             waiting to be emitted when the batch completes.
 // The replica table lives in registers, lane r holding the r-th replica in order of the time it is
 // free again, so the earliest free replica is lane 0 and batches complete in lane order.
-enum { SCAN_INRING = 256 };
+
 
 // Write the members of the batches in the table lanes of tie, which all complete at time mv, merged by
 // query index, to out[base ...]; returns their number.  (Times clamped at the horizon need no order:
@@ -438,12 +439,13 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     uint32_t *g_end = c.rep + op.rep_off, *g_cnt = g_end + op.r_max, *g_slot = g_cnt + op.r_max;
     uint32_t *g_slots = c.slots + op.slot_off;
     uint64_t *lkey = c.lds;
-    uint32_t *ltab = (uint32_t *)(c.lds + SCAN_INRING);  // 4 x 64 words of per-group values (reused as staging by the rare table re-sort)
+    const uint32_t RING = wv::uniform(P.scan_ring), rmask = RING - 1u;
+    uint32_t *ltab = (uint32_t *)(c.lds + RING);  // 4 x 64 words of per-group values (reused as staging by the rare table re-sort)
     uint32_t *lstart = ltab + 256;         // 65 (of 72): first lane of each group of a window (+ the end)
-    uint32_t *linv = ltab + 328;           // 64: linv[d-1] = ceil(65536 / d), so that floor(x / d) = x * linv[d-1] >> 16 for x <= 64
-    uint32_t *lslots = ltab + 392;
+    uint16_t *linv = (uint16_t *)(ltab + 328);  // 64 half words: linv[d-1] = ceil(65536 / d) - 1, so that floor(x / d) = x * (linv[d-1] + 1) >> 16 for x <= 64
+    uint32_t *lslots = ltab + 360;
     const uint8_t *acc = c.a->acc + (uint64_t)op.acc_idx * c.a->acc_stride;
-    linv[ln] = (65536u + ln) / (ln + 1u);
+    linv[ln] = (uint16_t)((65536u + ln) / (ln + 1u) - 1u);
     const uint32_t inv_b = (65536u + B - 1u) / B, inv_r = (65536u + R - 1u) / R;
 
     // replica table, sorted by the time the replica is free again
@@ -487,8 +489,9 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
     for (;;) {
         uint32_t staged = ltail - lhead;
         if (staged < 64 && rraw != in.wr) {
-            // refill: up to three 64-element windows of the source, loads issued together
-            const uint32_t left = in.wr - rraw;
+            // refill: as much of the source as the ring has room for beside what is staged (up to three loads of 64
+            // elements, issued together)
+            const uint32_t left = umin(umin(in.wr - rraw, RING - staged), 192u);
             const uint32_t w0 = umin(left, 64u), w1 = left > 64 ? umin(left - 64, 64u) : 0u,
                            w2 = left > 128 ? umin(left - 128, 64u) : 0u;
             const uint64_t k0 = ln < w0 ? in.base[(rraw + ln) & in.mask] : 0ull;
@@ -502,17 +505,17 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                 A0 &= wv::ballot(f0); A1 &= wv::ballot(f1); A2 &= wv::ballot(f2);
                 a0 = a0 && f0; a1 = a1 && f1; a2 = a2 && f2;
             }
-            const uint32_t i0 = (ltail + wv::rank_below(A0)) & (SCAN_INRING - 1);
+            const uint32_t i0 = (ltail + wv::rank_below(A0)) & rmask;
             ltail += popc64(A0);
-            const uint32_t i1 = (ltail + wv::rank_below(A1)) & (SCAN_INRING - 1);
+            const uint32_t i1 = (ltail + wv::rank_below(A1)) & rmask;
             ltail += popc64(A1);
-            const uint32_t i2 = (ltail + wv::rank_below(A2)) & (SCAN_INRING - 1);
+            const uint32_t i2 = (ltail + wv::rank_below(A2)) & rmask;
             ltail += popc64(A2);
             if (a0) lkey[i0] = k0;
             if (a1) lkey[i1] = k1;
             if (a2) lkey[i2] = k2;
             rraw += w0 + w1 + w2;
-            EST_CHECK(ltail - lhead <= SCAN_INRING);
+            EST_CHECK(ltail - lhead <= RING);
             wv::sync_lds();
             continue;
         }
@@ -528,10 +531,10 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
         if (space < 64u) break;
         if (DIAG) tk0 = wv::ticks();
         const uint32_t w = umin(staged, 64u);
-        const uint64_t key = ln < w ? lkey[(lhead + ln) & (SCAN_INRING - 1)] : ~0ull;
+        const uint64_t key = ln < w ? lkey[(lhead + ln) & rmask] : ~0ull;
         const uint32_t rdy = (uint32_t)(key >> 32);
         uint32_t q = (uint32_t)key;
-        EST_CHECK(ln == 0 || ln >= w || rdy == 0xFFFFFFFFu || key > lkey[(lhead + ln - 1) & (SCAN_INRING - 1)]);  // input is ordered
+        EST_CHECK(ln == 0 || ln >= w || rdy == 0xFFFFFFFFu || key > lkey[(lhead + ln - 1) & rmask]);  // input is ordered
         const uint32_t f0 = wv::uniform(rend);  // earliest free replica = lane 0
         if (f0 == 0xFFFFFFFFu) {
             // Every replica is busy up to the horizon: whatever is still queued starts and ends at the
@@ -631,7 +634,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
             //   equal completion times would have to be put in query order).
             const bool final = staged <= 64 && rraw == in.wr && in.fin;
             const uint64_t WM = lanes_below(w);
-            const uint32_t back = ln >= R && ln < w ? (uint32_t)(lkey[(lhead + ln - R) & (SCAN_INRING - 1)] >> 32) : 0u;
+            const uint32_t back = ln >= R && ln < w ? (uint32_t)(lkey[(lhead + ln - R) & rmask] >> 32) : 0u;
             const uint32_t prev1 = ln < R ? rend : sat_add(back, L1);
             uint64_t ok1 = WM & wv::ballot(prev1 <= rdy);
             if (B > 1) ok1 &= wv::ballot(rdy != wv::shl1(rdy)) | ~lanes_below(w - 1u);
@@ -935,7 +938,7 @@ EST_DEV bool scan_run(const Ctx &c, const EstOp &op, uint32_t opi) {
                         space -= ns + extra;
                         EST_CHK_ORDER(inv ? 3 : 2);
                         // the run's batches that finish at or after tau wait in the slot of their replica
-                        const uint32_t inv_p = wv::uniform(linv[p - 1u]);                      // floor(x / p) = x * inv_p >> 16 for x < 64
+                        const uint32_t inv_p = wv::uniform((uint32_t)linv[p - 1u]) + 1u;                      // floor(x / p) = x * inv_p >> 16 for x < 64
                         const uint32_t kmod = bid - p * ((bid * inv_p) >> 16);   // the replica (idle-table lane) of my group
                         const uint32_t myslot = wv::shfl(rslot, kmod);
                         const bool waits = ln < m && !safe;

@@ -196,7 +196,14 @@ int build_plan(estimator *h, const EstStatus &st, uint64_t n, PlanOut &po) {
     }
     P.max_src = 1;
     for (uint32_t i = 0; i < no; ++i) P.max_src = std::max(P.max_src, P.ops[i].n_src);
-    po.lds_bytes = (uint32_t)align_up(std::max<uint64_t>(EST_LDS_MERGE_BYTES(P.max_src), EST_LDS_SCAN_BYTES(max_rb)), 256);
+    // the scans' in-ring: 256 keys, or 128 where that lets one more wavefront share a SIMD (the smaller ring is
+    // refilled twice as often, which costs less than the extra wavefront brings)
+    const uint32_t lds256 = (uint32_t)align_up(std::max<uint64_t>(EST_LDS_MERGE_BYTES(P.max_src), EST_LDS_SCAN_BYTES(max_rb, 256u)), 256);
+    const uint32_t lds128 = (uint32_t)align_up(std::max<uint64_t>(EST_LDS_MERGE_BYTES(P.max_src), EST_LDS_SCAN_BYTES(max_rb, 128u)), 256);
+    P.scan_ring = estbe::waves_per_simd(lds128) > estbe::waves_per_simd(lds256) ? 128u : 256u;
+    if (const char *e = getenv("EST_SCAN_RING"))  // for tests: 128 or 256
+        if (atoi(e) == 128 || atoi(e) == 256) P.scan_ring = (uint32_t)atoi(e);
+    po.lds_bytes = P.scan_ring == 128u ? lds128 : lds256;
 
     // ring capacities: a stream read by several operations may have to hold the whole skew between
     // them (one branch of a fork can lag another by the length of its simulated queue), so it gets

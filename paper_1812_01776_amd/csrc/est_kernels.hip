@@ -22,8 +22,7 @@ int check(hipError_t e, const char *what) {
 
 // Four wavefronts per workgroup; each wavefront owns one scratch slot and its own part of the LDS
 // and works through candidates until the launch's work counter runs out.  The register budget is
-// pinned at 128 per lane (four wavefronts per SIMD): one register more would cost a quarter of the
-// resident wavefronts, which costs more than the few spills this forces.
+// pinned per build (WAVES_PER_SIMD resident wavefronts per SIMD: 128, 96 or 80 registers per lane).
 #define EST_WAVES_PER_BLOCK 4
 template <bool DIAG, int WAVES_PER_SIMD, bool MEMO = false>
 __global__ __launch_bounds__(64 * EST_WAVES_PER_BLOCK) __attribute__((amdgpu_waves_per_eu(WAVES_PER_SIMD, WAVES_PER_SIMD)))
@@ -76,13 +75,16 @@ void est_sim_mw_kernel(EstSimArgs a) {
     }
 }
 
-// The kernel is built for four wavefronts per SIMD (128 registers per lane) and for five (96 registers, a
-// few spills): the second is used when the LDS need of the launch lets five workgroups share a compute
-// unit, where the extra wavefront hides more latency than the spills cost.
+// The kernel is built for four wavefronts per SIMD (128 registers per lane, no spills), for five (96, a few
+// spills) and for six (80, about twenty): the build with the most wavefronts that the LDS need of the launch
+// allows is used, because each extra wavefront hides more latency than its spills cost.
 constexpr uint32_t LDS_PER_CU = 160u * 1024u;
-bool five_fit(uint32_t lds_bytes_per_wave) {
-    static const bool four = getenv("EST_FOUR_WAVES_PER_SIMD") != nullptr;  // tuning aid: always the 128-register build
-    return !four && (uint64_t)lds_bytes_per_wave * EST_WAVES_PER_BLOCK * 5u <= LDS_PER_CU;
+int waves_fit(uint32_t lds_bytes_per_wave) {
+    static const char *cap = getenv("EST_WAVES_PER_SIMD");  // tuning aid: no more than this many (4, 5 or 6)
+    const int most = cap ? atoi(cap) : 6;
+    for (int w = 6; w > 4; --w)
+        if (w <= most && (uint64_t)lds_bytes_per_wave * EST_WAVES_PER_BLOCK * (uint32_t)w <= LDS_PER_CU) return w;
+    return 4;
 }
 
 __global__ __launch_bounds__(256) void est_prep1_kernel(EstPrepArgs a) {
@@ -178,6 +180,7 @@ int launch_envelope(const EstEnvArgs &a, void *stream) {
     est_envelope_kernel<<<blocks_for(a.n, 256 * 16, 8192), 256, 0, (hipStream_t)stream>>>(a);  // 16 queries in a row per thread
     return check(hipGetLastError(), "est_envelope_kernel");
 }
+uint32_t waves_per_simd(uint32_t lds_bytes_per_wave) { return (uint32_t)waves_fit(lds_bytes_per_wave); }
 int launch_sim_mw(const EstSimArgs &a, void *stream) {
     const size_t lds = (size_t)a.lds_bytes * EST_MW_WAVES;
     est_sim_mw_kernel<<<dim3(a.n_slots), dim3(64 * EST_MW_WAVES), lds, (hipStream_t)stream>>>(a);
@@ -198,13 +201,18 @@ int launch_sim(const EstSimArgs &a, void *stream) {
     const size_t lds = (size_t)a.lds_bytes * EST_WAVES_PER_BLOCK;
     const dim3 grid(blocks), block(64 * EST_WAVES_PER_BLOCK);
     if (a.skip_ops) {  // candidates that skip operations (shared upstream stages): the variant that reads the extra arguments
-        if (five_fit(a.lds_bytes))
+        const int w = waves_fit(a.lds_bytes);
+        if (w == 6)
+            est_sim_kernel<false, 6, true><<<grid, block, lds, (hipStream_t)stream>>>(a);
+        else if (w == 5)
             est_sim_kernel<false, 5, true><<<grid, block, lds, (hipStream_t)stream>>>(a);
         else
             est_sim_kernel<false, 4, true><<<grid, block, lds, (hipStream_t)stream>>>(a);
     } else if (a.dbg_ticks)
         est_sim_kernel<true, 4><<<grid, block, lds, (hipStream_t)stream>>>(a);
-    else if (five_fit(a.lds_bytes))
+    else if (waves_fit(a.lds_bytes) == 6)
+        est_sim_kernel<false, 6><<<grid, block, lds, (hipStream_t)stream>>>(a);
+    else if (waves_fit(a.lds_bytes) == 5)
         est_sim_kernel<false, 5><<<grid, block, lds, (hipStream_t)stream>>>(a);
     else
         est_sim_kernel<false, 4><<<grid, block, lds, (hipStream_t)stream>>>(a);
@@ -218,11 +226,11 @@ uint32_t max_resident_waves(uint32_t lds_bytes_per_wave) {
     int dev = 0, cus = 0, blocks = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    const hipError_t e = five_fit(lds_bytes_per_wave)
-                             ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_kernel<false, 5>, 64 * EST_WAVES_PER_BLOCK,
-                                                                            (size_t)lds_bytes_per_wave * EST_WAVES_PER_BLOCK)
-                             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_kernel<false, 4>, 64 * EST_WAVES_PER_BLOCK,
-                                                                            (size_t)lds_bytes_per_wave * EST_WAVES_PER_BLOCK);
+    const int w = waves_fit(lds_bytes_per_wave);
+    const size_t lds = (size_t)lds_bytes_per_wave * EST_WAVES_PER_BLOCK;
+    const hipError_t e = w == 6   ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_kernel<false, 6>, 64 * EST_WAVES_PER_BLOCK, lds)
+                         : w == 5 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_kernel<false, 5>, 64 * EST_WAVES_PER_BLOCK, lds)
+                                  : hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_kernel<false, 4>, 64 * EST_WAVES_PER_BLOCK, lds);
     if (e != hipSuccess || blocks < 1) blocks = 8;  // unknown: assume the most a compute unit can hold
     return (uint32_t)cus * (uint32_t)blocks * EST_WAVES_PER_BLOCK;
 }

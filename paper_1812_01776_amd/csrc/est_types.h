@@ -15,7 +15,7 @@
 #define EST_TRACE_BIT 32        // bit of the "arrival trace" pseudo-source in a source set
 #define EST_SRC_TRACE (-1)
 #define EST_LDS_MERGE_BYTES(k) ((k) * 1664u)   // LDS of one wavefront for a k-source merge: staged keys 128 x 8, passed-on keys 64 x 8, accept masks 128 per source
-#define EST_LDS_SCAN_BYTES(rb) (3616u + 4u * (rb))      // ... for a scan whose replica slots hold rb members
+#define EST_LDS_SCAN_BYTES(rb, ring) (1440u + 8u * (ring) + 4u * (rb))   // ... for a scan whose replica slots hold rb members and whose in-ring holds ring keys (128 or 256)
 
 enum { EST_OP_SCAN = 0, EST_OP_MERGE = 1, EST_OP_LAT = 2 };
 
@@ -52,7 +52,7 @@ struct EstOp {
 struct EstPlan {
     uint32_t n_ops, n_rings, n_edges, state_words;
     // state words of one candidate: wr[n_rings] | fin[n_rings] | rd[n_edges] | opdone[n_ops] | miss, latency count | pub[n_rings]
-    uint32_t wr_off, fin_off, rd_off, done_off, miss_off, max_src, pub_off, pad2;  // max_src: widest merge; pub: published prefix of each ring
+    uint32_t wr_off, fin_off, rd_off, done_off, miss_off, max_src, pub_off, scan_ring;  // max_src: widest merge; pub: published prefix of each ring; scan_ring: keys in a scan's LDS in-ring
     EstOp ops[EST_MAX_OPS];
     EstRing rings[EST_MAX_RINGS];
 };

@@ -170,6 +170,7 @@ int launch_sim_mw(const EstSimArgs &a, void *) {
 }
 uint32_t max_resident_groups(uint32_t) { return 2; }
 uint32_t max_resident_waves(uint32_t) { return 3; }
+uint32_t waves_per_simd(uint32_t) { return 4; }
 
 void *stream_create() { return malloc(1); }  // everything runs in program order here
 void stream_destroy(void *s) { free(s); }

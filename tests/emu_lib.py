@@ -1,6 +1,7 @@
 """Builds and loads the lock-step CPU emulation of the kernels (tests/emu): the same device source
 and host planner as the GPU library, with the wavefront primitives replaced by fibers.  Used only by
 the host-side checks of the kernel logic; the product binding never loads it."""
+import fcntl
 import os
 import subprocess
 
@@ -16,10 +17,19 @@ def build():
     srcs = [os.path.join(_EMU, "backend_emu.cpp"), os.path.join(_CSRC, "est_host.cpp"), os.path.join(_CSRC, "est_planner.cpp")]
     deps = srcs + [os.path.join(_EMU, "wave_emu.h")] + [os.path.join(_CSRC, f) for f in os.listdir(_CSRC)] + \
         [os.path.join(os.path.dirname(_HERE), "include", "estimator.h")]
-    if os.path.exists(_LIB) and all(os.path.getmtime(_LIB) >= os.path.getmtime(d) for d in deps):
+    def fresh():
+        return os.path.exists(_LIB) and all(os.path.getmtime(_LIB) >= os.path.getmtime(d) for d in deps)
+
+    if fresh():
         return _LIB
-    subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fPIC", "-shared", "-DEST_EMU_CHECKS", "-Wall", "-Wno-unused-parameter",
-                           "-o", _LIB] + srcs)
+    # one builder at a time (test workers start together), and the library appears under its name only when complete
+    with open(_LIB + ".lock", "w") as lock:
+        fcntl.flock(lock, fcntl.LOCK_EX)
+        if not fresh():
+            tmp = _LIB + ".tmp%d" % os.getpid()
+            subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fPIC", "-shared", "-DEST_EMU_CHECKS", "-Wall", "-Wno-unused-parameter",
+                                   "-o", tmp] + srcs)
+            os.replace(tmp, _LIB)
     return _LIB
 
 

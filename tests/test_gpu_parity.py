@@ -119,6 +119,14 @@ def test_bursts_of_large_groups(seed, waves):
     _compare(workloads.grouped_case(seed))
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_small_in_ring(seed, monkeypatch):
+    """The scans' LDS in-ring at 128 keys instead of 256 (what the host picks when that lets a sixth wavefront
+    share a SIMD, as on W4 and W5): refills of uneven length, with and without a filter."""
+    monkeypatch.setenv("EST_SCAN_RING", "128")
+    _compare([workloads.random_case, workloads.backlog_case, workloads.grouped_case, workloads.provisioned_case][seed % 4](seed + 100))
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_provisioned_small_batches_with_tied_completions(seed, waves):
     """Pipelines at 80-100 % utilisation with small batches on many replicas downstream of a batching stage

@@ -94,6 +94,17 @@ def test_several_wavefronts_per_candidate_match_oracle(seed, monkeypatch):
     assert est.stats()["waves_per_candidate"] == 4
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_small_in_ring_matches_oracle(seed, monkeypatch):
+    # the scans' LDS in-ring at 128 keys (what the host picks when that lets a sixth wavefront share a SIMD):
+    # refills of uneven length, with and without a filter
+    monkeypatch.setenv("EST_SCAN_RING", "128")
+    w = [workloads.random_case, workloads.backlog_case, workloads.grouped_case, workloads.provisioned_case][seed % 4](seed + 100)
+    if w.n_queries > 1500:
+        w = w.subset(n_queries=1500)
+    _compare(w)
+
+
 def test_wide_batches_many_replicas_and_ring_wrap():
     """R up to 16, B up to 64 and enough queries for the bounded rings to wrap several times; every
     time a multiple of 10 so that batches complete together and have to be merged by query index."""
