@@ -346,7 +346,11 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
         uint64_t want = fixed + per_cfg * max_slots + 8 * 256;
         uint64_t avail = (uint64_t)estbe::mem_free() + h->ws_bytes;
         uint64_t budget = std::min<uint64_t>(want, avail / 100 * 85);
-        if (h->ws_bytes < budget || h->ws_bytes > 2 * budget + (64u << 20)) {
+        // (when the free memory is what limits the scratch, the budget moves a little from call to call with whatever
+        // else the process allocates: a cached workspace within a sixteenth of it is kept, since freeing and
+        // allocating a few hundred GB costs seconds)
+        const bool too_small = budget < want ? h->ws_bytes < budget - budget / 16 : h->ws_bytes < budget;
+        if (too_small || h->ws_bytes > 2 * budget + (64u << 20)) {
             if (h->ws) estbe::dfree(h->ws);
             h->ws = nullptr;
             h->ws_bytes = 0;
