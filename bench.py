@@ -249,10 +249,10 @@ def main():
         if prof is not None and launches == passes:
             if prof["csrc_sha16"] == csrc_sha16():
                 r["traffic"] = prof["traffic_bytes"]
-                for key, peak in (("valu", VALU_PEAK_GINST_S), ("salu", SALU_PEAK_GINST_S)):
+                for key, peak, unit in (("valu", VALU_PEAK_GINST_S, "G wave64 vector instructions/s"), ("salu", SALU_PEAK_GINST_S, "G scalar instructions/s")):
                     g = prof[key + "_insts"] / avg_s / 1e9
                     r[key + "_issue"] = {"insts_per_launch": prof[key + "_insts"], "achieved": g, "peak": peak,
-                                         "unit": "G wave64 instructions/s", "frac": g / peak, "source": prof["source"]}
+                                         "unit": unit, "frac": g / peak, "source": prof["source"]}
             else:
                 r["profile_note"] = "counters in %s were taken on other kernel sources (%s): not repeated here" % (prof["source"], prof["csrc_sha16"])
         return r
