@@ -85,6 +85,8 @@ def main():
     ap.add_argument("--regime-sample", type=int, default=512, help="candidates run once more with step counters for config.regime_mix (0 = skip)")
     ap.add_argument("--largest-sweep", default="auto", choices=["auto", "always", "never"],
                     help="with --workload W4: also time one pass of W5 after the timed steps (auto: when it fits --budget-s)")
+    ap.add_argument("--provisioned", type=int, default=6144,
+                    help="with --workload W4: also time one call of this many candidates provisioned around the SLO boundary (0 = skip)")
     ap.add_argument("--budget-s", type=int, default=540, help="wall time the default run allows itself before it leaves out the W5 pass")
     ap.add_argument("--planner", action="store_true",
                     help="instead of the sweep, time the greedy planner (estimator_plan) on the workload's pipeline, trace and SLO")
@@ -349,6 +351,23 @@ def main():
     # the largest sweep (W5): one pass of it after the timed steps when that fits the time this run may take;
     # a pass of W5 does about 8.9 x the work of a pass of W4 (8 x the simulations, a few more visits per query)
     largest = None
+    # the regime a planner's search visits (W4's pipeline and trace, candidates provisioned around the SLO boundary):
+    # one call, timed like the sweep, reported beside it
+    provisioned = None
+    if args.workload == "W4" and args.provisioned > 0:
+        wp = workloads.w4_provisioned(n=w.n_queries, n_configs=args.provisioned, base=w)
+        cp = torch.from_numpy(estimator.pack_configs(wp.cfg_hw, wp.cfg_batch, wp.cfg_replicas).view(np.uint8).reshape(-1)).to(dev)
+        torch.cuda.synchronize()
+        q0 = time.perf_counter()
+        rp = est.run_dev(arr_t, msk_t, cp, wp.n_configs, wp.slo_us)
+        torch.cuda.synchronize()
+        q1 = time.perf_counter()
+        sp = est.stats()
+        pp = rp["p99_us"].cpu().numpy().view(np.uint32)
+        provisioned = {"workload": "W4p", "n_configs": wp.n_configs, "n_queries": wp.n_queries, "ms": (q1 - q0) * 1e3, "kernel_ms": sp["sim_ms"],
+                       "value": wp.n_configs * wp.n_queries / (q1 - q0), "unit": "config*query simulations/s",
+                       "feasible_configs": int((pp <= wp.slo_us).sum()),
+                       "roofline_frac": 8.0 * sp["stage_visits"] * wp.n_configs / (sp["sim_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS}
     if args.workload == "W5":
         largest = "this line"
     elif args.workload == "W4" and args.largest_sweep != "never":
@@ -386,7 +405,7 @@ def main():
         "config": {"workload": args.workload, "n_configs": w.n_configs, "n_queries": w.n_queries, "n_stages": w.n_stages,
                    "stage_visits_per_config": st["stage_visits"], "scratch_slots": st["n_slots"], "candidates_per_call": min(args.chunk, w.n_configs),
                    "feasible_configs": feasible, "kernel_sources_sha16": csrc_sha16(), "input_sha256": input_sha256, "largest_sweep": largest,
-                   "regime_mix": regime},
+                   "provisioned_regime": provisioned, "regime_mix": regime},
         "roofline": roof,
         "cpu_baseline": cpu,
     }

@@ -240,14 +240,15 @@ def w4(n=1_000_000):
     return Workload("W4", W45_PARENTS, lat, cost, arr, mask, hw, bt, rp, 250_000)
 
 
-def w4_provisioned(n=1_000_000, n_configs=16, seed=2404):
+def w4_provisioned(n=1_000_000, n_configs=16, seed=2404, base=None):
     """W4's pipeline, profiles, trace and masks with candidates that are provisioned for the load
     (the regime a planner's search spends its time in, around the SLO boundary): per stage a seeded
     batch size in {1, 2, 4, 8}, the hardware type with the lowest latency at that batch size, and
     replicas = ceil(f x demand / (B / L(B))) with a seeded head-room f in [0.9, 1.3], up to the 64
     replicas the interface allows.  The head-room grows with the candidate index, so the set runs
-    from slightly overloaded through barely stable to comfortably feasible."""
-    w = w4(n=n)
+    from slightly overloaded through barely stable to comfortably feasible.  (base: W4 as already generated, to
+    save generating it again.)"""
+    w = base if base is not None else w4(n=n)
     S = w.n_stages
     prng = np.random.default_rng(1004 + 500)
     pa, pb = prng.uniform(0.3, 1.0, size=2)  # the branch probabilities w4() drew
