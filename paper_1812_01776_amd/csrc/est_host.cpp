@@ -345,7 +345,7 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
         const uint64_t max_slots = std::min<uint64_t>(n_cfg, std::max<uint32_t>(estbe::max_resident_waves(po.lds_bytes), 1));
         uint64_t want = fixed + per_cfg * max_slots + 8 * 256;
         uint64_t avail = (uint64_t)estbe::mem_free() + h->ws_bytes;
-        uint64_t budget = std::min<uint64_t>(want, avail / 100 * 85);
+        uint64_t budget = std::min<uint64_t>(want, avail / 100 * 92);  // (an allocation that fails is tried again smaller, below)
         // (when the free memory is what limits the scratch, the budget moves a little from call to call with whatever
         // else the process allocates: a cached workspace within a sixteenth of it is kept, since freeing and
         // allocating a few hundred GB costs seconds)
@@ -355,6 +355,10 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
             h->ws = nullptr;
             h->ws_bytes = 0;
             h->ws = estbe::dmalloc(budget);
+            for (int shrink = 0; !h->ws && shrink < 3 && budget < want; ++shrink) {  // the free memory was less than reported: fewer slots
+                budget = budget / 8 * 7;
+                h->ws = estbe::dmalloc(budget);
+            }
             if (!h->ws) return fail(h, EST_ENOMEM, "cannot allocate %llu bytes of device scratch", (unsigned long long)budget);
             h->ws_bytes = budget;
         }

@@ -134,7 +134,10 @@ int init() {
 
 void *dmalloc(size_t bytes) {
     void *p = nullptr;
-    if (check(hipMalloc(&p, bytes), "hipMalloc")) return nullptr;
+    if (check(hipMalloc(&p, bytes), "hipMalloc")) {
+        (void)hipGetLastError();  // (the caller may try again smaller: no stale error for the next launch check to find)
+        return nullptr;
+    }
     return p;
 }
 
