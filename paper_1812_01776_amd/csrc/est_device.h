@@ -233,11 +233,28 @@ EST_DEV uint64_t sort_time_query(uint32_t e, uint32_t q, uint64_t VM, uint32_t b
 // free again, so the earliest free replica is lane 0 and batches complete in lane order.
 
 
+// Number of lanes whose value is below x (<= x with incl), for values that ascend with the lane: a binary search
+// over the lanes, the same for every lane's own x.  Only the first width lanes are searched (a power of two, the
+// same in every lane): no lane from there on may pass the test.
+EST_DEV uint32_t lanes_less(uint32_t v, uint32_t x, bool incl, uint32_t width = 64u) {
+    uint32_t pos = 0;
+    for (uint32_t step = width >> 1; step >= 1; step >>= 1) {
+        const uint32_t y = wv::shfl(v, pos + step - 1u);
+        if (incl ? y <= x : y < x) pos += step;
+    }
+    const uint32_t y = wv::shfl(v, width - 1u);  // (pos is width-1 only when the lanes before that one all pass)
+    if (pos == width - 1u && (incl ? y <= x : y < x)) pos = width;
+    return pos;
+}
+
+// The smallest power of two that is at least n (n from 1 to 64), at least 2
+EST_DEV uint32_t pow2_at_least(uint32_t n) { return n <= 2u ? 2u : 1u << (32u - (uint32_t)__builtin_clz(n - 1u)); }
+
 // Write the members of the batches in the table lanes of tie, which all complete at time mv, merged by
 // query index, to out[base ...]; returns their number.  (Times clamped at the horizon need no order:
-// everything downstream of a clamped time is clamped too, so those are concatenated.)
+// everything downstream of a clamped time is clamped too, so those are concatenated.)  tw: lanes of the table.
 EST_DEV uint32_t emit_tied(const EstOp &op, const uint32_t *lslots, uint64_t tie, uint32_t mv, uint32_t rcnt, uint32_t rslot,
-                           uint64_t *out, uint32_t omask, uint32_t base) {
+                           uint64_t *out, uint32_t omask, uint32_t base, uint32_t tw) {
     const uint32_t ln = wv::lane();
     const uint32_t bm = wv::uniform(op.b_max);
     const uint64_t tkey = (uint64_t)mv << 32;
@@ -251,7 +268,21 @@ EST_DEV uint32_t emit_tied(const EstOp &op, const uint32_t *lslots, uint64_t tie
         }
         return total;
     }
+    for (uint64_t m = tie; m; m &= m - 1) total += wv::bcast(rcnt, ctz64(m));
+    if (total <= 64u) {
+        // all members fit one per lane (a group that arrived together and was cut into many small batches, say): lane i
+        // takes the i-th member in table order, and one sorting network over the query indices does the merge
+        const uint32_t c = wv::lane_in(tie) ? rcnt : 0u;
+        const uint32_t off = wv::prefix_excl_u32(c);
+        const uint32_t l = lanes_less(off, ln, true, tw) - 1u;  // the last table lane whose batch starts at or before position ln
+        const uint32_t o = wv::shfl(off, l), sl = wv::shfl(rslot, l);
+        const uint32_t x = ln < total ? lslots[sl * bm + (ln - o)] : 0xFFFFFFFFu;  // (query indices stay below 2^31)
+        const uint32_t sorted = sort_lanes(x, pow2_at_least(total));
+        if (ln < total) out[(base + ln) & omask] = tkey | sorted;
+        return total;
+    }
     // rank every member among all of them
+    total = 0;
     for (uint64_t m = tie; m; m &= m - 1) {
         const uint32_t r = ctz64(m);
         const uint32_t cr = wv::bcast(rcnt, r), sl = wv::bcast(rslot, r);
@@ -275,23 +306,6 @@ EST_DEV uint32_t emit_tied(const EstOp &op, const uint32_t *lslots, uint64_t tie
     return total;
 }
 
-// Number of lanes whose value is below x (<= x with incl), for values that ascend with the lane: a binary search
-// over the lanes, the same for every lane's own x.  Only the first width lanes are searched (a power of two, the
-// same in every lane): no lane from there on may pass the test.
-EST_DEV uint32_t lanes_less(uint32_t v, uint32_t x, bool incl, uint32_t width = 64u) {
-    uint32_t pos = 0;
-    for (uint32_t step = width >> 1; step >= 1; step >>= 1) {
-        const uint32_t y = wv::shfl(v, pos + step - 1u);
-        if (incl ? y <= x : y < x) pos += step;
-    }
-    const uint32_t y = wv::shfl(v, width - 1u);  // (pos is width-1 only when the lanes before that one all pass)
-    if (pos == width - 1u && (incl ? y <= x : y < x)) pos = width;
-    return pos;
-}
-
-// The smallest power of two that is at least n (n from 1 to 64), at least 2
-EST_DEV uint32_t pow2_at_least(uint32_t n) { return n <= 2u ? 2u : 1u << (32u - (uint32_t)__builtin_clz(n - 1u)); }
-
 // The batches in the table lanes of E (ascending completion times, no two of them equal) written out in table
 // order in one sweep: off (the members of the lanes of E before mine, e.g. from emit_offsets) turns an output
 // position into a batch and a member.  Every member goes to out[base + its position + extra of its batch], where
@@ -313,7 +327,7 @@ EST_DEV void emit_many(const EstOp &op, const uint32_t *lslots, uint32_t total, 
 // have been placed already, each shifted by the members of the older batches that finish before it; here the
 // older batches are written into the gaps, those that complete together merged by query index.
 EST_DEV void weave_out(const EstOp &op, const uint32_t *lslots, uint64_t woven, uint64_t emitm, uint32_t ke, uint32_t rend,
-                       uint32_t rcnt, uint32_t rslot, uint64_t *out, uint32_t omask, uint32_t wr) {
+                       uint32_t rcnt, uint32_t rslot, uint64_t *out, uint32_t omask, uint32_t wr, uint32_t tw) {
     const uint32_t ln = wv::lane();
     const uint32_t bm = wv::uniform(op.b_max);
     uint32_t before = 0;
@@ -327,7 +341,7 @@ EST_DEV void weave_out(const EstOp &op, const uint32_t *lslots, uint64_t woven, 
             if (ln < cj) out[(pos + ln) & omask] = ((uint64_t)ej << 32) | lslots[sj * bm + ln];
             before += cj;
         } else {
-            before += emit_tied(op, lslots, tie, ej, rcnt, rslot, out, omask, pos);
+            before += emit_tied(op, lslots, tie, ej, rcnt, rslot, out, omask, pos, tw);
         }
         pm &= ~tie;
     }
@@ -366,7 +380,7 @@ EST_DEV void weave_all(const EstOp &op, const uint32_t *lslots, uint32_t *lscr, 
         if (ej < ke) shift += cj;
     }
     if (emit_me) out[(wr + orank + shift) & omask] = key;
-    weave_out(op, lslots, woven, emitm, ke, rend, rcnt, rslot, out, omask, wr);
+    weave_out(op, lslots, woven, emitm, ke, rend, rcnt, rslot, out, omask, wr, tw);
 }
 
 // Emit, in (completion time, query index) order, the batches whose replica-table lanes are in E
@@ -410,7 +424,7 @@ EST_DEV bool scan_emit(const EstOp &op, const uint32_t *lslots, uint64_t E, uint
             uint32_t total = 0;
             for (uint64_t m = tie; m; m &= m - 1) total += wv::bcast(rcnt, ctz64(m));
             if (total > space) return false;
-            emit_tied(op, lslots, tie, mv, rcnt, rslot, out, omask, wr);
+            emit_tied(op, lslots, tie, mv, rcnt, rslot, out, omask, wr, tw);
             wr += total;
             space -= total;
         }
