@@ -59,9 +59,18 @@ EST_DEV uint32_t opaque(uint32_t v) {
     return v;
 }
 
+// the value of the first lane, in a scalar register (for a value the compiler already knows to be the same in every
+// lane this costs nothing)
+EST_DEV uint32_t uniform(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+
+// The helpers below take operands that are the same in every lane and work on the scalar unit.  Their operands go
+// through uniform() first: where the compiler keeps such a value in a vector register (it does when it cannot
+// prove the value uniform), the scalar-register operand of the instruction text would otherwise not assemble.
+
 // v (the same in every lane), hidden from the optimiser and kept in a scalar register: a test of the result stays a
 // scalar compare and branch of its own instead of being merged with its neighbours into lane-mask arithmetic
 EST_DEV uint32_t opaque_uniform(uint32_t v) {
+    v = uniform(v);
     asm volatile("" : "+s"(v));
     return v;
 }
@@ -70,23 +79,27 @@ EST_DEV uint32_t opaque_uniform(uint32_t v) {
 // integer in a scalar register (several tests combined with & and | then cost one branch, and no lane masks)
 EST_DEV uint32_t flag_ge(uint32_t a, uint32_t b) {
     uint32_t r;
+    a = uniform(a); b = uniform(b);
     asm("s_cmp_ge_u32 %1, %2\n\ts_cselect_b32 %0, 1, 0" : "=s"(r) : "s"(a), "s"(b) : "scc");
     return r;
 }
 EST_DEV uint32_t flag_lt(uint32_t a, uint32_t b) {
     uint32_t r;
+    a = uniform(a); b = uniform(b);
     asm("s_cmp_lt_u32 %1, %2\n\ts_cselect_b32 %0, 1, 0" : "=s"(r) : "s"(a), "s"(b) : "scc");
     return r;
 }
 // 1 when a != b and c >= d (d at least 1), else 0
 EST_DEV uint32_t flag_ne_and_ge(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
     uint32_t r;
+    a = uniform(a); b = uniform(b); c = uniform(c); d = uniform(d);
     asm("s_cmp_lg_u32 %1, %2\n\ts_cselect_b32 %0, %3, 0\n\ts_cmp_ge_u32 %0, %4\n\ts_cselect_b32 %0, 1, 0"
         : "=&s"(r) : "s"(a), "s"(b), "s"(c), "s"(d) : "scc");
     return r;
 }
 EST_DEV uint32_t flag_ne(uint32_t a, uint32_t b) {
     uint32_t r;
+    a = uniform(a); b = uniform(b);
     asm("s_cmp_lg_u32 %1, %2\n\ts_cselect_b32 %0, 1, 0" : "=s"(r) : "s"(a), "s"(b) : "scc");
     return r;
 }
@@ -96,12 +109,11 @@ EST_DEV uint32_t flag_ne(uint32_t a, uint32_t b) {
 extern "C" __device__ uint32_t est_llvm_writelane(uint32_t x, uint32_t l, uint32_t v) __asm("llvm.amdgcn.writelane");
 EST_DEV uint32_t set_lane(uint32_t v, uint32_t x, uint32_t l) { return est_llvm_writelane(x, l, v); }
 
-EST_DEV uint32_t uniform(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
-
 // min(t + d, 2^32 - 1) for operands that are the same in every lane, on the scalar unit (the compiler's own
 // saturating add exists on the vector unit only, with a trip there and back)
 EST_DEV uint32_t sat_add_uniform(uint32_t t, uint32_t d) {
     uint32_t r;
+    t = uniform(t); d = uniform(d);
     asm("s_add_u32 %0, %1, %2\n\ts_cselect_b32 %0, -1, %0" : "=s"(r) : "s"(t), "s"(d) : "scc");
     return r;
 }
