@@ -330,8 +330,8 @@ def main():
                                            "p99_selection": oth[:, 2].sum() / ticks},
                   "queries_clamped_at_horizon": clamped}
 
-    # CPU baseline: the oracle as it stands on a bounded seeded sample of the same workload, on this box's host
-    # cores: one thread, and fanned out over the threads the box gives (at most 16, the CPU share of a one-GPU machine)
+    # CPU baseline: the oracle as it stands on a bounded seeded sample of the same workload, on this machine's host
+    # cores: one thread, and fanned out over the host threads available (at most 16)
     n_sample = args.cpu_sample if args.cpu_sample >= 0 else {"W1": 16, "W2": 1024, "W3": 96, "W4": 8, "W5": 4}[args.workload]
     cpu = None
     if n_sample > 0:
