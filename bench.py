@@ -248,7 +248,7 @@ def main():
              "kernel": "est_sim_kernel", "avg_launch_ms": avg_s * 1e3, "algorithmic_bytes_per_launch": 8.0 * visits * per_launch,
              "limited_by": "vector and scalar instruction issue, not memory bandwidth (profiles/)"}
         prof = PROFILED.get((wl.name, min(args.chunk, wl.n_configs)))
-        if prof is not None and launches == passes:
+        if prof is not None and per_launch == min(args.chunk, wl.n_configs):  # (one launch per library call of that many candidates)
             if prof["csrc_sha16"] == csrc_sha16():
                 r["traffic"] = prof["traffic_bytes"]
                 for key, peak, unit in (("valu", VALU_PEAK_GINST_S, "G wave64 vector instructions/s"), ("salu", SALU_PEAK_GINST_S, "G scalar instructions/s")):
