@@ -100,8 +100,8 @@ def test_small_in_ring_matches_oracle(seed, monkeypatch):
     # refills of uneven length, with and without a filter
     monkeypatch.setenv("EST_SCAN_RING", "128")
     w = [workloads.random_case, workloads.backlog_case, workloads.grouped_case, workloads.provisioned_case][seed % 4](seed + 100)
-    if w.n_queries > 1500:
-        w = w.subset(n_queries=1500)
+    if w.n_queries > 900:
+        w = w.subset(n_queries=900)
     _compare(w)
 
 

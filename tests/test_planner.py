@@ -194,7 +194,7 @@ def _same_as_oracle(est, w, rmax):
     assert got["cost_uusd_hr"] == po.cost(ref) and got["p99_us"] == _p99(w, ref)
 
 
-@pytest.mark.parametrize("seed", [1, 2, 6])
+@pytest.mark.parametrize("seed", [2, 6])  # (the GPU test runs more seeds; under the emulation each takes tens of seconds)
 def test_library_planner_takes_the_same_decisions_emulated(seed):
     w = workloads.planner_case(seed, n=150)
     _same_as_oracle(emu_lib.make(w), w, 6)
