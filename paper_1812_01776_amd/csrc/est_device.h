@@ -1766,16 +1766,25 @@ EST_DEV void slot_loop(const EstSimArgs &a, uint32_t wave_slot, uint64_t *lds) {
 
 // Nearest visited ancestors of every stage (and of the virtual sink, index S) for one query:
 // bit p = the completion of stage p feeds the stage directly, bit EST_TRACE_BIT = the arrival does.
+// A member that is an ancestor of another member is left out: times never decrease along a path of the
+// pipeline (a skipped stage passes its ready time on), so its completion is no later than the other's and never
+// decides the maximum (Section 4.1, conditional control flow: a query that takes one branch of a fork and skips
+// the other is fed by that branch alone, not also by the stage before the fork).
 EST_DEV void nearest_sets(const EstDag &d, uint32_t mask, uint64_t *nv) {
+    uint64_t anc[EST_MAX_STAGES + 1];  // every ancestor of the stage, and the arrival
     for (uint32_t c = 0; c <= d.S; ++c) {
-        uint64_t s = 0;
+        uint64_t s = 0, a = 1ull << EST_TRACE_BIT;
         const uint32_t b = d.parent_off[c], e = d.parent_off[c + 1];
         if (b == e) s = 1ull << EST_TRACE_BIT;
         for (uint32_t i = b; i < e; ++i) {
             const uint32_t p = d.parent_idx[i];
             s |= ((mask >> p) & 1u) ? (1ull << p) : nv[p];
+            a |= (1ull << p) | anc[p];
         }
-        nv[c] = s;
+        uint64_t dominated = 0;
+        for (uint64_t t = s & ~(1ull << EST_TRACE_BIT); t; t &= t - 1) dominated |= anc[__builtin_ctzll(t)];
+        nv[c] = s & ~dominated;
+        anc[c] = a;
     }
 }
 
