@@ -264,6 +264,25 @@ typedef struct {
 int estimator_tuner_handoff(estimator_t *h, const est_trace_t *trace, const est_stage_cfg_t *config,
                             uint32_t service_time_us, est_handoff_t *out);
 
+/*
+ * Latency tables for models whose latency depends on the input (Section 8, the second limitation: measure the
+ * latency distribution over the sample queries while profiling and give the Estimator its tail as the processing
+ * time, which yields feasible but costlier plans).  samples_us is [n_entries][n_samples], HOST memory: n_samples
+ * measured latencies (1..EST_MAX_PROFILE_SAMPLES) for each entry of est_profiles_t.lat_us, in that array's order
+ * ([S][H][Bmax] flattened).  lat_us_out [n_entries], HOST memory, receives per entry
+ *   EST_TAIL_PERCENTILE: the nearest-rank percentile: the k-th smallest sample, k = ceil(param x n_samples / 10000),
+ *                        param in hundredths of a percent, 1..10000 (9900 = the 99th percentile);
+ *   EST_TAIL_SIGMA:      the smallest integer >= mean + (param / 1000) x sigma, sigma the population standard
+ *                        deviation of the samples, param 0..10000 (3000 = three standard deviations).
+ * Exact integer arithmetic, no handle, no device work.  Errors: EST_EINVAL for NULLs, n_samples or param out of
+ * range, an unknown mode, or a result that is 0 or does not fit 32 bits; EST_ENOMEM.  lat_us_out is untouched on error.
+ */
+#define EST_TAIL_PERCENTILE 0
+#define EST_TAIL_SIGMA 1
+#define EST_MAX_PROFILE_SAMPLES 65536
+int estimator_profile_tail(const uint32_t *samples_us, uint64_t n_entries, uint32_t n_samples, uint32_t mode,
+                           uint32_t param, uint32_t *lat_us_out);
+
 /* Fill *out with the timing of the last successful run on this handle. */
 int estimator_last_stats(const estimator_t *h, est_stats_t *out);
 

@@ -425,3 +425,54 @@ extern "C" int estimator_tuner_handoff(estimator_t *h, const est_trace_t *trace,
     return EST_OK;
 }
 
+
+// ---- latency tables for models whose latency depends on the input (Section 8, second limitation): the profile
+//      entry is the tail of the latencies measured over the sample queries.  Host code, exact integer arithmetic.
+extern "C" int estimator_profile_tail(const uint32_t *samples_us, uint64_t n_entries, uint32_t n_samples, uint32_t mode,
+                                      uint32_t param, uint32_t *lat_us_out) {
+    if (n_entries == 0) return EST_OK;
+    if (!samples_us || !lat_us_out) return EST_EINVAL;
+    if (n_samples < 1 || n_samples > EST_MAX_PROFILE_SAMPLES) return EST_EINVAL;
+    if (mode != EST_TAIL_PERCENTILE && mode != EST_TAIL_SIGMA) return EST_EINVAL;
+    if (mode == EST_TAIL_PERCENTILE && (param < 1 || param > 10000)) return EST_EINVAL;
+    if (mode == EST_TAIL_SIGMA && param > 10000) return EST_EINVAL;
+    typedef unsigned __int128 u128;
+    std::vector<uint32_t> res, v;
+    try {
+        res.resize(n_entries);
+        v.resize(n_samples);
+    } catch (const std::bad_alloc &) {
+        return EST_ENOMEM;
+    }
+    const uint64_t n = n_samples;
+    for (uint64_t e = 0; e < n_entries; ++e) {
+        const uint32_t *x = samples_us + e * n;
+        if (mode == EST_TAIL_PERCENTILE) {
+            // nearest rank: the k-th smallest, k = ceil(param x n / 10000)
+            const uint64_t k = ((uint64_t)param * n + 9999) / 10000;
+            std::copy(x, x + n, v.begin());
+            std::nth_element(v.begin(), v.begin() + (k - 1), v.end());
+            res[e] = v[k - 1];
+        } else {
+            // the smallest integer t with t >= mean + (param / 1000) sigma, sigma^2 = (n S2 - S1^2) / n^2:
+            //   n t - S1 >= (param / 1000) sqrt(D), D = n S2 - S1^2   <=>   (1000 (n t - S1))^2 >= param^2 D  (left side >= 0)
+            u128 s1 = 0, s2 = 0;
+            for (uint64_t i = 0; i < n; ++i) {
+                s1 += x[i];
+                s2 += (u128)x[i] * x[i];
+            }
+            const u128 D = (u128)n * s2 - s1 * s1, rhs = (u128)param * param * D;
+            uint64_t lo = (uint64_t)((s1 + n - 1) / n), hi = 1ull << 36;  // t >= ceil(mean); sigma <= half the range, so mean + 10 sigma < 2^36
+            while (lo < hi) {  // (the left side grows with t)
+                const uint64_t t = lo + (hi - lo) / 2;
+                const u128 a = ((u128)n * t - s1) * 1000u;
+                if (a * a >= rhs) hi = t; else lo = t + 1;
+            }
+            if (lo > 0xFFFFFFFFull) return EST_EINVAL;  // does not fit a latency
+            res[e] = (uint32_t)lo;
+        }
+        if (res[e] == 0) return EST_EINVAL;  // a latency table has no zero entries
+    }
+    std::copy(res.begin(), res.end(), lat_us_out);
+    return EST_OK;
+}

@@ -21,7 +21,7 @@ CFG_DTYPE = np.dtype([("hw", "u1"), ("batch", "u1"), ("replicas", "<u2")])
 SYMBOLS = ["estimator_create", "estimator_run", "estimator_run_dev", "estimator_run_latencies",
            "estimator_run_latencies_dev", "estimator_workspace_bytes", "estimator_last_stats",
            "estimator_last_error", "estimator_destroy", "estimator_plan", "estimator_tuner_handoff",
-           "estimator_run_shared_dev", "estimator_run_static_dev"]
+           "estimator_run_shared_dev", "estimator_run_static_dev", "estimator_profile_tail"]
 
 
 class EstimatorError(RuntimeError):
@@ -96,7 +96,23 @@ def load_library(path=LIB_PATH):
     lib.estimator_tuner_handoff.restype = ctypes.c_int
     lib.estimator_run_shared_dev.restype = ctypes.c_int
     lib.estimator_run_static_dev.restype = ctypes.c_int
+    lib.estimator_profile_tail.restype = ctypes.c_int
     return lib
+
+
+EST_TAIL_PERCENTILE, EST_TAIL_SIGMA = 0, 1
+
+
+def profile_tail(samples_us, mode, param, lib=None):
+    """estimator_profile_tail: samples_us [..., n_samples] uint32 -> the table of tails, shape samples_us.shape[:-1]."""
+    lib = lib or load_library()
+    x = np.ascontiguousarray(samples_us, dtype=np.uint32)
+    out = np.zeros(x.shape[:-1], np.uint32)
+    rc = lib.estimator_profile_tail(_ptr(x), ctypes.c_uint64(out.size), ctypes.c_uint32(x.shape[-1]), ctypes.c_uint32(mode),
+                                    ctypes.c_uint32(param), _ptr(out))
+    if rc != EST_OK:
+        raise EstimatorError(rc, "estimator_profile_tail")
+    return out
 
 
 def pack_configs(cfg_hw, cfg_batch, cfg_replicas):
