@@ -354,7 +354,14 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
             if (h->ws) estbe::dfree(h->ws);
             h->ws = nullptr;
             h->ws_bytes = 0;
+            // (a little more than this call needs, when there is room: a later call with some more candidates, whose
+            // result staging is a few bytes each, then finds the cached scratch large enough)
+            if (budget == want) budget = std::min<uint64_t>(want + std::min<uint64_t>(64ull << 20, want / 64 + (1ull << 20)), std::max<uint64_t>(want, avail / 100 * 92));
             h->ws = estbe::dmalloc(budget);
+            if (!h->ws && budget > want) {
+                budget = want;
+                h->ws = estbe::dmalloc(budget);
+            }
             for (int shrink = 0; !h->ws && shrink < 3 && budget < want; ++shrink) {  // the free memory was less than reported: fewer slots
                 budget = budget / 8 * 7;
                 h->ws = estbe::dmalloc(budget);
