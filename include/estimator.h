@@ -98,7 +98,7 @@ typedef struct {
     uint64_t workspace_bytes; /* device scratch used                                                  */
     float capture_ms;         /* estimator_run_shared_dev: the launch that simulates the bases (part of sim_ms) */
     float ops_run_fraction;   /* estimator_run_shared_dev: operations run / (candidates x operations); else 0    */
-    uint32_t waves_per_candidate; /* 1, or 4 when the call had so few candidates that each was given a workgroup   */
+    uint32_t waves_per_candidate; /* 1, or 2 or 4 when the call had so few candidates that each was given a workgroup */
     uint32_t reserved;
 } est_stats_t;
 

@@ -23,11 +23,11 @@ int launch_cfg(const EstCfgArgs &a, void *stream);
 int launch_prep1(const EstPrepArgs &a, void *stream);
 int launch_prep2(const EstPrepArgs &a, void *stream);
 int launch_sim(const EstSimArgs &a, void *stream);
-int launch_sim_mw(const EstSimArgs &a, void *stream);  // one workgroup of EST_MW_WAVES wavefronts per scratch slot (a.n_slots workgroups)
+int launch_sim_mw(const EstSimArgs &a, uint32_t waves, void *stream);  // one workgroup of `waves` (2 or EST_MW_WAVES) wavefronts per scratch slot (a.n_slots workgroups)
 int launch_envelope(const EstEnvArgs &a, void *stream);
-uint32_t max_resident_waves(uint32_t lds_bytes_per_wave);
+uint32_t max_resident_waves(uint32_t lds_bytes_per_wave);  // wavefronts of the simulation kernel the device holds at once
 uint32_t waves_per_simd(uint32_t lds_bytes_per_wave);      // which build of the simulation kernel runs at this LDS need: 4, 5 or 6 wavefronts per SIMD
-uint32_t max_resident_groups(uint32_t lds_bytes_per_wave);  // workgroups of launch_sim_mw the device holds at once  // wavefronts of the simulation kernel the device holds at once
+uint32_t max_resident_groups(uint32_t lds_bytes_per_wave, uint32_t waves);  // workgroups of launch_sim_mw the device holds at once
 
 void *stream_create();            // a second stream at the default priority; nullptr on failure
 void stream_destroy(void *stream);

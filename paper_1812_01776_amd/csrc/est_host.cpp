@@ -381,14 +381,24 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     uint64_t n_slots = std::min<uint64_t>((ws_bytes - fixed - 8 * 256) / per_cfg, n_cfg);
     n_slots = std::min<uint64_t>(n_slots, std::max<uint32_t>(estbe::max_resident_waves(po.lds_bytes), 1));
     // A call with so few candidates that most of the device would stay empty gives every candidate a workgroup
-    // of EST_MW_WAVES wavefronts instead of one wavefront (EST_WAVES_PER_CANDIDATE = 1 or 4 overrides the choice):
-    // up to one and a half times the workgroups the device holds at once (measured: with 1,024 resident workgroups,
-    // 1,024 candidates of a ten-stage pipeline take 0.39 s against 0.87 s, 1,536 take 0.77 against 1.16 s, and from
-    // 2,048 on one wavefront each is faster).
-    bool several = n > 0 && po.plan.n_ops >= 2 && n_cfg <= n_slots && n_cfg * 2 <= (uint64_t)estbe::max_resident_groups(po.lds_bytes) * 3;
-    if (const char *e = getenv("EST_WAVES_PER_CANDIDATE")) several = n > 0 && atoi(e) == EST_MW_WAVES;
-    if (getenv("EST_DEBUG_TICKS") && !no_alloc) several = false;  // (the step counters are per wavefront)
-    if (several) n_slots = std::min<uint64_t>(n_slots, std::max<uint32_t>(estbe::max_resident_groups(po.lds_bytes), 1));
+    // of wavefronts instead of one wavefront (EST_WAVES_PER_CANDIDATE = 1, 2 or 4 overrides the choice): four up to
+    // one and a half times the workgroups of four the device holds at once, two up to the number of workgroups of
+    // two it holds.  Measured on a ten-stage pipeline, 10^6 queries, 1,024 resident workgroups of four and 2,048 of
+    // two, kernel seconds with 1 / 2 / 4 wavefronts per candidate: 1,024 candidates 0.87 / - / 0.39; 1,536: 1.15 /
+    // 0.91 / 0.80; 2,048: 1.06 / 0.80 / 0.88; 3,072: 1.26 / 1.32 / 1.24; 4,096: 1.30 / 1.50 / 1.54.
+    uint32_t nw = 1;  // wavefronts per candidate
+    if (n > 0 && po.plan.n_ops >= 2 && n_cfg <= n_slots) {
+        if (n_cfg * 2 <= (uint64_t)estbe::max_resident_groups(po.lds_bytes, EST_MW_WAVES) * 3) nw = EST_MW_WAVES;
+        else if (n_cfg <= estbe::max_resident_groups(po.lds_bytes, 2)) nw = 2;
+    }
+    if (const char *e = getenv("EST_WAVES_PER_CANDIDATE")) nw = n > 0 && (atoi(e) == 2 || atoi(e) == EST_MW_WAVES) ? (uint32_t)atoi(e) : 1;
+    if (getenv("EST_DEBUG_TICKS") && !no_alloc) nw = 1;  // (the step counters are per wavefront)
+    const bool several = nw > 1;
+    if (several) {
+        n_slots = std::min<uint64_t>(n_slots, std::max<uint32_t>(estbe::max_resident_groups(po.lds_bytes, nw), 1));
+        // (build_plan cut the operations into EST_MW_WAVES runs; a smaller workgroup takes neighbouring runs together)
+        for (uint32_t i = 0; i < po.plan.n_ops; ++i) po.plan.ops[i].owner = po.plan.ops[i].owner * nw / EST_MW_WAVES;
+    }
     uint64_t at = fixed;
     auto area = [&](uint64_t bytes_per_cfg) {
         uint64_t a0 = at;
@@ -474,7 +484,7 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
         sa.dbg_ticks = dbg_ticks;
         sa.p99 = s_p99; sa.miss = s_miss; sa.cost = s_cost;
         if (mode == MODE_P99 || n > 0)
-            if (several ? estbe::launch_sim_mw(sa, stream) : estbe::launch_sim(sa, stream)) return dev_fail(h, "simulation kernel");
+            if (several ? estbe::launch_sim_mw(sa, nw, stream) : estbe::launch_sim(sa, stream)) return dev_fail(h, "simulation kernel");
     }
     estbe::event_record(e1, stream);
     EstStatus st2_local;
@@ -499,7 +509,7 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     memset(&ss, 0, sizeof ss);
     ss.n_launches = 1;
     ss.n_slots = (uint32_t)n_slots;
-    ss.waves_per_candidate = several ? EST_MW_WAVES : 1;
+    ss.waves_per_candidate = nw;
     ss.sim_ms = estbe::event_ms(e0, e1);
     ss.prep_ms = estbe::event_ms(ev_p0, ev_p1) + estbe::event_ms(ev_p2, ev_p3);
     for (uint32_t s = 0; s < S; ++s) ss.stage_visits += st.n_visit[s];

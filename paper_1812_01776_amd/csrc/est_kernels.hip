@@ -33,14 +33,14 @@ void est_sim_kernel(EstSimArgs a) {
     if (slot < a.n_slots) estdev::slot_loop<DIAG, MEMO>(a, slot, lds + (size_t)wave * (a.lds_bytes / 8));
 }
 
-// Several wavefronts per candidate: a workgroup of EST_MW_WAVES wavefronts owns one scratch slot and takes
+// Several wavefronts per candidate: a workgroup of 2 to EST_MW_WAVES wavefronts (the launch's block size) owns one scratch slot and takes
 // candidates from the work counter; the candidate's operations are dealt out to the wavefronts (EstOp::owner),
 // which run them as a pipeline through the rings.  A wavefront that finds nothing to do waits a little and looks
 // again; every wait is bounded (a stuck candidate sets the error flag and every wavefront leaves).
 constexpr uint32_t MW_IDLE_LIMIT = 1u << 24;
 __global__ __launch_bounds__(64 * EST_MW_WAVES) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void est_sim_mw_kernel(EstSimArgs a) {
-    extern __shared__ uint64_t lds[];  // EST_MW_WAVES x a.lds_bytes
+    extern __shared__ uint64_t lds[];  // wavefronts of the workgroup x a.lds_bytes
     __shared__ uint32_t next_t;
     const uint32_t wave = threadIdx.x >> 6;
     const uint32_t slot = blockIdx.x;
@@ -184,16 +184,20 @@ int launch_envelope(const EstEnvArgs &a, void *stream) {
     return check(hipGetLastError(), "est_envelope_kernel");
 }
 uint32_t waves_per_simd(uint32_t lds_bytes_per_wave) { return (uint32_t)waves_fit(lds_bytes_per_wave); }
-int launch_sim_mw(const EstSimArgs &a, void *stream) {
-    const size_t lds = (size_t)a.lds_bytes * EST_MW_WAVES;
-    est_sim_mw_kernel<<<dim3(a.n_slots), dim3(64 * EST_MW_WAVES), lds, (hipStream_t)stream>>>(a);
+int launch_sim_mw(const EstSimArgs &a, uint32_t waves, void *stream) {
+    if (waves < 2 || waves > EST_MW_WAVES) {
+        g_err = "est_sim_mw_kernel: a workgroup has 2 to 4 wavefronts";
+        return 1;
+    }
+    const size_t lds = (size_t)a.lds_bytes * waves;
+    est_sim_mw_kernel<<<dim3(a.n_slots), dim3(64 * waves), lds, (hipStream_t)stream>>>(a);
     return check(hipGetLastError(), "est_sim_mw_kernel");
 }
-uint32_t max_resident_groups(uint32_t lds_bytes_per_wave) {
+uint32_t max_resident_groups(uint32_t lds_bytes_per_wave, uint32_t waves) {
     int dev = 0, cus = 0, blocks = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_mw_kernel, 64 * EST_MW_WAVES, (size_t)lds_bytes_per_wave * EST_MW_WAVES) != hipSuccess ||
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_mw_kernel, 64 * (int)waves, (size_t)lds_bytes_per_wave * waves) != hipSuccess ||
         blocks < 1)
         blocks = 1;
     return (uint32_t)cus * (uint32_t)blocks;

@@ -140,7 +140,7 @@ int launch_sim(const EstSimArgs &a, void *) {
 }
 // Several wavefronts per candidate: the wavefronts of a workgroup take turns, one pass over their own operations
 // each, until all are done (a full turn without progress is a stuck candidate).
-int launch_sim_mw(const EstSimArgs &a, void *) {
+int launch_sim_mw(const EstSimArgs &a, uint32_t waves, void *) {
     static uint64_t lds[EST_MW_WAVES][(64 * 1024) / 8];
     if (a.lds_bytes > sizeof lds[0]) abort();
     for (uint32_t t = 0; t < a.n_cfg; ++t) {
@@ -149,9 +149,9 @@ int launch_sim_mw(const EstSimArgs &a, void *) {
         if (a.n > 0) {
             emu::run_wave([&] { estdev::mw_init(a, t, slot); });
             uint32_t done = 0;
-            while (done != (1u << EST_MW_WAVES) - 1u) {
+            while (done != (1u << waves) - 1u) {
                 bool progress = false;
-                for (uint32_t wv_ = 0; wv_ < EST_MW_WAVES; ++wv_) {
+                for (uint32_t wv_ = 0; wv_ < waves; ++wv_) {
                     if ((done >> wv_) & 1u) continue;
                     uint32_t r = 0;
                     emu::run_wave([&] { uint32_t x = estdev::mw_pass(a, t, slot, lds[wv_], wv_); if (wv::lane() == 0) r = x; });
@@ -168,7 +168,7 @@ int launch_sim_mw(const EstSimArgs &a, void *) {
     }
     return 0;
 }
-uint32_t max_resident_groups(uint32_t) { return 2; }
+uint32_t max_resident_groups(uint32_t, uint32_t) { return 2; }
 uint32_t max_resident_waves(uint32_t) { return 3; }
 uint32_t waves_per_simd(uint32_t) { return 4; }
 

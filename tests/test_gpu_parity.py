@@ -15,10 +15,10 @@ pytestmark = pytest.mark.gpu
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
 
-@pytest.fixture(params=["1", "4"], ids=["wave_per_candidate", "workgroup_per_candidate"])
+@pytest.fixture(params=["1", "4", "2"], ids=["wave_per_candidate", "workgroup_per_candidate", "two_wavefronts_per_candidate"])
 def waves(request, monkeypatch):
-    """Both ways a candidate is run: by one wavefront, or (what calls with few candidates get by default) by a
-    workgroup of four wavefronts that share its operations as a pipeline."""
+    """The ways a candidate is run: by one wavefront, or (what calls with few candidates get by default) by a
+    workgroup of four, or of two, wavefronts that share its operations as a pipeline."""
     monkeypatch.setenv("EST_WAVES_PER_CANDIDATE", request.param)
     return int(request.param)
 

@@ -82,16 +82,17 @@ def test_provisioned_small_batches_with_tied_completions_match_oracle(seed):
     _compare(workloads.provisioned_case(seed, n=1500))
 
 
+@pytest.mark.parametrize("nw", [4, 2])
 @pytest.mark.parametrize("seed", range(12))
-def test_several_wavefronts_per_candidate_match_oracle(seed, monkeypatch):
-    # the candidate's operations dealt out to four wavefronts that run as a pipeline through the rings
-    monkeypatch.setenv("EST_WAVES_PER_CANDIDATE", "4")
+def test_several_wavefronts_per_candidate_match_oracle(seed, nw, monkeypatch):
+    # the candidate's operations dealt out to four (or two) wavefronts that run as a pipeline through the rings
+    monkeypatch.setenv("EST_WAVES_PER_CANDIDATE", str(nw))
     w = [workloads.random_case, workloads.backlog_case, workloads.grouped_case, workloads.provisioned_case][seed % 4](seed)
     if w.n_queries > 1500:
         w = w.subset(n_queries=1500)
     est = emu_lib.make(w)
     _compare(w, est=est)
-    assert est.stats()["waves_per_candidate"] == 4
+    assert est.stats()["waves_per_candidate"] == nw
 
 
 @pytest.mark.parametrize("seed", range(12))
