@@ -380,17 +380,16 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     // would only wait
     uint64_t n_slots = std::min<uint64_t>((ws_bytes - fixed - 8 * 256) / per_cfg, n_cfg);
     n_slots = std::min<uint64_t>(n_slots, std::max<uint32_t>(estbe::max_resident_waves(po.lds_bytes), 1));
-    // A call with so few candidates that most of the device would stay empty gives every candidate a workgroup
-    // of wavefronts instead of one wavefront (EST_WAVES_PER_CANDIDATE = 1, 2 or 4 overrides the choice): four up to
-    // one and a half times the workgroups of four the device holds at once, two up to the number of workgroups of
-    // two it holds.  Measured on a ten-stage pipeline, 10^6 queries, 1,024 resident workgroups of four and 2,048 of
-    // two, kernel seconds with 1 / 2 / 4 wavefronts per candidate: 1,024 candidates 0.87 / - / 0.39; 1,536: 1.15 /
-    // 0.91 / 0.80; 2,048: 1.06 / 0.80 / 0.88; 3,072: 1.26 / 1.32 / 1.24; 4,096: 1.30 / 1.50 / 1.54.
+    // A call with so few candidates that most of the device would stay empty gives every candidate a workgroup of
+    // EST_MW_WAVES wavefronts instead of one wavefront, up to one and a half times the workgroups the device holds at
+    // once (EST_WAVES_PER_CANDIDATE = 1, 2 or 4 overrides the choice).  Measured on a ten-stage pipeline, 10^6 queries,
+    // 1,536 resident workgroups of four, kernel seconds with 1 / 2 / 4 wavefronts per candidate: 1,024 candidates
+    // 0.87 / 0.65 / 0.41; 1,536: 1.17 / 0.91 / 0.65; 2,304: 1.28 / 1.06 / 0.92; 3,072: 1.27 / 1.18 / 1.04; on a
+    // five-stage pipeline four stop paying at 2,048 candidates (104 / 104 / 102 ms; 3,072: 117 / 127 / 136).
+    // Workgroups of two are never better than both alternatives by much, so they are not chosen automatically.
     uint32_t nw = 1;  // wavefronts per candidate
-    if (n > 0 && po.plan.n_ops >= 2 && n_cfg <= n_slots) {
-        if (n_cfg * 2 <= (uint64_t)estbe::max_resident_groups(po.lds_bytes, EST_MW_WAVES) * 3) nw = EST_MW_WAVES;
-        else if (n_cfg <= estbe::max_resident_groups(po.lds_bytes, 2)) nw = 2;
-    }
+    if (n > 0 && po.plan.n_ops >= 2 && n_cfg <= n_slots && n_cfg * 2 <= (uint64_t)estbe::max_resident_groups(po.lds_bytes, EST_MW_WAVES) * 3)
+        nw = EST_MW_WAVES;
     if (const char *e = getenv("EST_WAVES_PER_CANDIDATE")) nw = n > 0 && (atoi(e) == 2 || atoi(e) == EST_MW_WAVES) ? (uint32_t)atoi(e) : 1;
     if (getenv("EST_DEBUG_TICKS") && !no_alloc) nw = 1;  // (the step counters are per wavefront)
     const bool several = nw > 1;

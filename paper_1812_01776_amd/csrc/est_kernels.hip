@@ -38,7 +38,8 @@ void est_sim_kernel(EstSimArgs a) {
 // which run them as a pipeline through the rings.  A wavefront that finds nothing to do waits a little and looks
 // again; every wait is bounded (a stuck candidate sets the error flag and every wavefront leaves).
 constexpr uint32_t MW_IDLE_LIMIT = 1u << 24;
-__global__ __launch_bounds__(64 * EST_MW_WAVES) __attribute__((amdgpu_waves_per_eu(4, 4)))
+template <int WAVES_PER_SIMD>
+__global__ __launch_bounds__(64 * EST_MW_WAVES) __attribute__((amdgpu_waves_per_eu(WAVES_PER_SIMD, WAVES_PER_SIMD)))
 void est_sim_mw_kernel(EstSimArgs a) {
     extern __shared__ uint64_t lds[];  // wavefronts of the workgroup x a.lds_bytes
     __shared__ uint32_t next_t;
@@ -190,15 +191,20 @@ int launch_sim_mw(const EstSimArgs &a, uint32_t waves, void *stream) {
         return 1;
     }
     const size_t lds = (size_t)a.lds_bytes * waves;
-    est_sim_mw_kernel<<<dim3(a.n_slots), dim3(64 * waves), lds, (hipStream_t)stream>>>(a);
+    if (waves_fit(a.lds_bytes) == 6)  // (the builds for four and for six wavefronts per SIMD, as for est_sim_kernel)
+        est_sim_mw_kernel<6><<<dim3(a.n_slots), dim3(64 * waves), lds, (hipStream_t)stream>>>(a);
+    else
+        est_sim_mw_kernel<4><<<dim3(a.n_slots), dim3(64 * waves), lds, (hipStream_t)stream>>>(a);
     return check(hipGetLastError(), "est_sim_mw_kernel");
 }
 uint32_t max_resident_groups(uint32_t lds_bytes_per_wave, uint32_t waves) {
     int dev = 0, cus = 0, blocks = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_mw_kernel, 64 * (int)waves, (size_t)lds_bytes_per_wave * waves) != hipSuccess ||
-        blocks < 1)
+    const hipError_t e = waves_fit(lds_bytes_per_wave) == 6
+                             ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_mw_kernel<6>, 64 * (int)waves, (size_t)lds_bytes_per_wave * waves)
+                             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, est_sim_mw_kernel<4>, 64 * (int)waves, (size_t)lds_bytes_per_wave * waves);
+    if (e != hipSuccess || blocks < 1)
         blocks = 1;
     return (uint32_t)cus * (uint32_t)blocks;
 }
