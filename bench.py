@@ -39,7 +39,7 @@ def csrc_sha16():
     d = os.path.join(ROOT, "paper_1812_01776_amd", "csrc")
     h = hashlib.sha256()
     for f in sorted(os.listdir(d)):
-        if f.endswith((".h", ".hip")):  # what the kernels are compiled from (the host sources are not)
+        if f.endswith((".h", ".hip")) or f == "est_host.cpp":  # what the kernels are compiled from, and the host code that lays out their operations and streams
             h.update(f.encode()); h.update(open(os.path.join(d, f), "rb").read())
     return h.hexdigest()[:16]
 

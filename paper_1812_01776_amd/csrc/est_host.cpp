@@ -65,7 +65,7 @@ struct PlanOut {
 // queries of the query's nearest visited ancestors.  Those are the streams the stage's input has to
 // be merged from.  A stage fed by exactly one stream, every element of which visits the stage, reads
 // that stream directly.
-int build_plan(estimator *h, const EstStatus &st, uint64_t n, PlanOut &po) {
+int build_plan(estimator *h, const EstStatus &st, uint64_t n, PlanOut &po, bool small_rings = false) {
     const uint32_t S = h->dag.S;
     EstPlan &P = po.plan;
     memset(&P, 0, sizeof P);
@@ -77,7 +77,15 @@ int build_plan(estimator *h, const EstStatus &st, uint64_t n, PlanOut &po) {
     for (uint32_t s = 0; s < S; ++s) max_rb = std::max(max_rb, st.r_max[s] * st.b_max[s]);
     // A bounded ring must take a whole group of batches that complete together (<= R*B members)
     // while its consumer still holds back a look-ahead window, and a merge wants 64 x sources free.
-    const uint64_t cap_bounded = pow2ceil(std::max<uint64_t>(1024, (uint64_t)max_rb + 64 * EST_KMAX + 65));
+    // Beyond that need, longer rings let an operation run longer before it has to hand over to its neighbour:
+    // 8,192 elements (64 KB) instead of the 1,024 the need alone gives take 4 % off a sweep of the ten-stage
+    // pipeline (11.0 -> 10.5 s; 32,768 and more: 10.5 s).  A run inside a fixed scratch keeps the short ones (more
+    // candidates in flight matter more there).  EST_RING_ELEMS sets another floor (tests use a small one, so that
+    // short traces wrap the rings).
+    uint64_t ring_floor = small_rings ? 1024 : 8192;
+    if (const char *e = getenv("EST_RING_ELEMS"))
+        if (atol(e) >= 64 && atol(e) <= (1l << 24)) ring_floor = (uint64_t)atol(e);
+    const uint64_t cap_bounded = pow2ceil(std::max<uint64_t>(ring_floor, (uint64_t)max_rb + 64 * EST_KMAX + 65));
 
     std::vector<int32_t> out_ring(S, -1), in_ring(S, -1);
     struct Src { uint32_t n; int32_t ring_src[EST_KMAX]; };  // ring_src: stage index or EST_TRACE_BIT
@@ -315,7 +323,7 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     po.sz = Sizes();
     po.n_acc = 0;
     if (n > 0) {
-        int rc = build_plan(h, st, n, po);
+        int rc = build_plan(h, st, n, po, no_alloc);
         if (rc != EST_OK) return rc;
     } else {
         memset(&po.plan, 0, sizeof po.plan);

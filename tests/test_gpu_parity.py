@@ -182,6 +182,7 @@ def test_w1_full():
     _compare(workloads.w1())
 
 
+@pytest.mark.production_rings
 def test_w2_full():
     _compare(workloads.w2())
 
@@ -235,6 +236,7 @@ def _check_rows(w, exp, p99, miss, cost, est, lat_rows):
         assert hashlib.sha256(lat[i].astype("<u4").tobytes()).hexdigest() == row["latency_sha256"], row["config"]
 
 
+@pytest.mark.production_rings
 def test_w3_full_sweep_sampled_against_oracle():
     """All 8,192 configurations x 100,000 queries in one call (the launch shape the benchmark uses);
     48 sampled configurations are compared with stored oracle results (P99, misses, cost, and every
@@ -275,6 +277,7 @@ def _run_sweep_dev(est, w, arr_t, msk_t, cfg_t, per_call):
     return np.concatenate(p99), np.concatenate(miss), np.concatenate(cost)
 
 
+@pytest.mark.production_rings
 def test_w4_full_sweep_sampled_against_oracle():
     """All 65,536 configurations x 1,000,000 queries, called the way the benchmark calls the library
     (device pointers, 32,768 candidates per call); the 64 sampled configurations (the 16 with the least
@@ -293,6 +296,7 @@ def test_w4_full_sweep_sampled_against_oracle():
     est.close()
 
 
+@pytest.mark.production_rings
 def test_w3_workgroup_per_candidate_long_trace(monkeypatch):
     """64 candidates of W3 at the full 100,000 queries, each run by a workgroup of four wavefronts (fork, three
     branches, join): every per-query latency, P99, misses and cost against the live oracle."""
@@ -304,6 +308,7 @@ def test_w3_workgroup_per_candidate_long_trace(monkeypatch):
     est.close()
 
 
+@pytest.mark.production_rings
 def test_w4_pipeline_provisioned_candidates_full_trace():
     """W4's pipeline and full trace with 16 candidates provisioned around the SLO boundary (from slightly
     overloaded to comfortably feasible: the regime a planner's search works in): P99, misses, cost and
@@ -320,6 +325,7 @@ def test_w4_pipeline_provisioned_candidates_full_trace():
     est.close()
 
 
+@pytest.mark.production_rings
 def test_w5_sampled_configs_full_trace():
     """64 sampled configurations of the largest sweep (least head-room, most, random) at its full trace
     length (2,000,000 queries): P99, misses, cost and every per-query latency (SHA-256) against stored

@@ -135,6 +135,7 @@ def test_shared_run_on_the_ten_stage_pipeline():
 
 
 @pytest.mark.gpu
+@pytest.mark.production_rings
 def test_shared_run_at_full_trace_length_sampled():
     # W4's trace at its full 1,000,000 queries; 2,048 candidates of the grid, cut along its most downstream
     # swept stage (1,024 bases, two candidates each, streams of full length); two sampled candidates against the oracle
