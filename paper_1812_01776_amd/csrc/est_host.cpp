@@ -80,7 +80,7 @@ int build_plan(estimator *h, const EstStatus &st, uint64_t n, PlanOut &po, bool 
     // Beyond that need, longer rings let an operation run longer before it has to hand over to its neighbour:
     // 8,192 elements (64 KB) instead of the 1,024 the need alone gives take 4 % off a sweep of the ten-stage
     // pipeline (11.0 -> 10.5 s; 32,768 and more: 10.5 s).  A run inside a fixed scratch keeps the short ones (more
-    // candidates in flight matter more there).  EST_RING_ELEMS sets another floor (tests use a small one, so that
+    // candidates in flight matter more there), and so does a call that gives each candidate several wavefronts.  EST_RING_ELEMS sets another floor (tests use a small one, so that
     // short traces wrap the rings).
     uint64_t ring_floor = small_rings ? 1024 : 8192;
     if (const char *e = getenv("EST_RING_ELEMS"))
@@ -323,7 +323,15 @@ int run_core(estimator *h, uint64_t n, const uint32_t *d_arrival, const uint32_t
     po.sz = Sizes();
     po.n_acc = 0;
     if (n > 0) {
-        int rc = build_plan(h, st, n, po, no_alloc);
+        // Calls whose candidates will get several wavefronts each (below) keep the short rings: there the operations of
+        // a candidate run side by side, and a consumer starts when its producer first hands over, so long rings delay
+        // the pipeline instead of saving hand-overs (the planner on a five-stage pipeline: 0.67 s with short rings,
+        // 0.72 s with long ones).
+        bool small_rings = no_alloc;
+        const char *e = getenv("EST_WAVES_PER_CANDIDATE");
+        if (e ? (atoi(e) == 2 || atoi(e) == EST_MW_WAVES) : n_cfg * 2 <= (uint64_t)estbe::max_resident_groups(1024, EST_MW_WAVES) * 3)
+            small_rings = true;
+        int rc = build_plan(h, st, n, po, small_rings);
         if (rc != EST_OK) return rc;
     } else {
         memset(&po.plan, 0, sizeof po.plan);
