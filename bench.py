@@ -30,7 +30,7 @@ SALU_PEAK_GINST_S = 256 * 2.4            # 614.4 G scalar instructions / s: one 
 PROFILED = {
     ("W4", 65536): {"csrc_sha16": "3f0eef93ac58c684", "traffic_bytes": 1.65695e13, "valu_insts": 4.43262e12, "salu_insts": 4.74188e12,
                     "source": "profiles/est_sim_kernel_W4.md"},
-    ("W5", 65536): {"csrc_sha16": "3f0eef93ac58c684", "traffic_bytes": 3.46801e13, "valu_insts": 8.88678e12, "salu_insts": 1.04108e13,
+    ("W5", 262144): {"csrc_sha16": "3f0eef93ac58c684", "traffic_bytes": 1.38932e14, "valu_insts": 3.55471e13, "salu_insts": 4.16431e13,
                     "source": "profiles/est_sim_kernel_W5.md"},
 }
 
@@ -77,7 +77,7 @@ def main():
     ap.add_argument("--steps", type=int, default=1)
     ap.add_argument("--warmup", type=int, default=0)
     ap.add_argument("--workload", default="W4", choices=["W1", "W2", "W3", "W4", "W5"])
-    ap.add_argument("--chunk", type=int, default=65536, help="candidates per library call (a progress line is printed after each)")
+    ap.add_argument("--chunk", type=int, default=0, help="candidates per library call, 0 = the whole sweep in one call (a progress line is printed after each call)")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="configs timed on the CPU oracle (0 = skip)")
     ap.add_argument("--copy-mib", type=int, default=1024,
                     help="size of the device-to-device copy that measures the copy bandwidth before the timed region (0 = skip); "
@@ -222,12 +222,16 @@ def main():
                           "cpu_baseline": cpu}))
         return
 
+    def chunk_of(wl):
+        return min(args.chunk, wl.n_configs) if args.chunk > 0 else wl.n_configs
+
     def run_pass(wl, est_, arr, msk, cfgt, tag, acc=None):
         """The whole hot path over every candidate of wl, a chunk of candidates per library call."""
         parts = []
         S_ = wl.n_stages
-        for lo in range(0, wl.n_configs, args.chunk):
-            hi = min(lo + args.chunk, wl.n_configs)
+        chunk = chunk_of(wl)
+        for lo in range(0, wl.n_configs, chunk):
+            hi = min(lo + chunk, wl.n_configs)
             parts.append(est_.run_dev(arr, msk, cfgt[lo * S_ * 4:hi * S_ * 4], hi - lo, wl.slo_us))
             st_ = est_.stats()  # HIP-event durations of this call's kernels, on the stream they ran on
             if acc is not None:
@@ -247,8 +251,8 @@ def main():
         r = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
              "kernel": "est_sim_kernel", "avg_launch_ms": avg_s * 1e3, "algorithmic_bytes_per_launch": 8.0 * visits * per_launch,
              "limited_by": "vector and scalar instruction issue, not memory bandwidth (profiles/)"}
-        prof = PROFILED.get((wl.name, min(args.chunk, wl.n_configs)))
-        if prof is not None and per_launch == min(args.chunk, wl.n_configs):  # (one launch per library call of that many candidates)
+        prof = PROFILED.get((wl.name, chunk_of(wl)))
+        if prof is not None and per_launch == chunk_of(wl):  # (one launch per library call of that many candidates)
             if prof["csrc_sha16"] == csrc_sha16():
                 r["traffic"] = prof["traffic_bytes"]
                 for key, peak, unit in (("valu", VALU_PEAK_GINST_S, "G wave64 vector instructions/s"), ("salu", SALU_PEAK_GINST_S, "G scalar instructions/s")):
@@ -405,7 +409,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32", "data": "synthetic",
         "config": {"workload": args.workload, "n_configs": w.n_configs, "n_queries": w.n_queries, "n_stages": w.n_stages,
-                   "stage_visits_per_config": st["stage_visits"], "scratch_slots": st["n_slots"], "candidates_per_call": min(args.chunk, w.n_configs),
+                   "stage_visits_per_config": st["stage_visits"], "scratch_slots": st["n_slots"], "candidates_per_call": chunk_of(w),
                    "feasible_configs": feasible, "kernel_sources_sha16": csrc_sha16(), "input_sha256": input_sha256, "largest_sweep": largest,
                    "provisioned_regime": provisioned, "regime_mix": regime},
         "roofline": roof,
