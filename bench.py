@@ -102,7 +102,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: candidate configurations are independent, so more GPUs would each take "
-              "a slice of the configurations, but this build runs and reports a single MI355X (--gpus 1).", file=sys.stderr)
+              "a slice of the configurations, but the benchmark runs and reports a single MI355X (--gpus 1).", file=sys.stderr)
         sys.exit(2)
 
     import torch
