@@ -82,8 +82,7 @@ def test_provisioned_small_batches_with_tied_completions_match_oracle(seed):
     _compare(workloads.provisioned_case(seed, n=1500))
 
 
-@pytest.mark.parametrize("nw", [4, 2])
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed,nw", [(s, 4) for s in range(12)] + [(s, 2) for s in range(0, 12, 2)])
 def test_several_wavefronts_per_candidate_match_oracle(seed, nw, monkeypatch):
     # the candidate's operations dealt out to four (or two) wavefronts that run as a pipeline through the rings
     monkeypatch.setenv("EST_WAVES_PER_CANDIDATE", str(nw))
